@@ -1,0 +1,168 @@
+/*
+ * swarm.h -- C boundary of the MI355X hot path of co-activation-aware KV-cache offloading.
+ *
+ * The path, per decode step:
+ *     score every KV entry (token key or page summary) against the query   (Section 2.3)
+ *  -> keep the k highest-scoring entries                                   (Section 2.3)
+ *  -> record the selection as one row of a binary activation trace
+ *  -> count how often two entries are activated together, C = A^T A       (Section 5.1, Step 1)
+ *  -> turn the step's selection into per-SSD request queues               (Section 6.1)
+ *
+ * Conventions that hold for every call below:
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library never frees,
+ *    reallocates or keeps a caller pointer after the call's work has run.
+ *  - Work is enqueued on the context's HIP stream, in call order, and returns without waiting
+ *    for it; results are valid once the caller has synchronised that stream.
+ *  - Scratch memory belongs to the context and grows on demand.  Growing allocates (and
+ *    synchronises the stream); a call whose shapes are no larger than those of an earlier call
+ *    allocates nothing, so a warmed-up call sequence may be captured into a HIP graph.
+ *  - The return value is the only host-side error channel.  Nothing throws or aborts.  Bad
+ *    arguments give SWARM_EINVAL before anything is enqueued.  Bad *data* (an index outside
+ *    its range) never makes a kernel read or write out of bounds: the offending item is
+ *    skipped and a sticky flag is raised that swarm_device_status() reports.
+ *  - One context per stream; a context is not thread-safe.  bf16 is the upper half of an IEEE
+ *    binary32.  All integer arrays are int32 unless stated.
+ */
+#ifndef SWARM_H_
+#define SWARM_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct swarm_ctx swarm_ctx;
+
+typedef enum {
+    SWARM_OK = 0,
+    SWARM_EINVAL = -1,    /* argument rejected on the host; nothing was enqueued            */
+    SWARM_ENOMEM = -2,    /* scratch allocation failed                                      */
+    SWARM_EHIP = -3,      /* a HIP runtime call failed; text in swarm_last_error()          */
+    SWARM_EOVERFLOW = -4, /* a count could exceed int32                                      */
+    SWARM_EDATA = -5      /* swarm_device_status(): a kernel met an out-of-range index      */
+} swarm_status;
+
+typedef enum {
+    SWARM_KEYS_TOKEN = 0,       /* data: bf16 [H][N][d], one key per entry                   */
+    SWARM_KEYS_PAGE_MINMAX = 1  /* data: bf16 [H][N][2][d], channel-wise min then max of the
+                                   page's keys, 4*d contiguous bytes per page                */
+} swarm_key_kind;
+
+/* Key-side operand of the scoring step. */
+typedef struct {
+    int32_t kind;        /* swarm_key_kind                                                    */
+    const void* data;    /* device, 16-byte aligned                                           */
+    int32_t H;           /* KV heads                                                          */
+    int32_t N;           /* scored entries (tokens or pages) per head                         */
+    int32_t d;           /* head dimension: a multiple of 8, at most 512                      */
+    int32_t G;           /* query heads per KV head (grouped-query attention), >= 1           */
+} swarm_keys;
+
+/* flags of swarm_coact_accumulate */
+#define SWARM_CHECK_IDX 1u   /* validate range and distinctness of every selection on the device */
+
+/* bits of swarm_device_status()'s *flags */
+#define SWARM_DEV_BAD_ENTRY   1u  /* entry id outside [0,N)                      */
+#define SWARM_DEV_BAD_CLUSTER 2u  /* cluster id outside [0,Nc)                   */
+#define SWARM_DEV_BAD_SSD     4u  /* replica slot >= D, or a cluster with none   */
+#define SWARM_DEV_CAP         8u  /* a group had more distinct clusters than cap */
+#define SWARM_DEV_DUP_ENTRY   16u /* repeated entry within one selection         */
+
+/* Creates a context bound to HIP device `device` and to `hip_stream` (a hipStream_t; NULL is the
+ * default stream).  The stream stays the caller's.  */
+swarm_status swarm_create(swarm_ctx** out, int device, void* hip_stream);
+/* Frees the context and its scratch.  Synchronises the stream first. */
+swarm_status swarm_destroy(swarm_ctx* ctx);
+/* Text of the last error on this context (or of the last failed swarm_create when ctx is NULL).
+ * Valid until the next call on the context.  */
+const char* swarm_last_error(const swarm_ctx* ctx);
+/* Synchronises the stream, reads and clears the sticky device flags.  Returns SWARM_OK when no
+ * flag was set, SWARM_EDATA otherwise; *flags (nullable, host) receives the SWARM_DEV_* bits. */
+swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags);
+
+/*
+ * Score + select (Section 2.3: compute the relevance score of every KV entry against the query --
+ * "e.g. query-key inner products" -- and keep the entries with the highest scores).
+ *
+ *   token keys:      s[b][h][n] = sum_g sum_c q[b][h*G+g][c] * K[h][n][c]
+ *   page summaries:  s[b][h][n] = sum_g sum_c max(q_c * min[h][n][c], q_c * max[h][n][c])
+ *                    (channel-wise upper bound of the inner product over the page's box)
+ *   products of two bf16 values are exact in fp32; accumulation is fp32.
+ *   select: the k largest of s[b][h][0..N); equal scores are won by the lower index; -0 equals
+ *   +0; NaN ranks below every number.  The k indices come out in ascending order.
+ *
+ * q           device, bf16 [B][H*G][d], 16-byte aligned.
+ * B           decode streams scored in this call (>= 1); each gets its own selection.
+ * k           1 <= k <= N.
+ * out_idx     device, int32 [B][H][k].
+ * out_scores  device, fp32 [B][H][N], or NULL to keep the scores in the context's scratch.
+ * Errors: SWARM_EINVAL for a NULL required pointer, misaligned data/q, k outside [1,N], d not a
+ * multiple of 8 or above 512, H/N/G/B < 1.
+ */
+swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, int32_t k,
+                                int32_t* out_idx, float* out_scores);
+
+/*
+ * Co-activation accumulation (Section 5.1, Step 1: element (i,j) counts the number of times entries
+ * i and j are activated together; the diagonal is an entry's own activation count).
+ *
+ * The `rows` selections are scattered into a binary trace A (rows x N per head, kept entry-major
+ * as int8 in the context's scratch) and C[h] is updated with A^T A computed exactly in int32 by
+ * int8 matrix-core instructions:
+ *     decay_q16 == 65536 : C += A^T A
+ *     decay_q16 == 0     : C  = A^T A            (C is not read)
+ *     otherwise          : C  = floor((C * decay_q16 + 2^15) / 2^16) + A^T A   (int64 intermediate)
+ * The decayed form lets stale statistics fade when the workload drifts (the degradation of
+ * co-activation statistics is the paper's fourth challenge, Section 3.2); the mechanism itself is
+ * not in the paper.
+ *
+ * idx    device, int32 [rows][H][k]; within one (row, head) the k entries must be distinct and in
+ *        [0,N) (any order).  Out-of-range entries are skipped and flagged.
+ * rows   trace rows in this call (steps x streams since the last call), 1 <= rows <= 2^24.
+ * C      device, int32 [H][N][N] row-major, in/out, 16-byte aligned.
+ * flags  SWARM_CHECK_IDX additionally flags repeated entries (SWARM_DEV_DUP_ENTRY); a repeated
+ *        entry counts once either way, because the trace is binary.
+ * Errors: SWARM_EINVAL as above or decay_q16 > 65536; SWARM_ENOMEM if the trace (H*N*rows bytes,
+ * rows rounded up to 128) cannot be allocated.
+ */
+swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int32_t H, int32_t k,
+                                    int32_t N, int32_t* C, uint32_t decay_q16, uint32_t flags);
+
+/*
+ * Request mapping (Section 6.1: merge the activated clusters, drop what is already resident in
+ * DRAM, then fill one bucket per SSD -- items in ascending order of replication factor, an item
+ * with a single copy to its SSD, an item with several copies to the SSD whose bucket is currently
+ * the smallest).  The routed unit is a cluster, the paper's atomic retrieval unit.
+ *
+ * For each group g (KV head = g % H):
+ *   1. clusters = { e2c[head][e] : e in sel[g][0..S) } minus clusters whose bit is set in `resident`;
+ *   2. visit them in ascending (replication factor, cluster id), the replication factor being the
+ *      number of slots >= 0 in replicas[head*Nc + c][0..R);
+ *   3. send each to the candidate SSD with the smallest load, ties to the smallest SSD id;
+ *      load += weight[head*Nc + c] (1 when weight is NULL);
+ *   4. emit the buckets SSD-major, each in insertion order.
+ *
+ * sel        device, int32 [groups][S] entry ids (repeats allowed; all streams of a step merged).
+ * e2c        device, int32 [H][N] cluster of each entry, in [0,Nc).
+ * replicas   device, int32 [H*Nc][R]: distinct SSD ids in [0,D); a slot < 0 is unused.
+ * weight     device, int32 [H*Nc] or NULL.
+ * resident   device, uint32 bitmap over head*Nc + c (bit i of word i/32), or NULL.
+ * q_off      device out, int32 [groups][D+1]: bucket d of group g is q_cluster[g][q_off[g][d] .. q_off[g][d+1]).
+ * q_cluster  device out, int32 [groups][cap]; slots past q_off[g][D] are set to -1.
+ * q_load     device out, int32 [groups][D] final bucket loads.
+ * cap        row length of q_cluster; min(S, Nc) always suffices.  A group with more distinct
+ *            clusters than cap is truncated and flagged (SWARM_DEV_CAP).
+ * weight entries must be >= 0 (negative ones count as 0).
+ * Errors: SWARM_EINVAL for NULL required pointers, R < 1, R > D, D > 64, Nc > 2^20, cap < 1,
+ * S/H/N/Nc/groups < 1, or on-chip staging too large: 24 * cap + Nc / 8 + 256 bytes must fit in 64 KiB.
+ */
+swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int32_t S, int32_t H, int32_t N,
+                                const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
+                                const int32_t* weight, const uint32_t* resident,
+                                int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWARM_H_ */

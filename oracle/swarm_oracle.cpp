@@ -166,7 +166,7 @@ int oracle_coact_dense(const uint8_t* A, int64_t rows, int N, int32_t* C) {
 //     decay(c) = floor((c * decay_q16 + 2^15) / 2^16)   (round half up, Q16 multiplier),
 //     decay_q16 = 65536 keeps C (plain accumulation), 0 discards it.
 // New evidence enters undecayed.  The decay is not in the paper; it addresses the degradation of
-// stale co-activation statistics the paper describes as its fourth challenge (Section 4).
+// stale co-activation statistics the paper describes as its fourth challenge (Section 3.2).
 // idx[rows][H][k], C[H][N][N] in/out.  Returns -2 on a bad index, -3 on a repeated index in a row.
 // ---------------------------------------------------------------------------------------
 int oracle_coact_update(const int32_t* idx, int64_t rows, int H, int k, int N, int32_t* C,

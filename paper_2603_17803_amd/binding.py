@@ -1,0 +1,213 @@
+"""ctypes binding of libswarm (include/swarm.h).  Argument marshalling only.
+
+Module-level functions carry the C names and take raw device pointers; the `Swarm` class wraps
+them for torch tensors (torch supplies device memory and the stream, nothing else).  Every step
+of the path runs inside the HIP library.  If the library cannot be loaded this module raises:
+there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+from . import build as _build
+
+SWARM_OK, SWARM_EINVAL, SWARM_ENOMEM, SWARM_EHIP, SWARM_EOVERFLOW, SWARM_EDATA = 0, -1, -2, -3, -4, -5
+SWARM_KEYS_TOKEN, SWARM_KEYS_PAGE_MINMAX = 0, 1
+SWARM_CHECK_IDX = 1
+SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
+
+EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score_select",
+           "swarm_coact_accumulate", "swarm_map_requests"]
+
+
+class swarm_keys(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("data", C.c_void_p), ("H", C.c_int32), ("N", C.c_int32), ("d", C.c_int32),
+                ("G", C.c_int32)]
+
+
+class SwarmError(RuntimeError):
+    def __init__(self, fn: str, code: int, text: str = ""):
+        super().__init__(f"{fn} -> {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Loads the built library (building it first only when no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    L = C.CDLL(_build.LIB)
+    vp, i32, i64, u32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32
+    L.swarm_create.argtypes = [C.POINTER(vp), C.c_int, vp]
+    L.swarm_destroy.argtypes = [vp]
+    L.swarm_last_error.argtypes = [vp]
+    L.swarm_last_error.restype = C.c_char_p
+    L.swarm_device_status.argtypes = [vp, C.POINTER(u32)]
+    L.swarm_score_select.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, i32, vp, vp]
+    L.swarm_coact_accumulate.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, u32]
+    L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
+    for name in EXPORTS:
+        if name != "swarm_last_error":
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+# ---- raw layer: the C names, raw pointers ---------------------------------------------------
+
+def swarm_create(device: int, hip_stream: int) -> int:
+    ctx = C.c_void_p()
+    rc = load().swarm_create(C.byref(ctx), device, C.c_void_p(hip_stream))
+    if rc != SWARM_OK:
+        raise SwarmError("swarm_create", rc, load().swarm_last_error(None).decode())
+    return ctx.value
+
+
+def swarm_destroy(ctx: int) -> None:
+    load().swarm_destroy(C.c_void_p(ctx))
+
+
+def swarm_last_error(ctx: int) -> str:
+    return load().swarm_last_error(C.c_void_p(ctx)).decode()
+
+
+def swarm_device_status(ctx: int) -> Tuple[int, int]:
+    flags = C.c_uint32(0)
+    rc = load().swarm_device_status(C.c_void_p(ctx), C.byref(flags))
+    return rc, flags.value
+
+
+def swarm_score_select(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q: int, B: int, k: int,
+                       out_idx: int, out_scores: Optional[int]) -> int:
+    ks = swarm_keys(kind, data, H, N, d, G)
+    return load().swarm_score_select(C.c_void_p(ctx), C.byref(ks), C.c_void_p(q), B, k, C.c_void_p(out_idx),
+                                     C.c_void_p(out_scores))
+
+
+def swarm_coact_accumulate(ctx: int, idx: int, rows: int, H: int, k: int, N: int, Cptr: int, decay_q16: int,
+                           flags: int) -> int:
+    return load().swarm_coact_accumulate(C.c_void_p(ctx), C.c_void_p(idx), rows, H, k, N, C.c_void_p(Cptr),
+                                         decay_q16, flags)
+
+
+def swarm_map_requests(ctx: int, sel: int, groups: int, S: int, H: int, N: int, e2c: int, Nc: int, replicas: int,
+                       R: int, D: int, weight: Optional[int], resident: Optional[int], q_off: int, q_cluster: int,
+                       q_load: int, cap: int) -> int:
+    return load().swarm_map_requests(C.c_void_p(ctx), C.c_void_p(sel), groups, S, H, N, C.c_void_p(e2c), Nc,
+                                     C.c_void_p(replicas), R, D, C.c_void_p(weight), C.c_void_p(resident),
+                                     C.c_void_p(q_off), C.c_void_p(q_cluster), C.c_void_p(q_load), cap)
+
+
+# ---- tensor layer ---------------------------------------------------------------------------
+
+class Swarm:
+    """One library context on the current torch stream of `device`."""
+
+    def __init__(self, device: int = 0, stream=None):
+        import torch
+        self.torch = torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("paper_2603_17803_amd needs an MI355X; no GPU is visible")
+        self.device = torch.device("cuda", device)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self.ctx = swarm_create(device, self.stream.cuda_stream)
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            swarm_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, fn: str, rc: int):
+        if rc != SWARM_OK:
+            raise SwarmError(fn, rc, swarm_last_error(self.ctx))
+
+    def _dev(self, t, dtype=None, name="tensor"):
+        if t.device != self.device or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous tensor on {self.device}")
+        if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+            raise ValueError(f"{name} has dtype {t.dtype}, expected {dtype}")
+        return t.data_ptr()
+
+    def score_select(self, kind: str, keys, q, k: int, G: int = 1, out_idx=None, out_scores=None,
+                     want_scores: bool = False):
+        """keys: bf16 (or int16 bit patterns) [H][N][d] ('token') or [H][N][2][d] ('page');
+        q: [B][H*G][d].  Returns (idx int32 [B][H][k], scores fp32 [B][H][N] or None)."""
+        torch = self.torch
+        b16 = (torch.bfloat16, torch.int16, torch.uint16)
+        H, N, d = keys.shape[0], keys.shape[1], keys.shape[-1]
+        B = q.shape[0]
+        if tuple(q.shape) != (B, H * G, d):
+            raise ValueError(f"q has shape {tuple(q.shape)}, expected {(B, H * G, d)}")
+        want = (H, N, d) if kind == "token" else (H, N, 2, d)
+        if tuple(keys.shape) != want:
+            raise ValueError(f"keys has shape {tuple(keys.shape)}, expected {want}")
+        if out_idx is None:
+            out_idx = torch.empty((B, H, k), dtype=torch.int32, device=self.device)
+        if out_scores is None and want_scores:
+            out_scores = torch.empty((B, H, N), dtype=torch.float32, device=self.device)
+        rc = swarm_score_select(self.ctx, SWARM_KEYS_TOKEN if kind == "token" else SWARM_KEYS_PAGE_MINMAX,
+                                self._dev(keys, b16, "keys"), H, N, d, G, self._dev(q, b16, "q"), B, k,
+                                self._dev(out_idx, torch.int32, "out_idx"),
+                                None if out_scores is None else self._dev(out_scores, torch.float32, "out_scores"))
+        self._check("swarm_score_select", rc)
+        return out_idx, out_scores
+
+    def coact_accumulate(self, idx, N: int, Cm, decay_q16: int = 65536, flags: int = 0):
+        """idx int32 [rows][H][k]; Cm int32 [H][N][N] updated in place."""
+        torch = self.torch
+        rows, H, k = idx.shape
+        if tuple(Cm.shape) != (H, N, N):
+            raise ValueError(f"C has shape {tuple(Cm.shape)}, expected {(H, N, N)}")
+        rc = swarm_coact_accumulate(self.ctx, self._dev(idx, torch.int32, "idx"), rows, H, k, N,
+                                    self._dev(Cm, torch.int32, "C"), decay_q16, flags)
+        self._check("swarm_coact_accumulate", rc)
+        return Cm
+
+    def map_requests(self, sel, H: int, N: int, e2c, Nc: int, replicas, D: int, weight=None, resident=None,
+                     cap: Optional[int] = None, out=None):
+        """sel int32 [groups][S].  Returns (q_off [groups][D+1], q_cluster [groups][cap], q_load [groups][D])."""
+        torch = self.torch
+        groups, S = sel.shape
+        R = replicas.shape[1]
+        if tuple(e2c.shape) != (H, N) or tuple(replicas.shape) != (H * Nc, R):
+            raise ValueError("e2c must be [H][N] and replicas [H*Nc][R]")
+        if weight is not None and tuple(weight.shape) != (H * Nc,):
+            raise ValueError("weight must be [H*Nc]")
+        if resident is not None and resident.numel() < (H * Nc + 31) // 32:
+            raise ValueError("resident bitmap too short")
+        if cap is None:
+            cap = min(S, Nc)
+        if out is None:
+            q_off = torch.empty((groups, D + 1), dtype=torch.int32, device=self.device)
+            q_cluster = torch.empty((groups, cap), dtype=torch.int32, device=self.device)
+            q_load = torch.empty((groups, D), dtype=torch.int32, device=self.device)
+        else:
+            q_off, q_cluster, q_load = out
+        rc = swarm_map_requests(self.ctx, self._dev(sel, torch.int32, "sel"), groups, S, H, N,
+                                self._dev(e2c, torch.int32, "e2c"), Nc, self._dev(replicas, torch.int32, "replicas"),
+                                R, D, None if weight is None else self._dev(weight, torch.int32, "weight"),
+                                None if resident is None else self._dev(resident, (torch.int32, torch.uint32), "resident"),
+                                self._dev(q_off, torch.int32, "q_off"), self._dev(q_cluster, torch.int32, "q_cluster"),
+                                self._dev(q_load, torch.int32, "q_load"), cap)
+        self._check("swarm_map_requests", rc)
+        return q_off, q_cluster, q_load
+
+    def device_status(self) -> int:
+        """Synchronises, returns and clears the sticky SWARM_DEV_* flags."""
+        rc, flags = swarm_device_status(self.ctx)
+        if rc not in (SWARM_OK, SWARM_EDATA):
+            raise SwarmError("swarm_device_status", rc, swarm_last_error(self.ctx))
+        return flags

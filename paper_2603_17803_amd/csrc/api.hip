@@ -1,0 +1,163 @@
+// C-ABI entry points of libswarm: argument validation, scratch management, kernel sequencing.
+// Every step of the path runs in the HIP kernels of the sibling files; nothing here computes.
+#include <new>
+#include <string.h>
+
+#include "common.h"
+
+static char g_create_err[512] = "";
+
+swarm_status swarm_grow(swarm_ctx* ctx, void** buf, size_t* have, size_t bytes) {
+    if (*have >= bytes) return SWARM_OK;
+    SWARM_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (*buf) SWARM_HIP(ctx, hipFree(*buf));
+    *buf = nullptr;
+    *have = 0;
+    hipError_t e = hipMalloc(buf, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        snprintf(ctx->err, sizeof(ctx->err), "scratch allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+        *buf = nullptr;
+        return SWARM_ENOMEM;
+    }
+    *have = bytes;
+    return SWARM_OK;
+}
+
+extern "C" {
+
+swarm_status swarm_create(swarm_ctx** out, int device, void* hip_stream) {
+    if (!out) return SWARM_EINVAL;
+    *out = nullptr;
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || device < 0 || device >= ndev) {
+        snprintf(g_create_err, sizeof g_create_err, "no HIP device %d (count %d, %s)", device, ndev,
+                 hipGetErrorString(e));
+        (void)hipGetLastError();
+        return e != hipSuccess ? SWARM_EHIP : SWARM_EINVAL;
+    }
+    hipDeviceProp_t prop;
+    e = hipSetDevice(device);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
+    if (e != hipSuccess) {
+        snprintf(g_create_err, sizeof g_create_err, "cannot query device %d: %s", device, hipGetErrorString(e));
+        return SWARM_EHIP;
+    }
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+        snprintf(g_create_err, sizeof g_create_err, "device %d is %s; this library is built for gfx950 only", device,
+                 prop.gcnArchName);
+        return SWARM_EINVAL;
+    }
+    swarm_ctx* ctx = new (std::nothrow) swarm_ctx();
+    if (!ctx) return SWARM_ENOMEM;
+    ctx->device = device;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    e = hipMalloc(reinterpret_cast<void**>(&ctx->dev_flags), 256);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->dev_flags, 0, 256, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) {
+        snprintf(g_create_err, sizeof g_create_err, "context set-up failed: %s", hipGetErrorString(e));
+        delete ctx;
+        return SWARM_EHIP;
+    }
+    *out = ctx;
+    return SWARM_OK;
+}
+
+swarm_status swarm_destroy(swarm_ctx* ctx) {
+    if (!ctx) return SWARM_EINVAL;
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->scores) (void)hipFree(ctx->scores);
+    if (ctx->trace) (void)hipFree(ctx->trace);
+    if (ctx->dev_flags) (void)hipFree(ctx->dev_flags);
+    delete ctx;
+    return SWARM_OK;
+}
+
+const char* swarm_last_error(const swarm_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
+
+swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags) {
+    if (!ctx) return SWARM_EINVAL;
+    uint32_t host = 0;
+    SWARM_HIP(ctx, hipMemcpyAsync(&host, ctx->dev_flags, sizeof host, hipMemcpyDeviceToHost, ctx->stream));
+    SWARM_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (host) {
+        SWARM_HIP(ctx, hipMemsetAsync(ctx->dev_flags, 0, sizeof host, ctx->stream));
+        SWARM_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    if (flags) *flags = host;
+    if (host) {
+        snprintf(ctx->err, sizeof(ctx->err), "device data flags 0x%x", host);
+        return SWARM_EDATA;
+    }
+    return SWARM_OK;
+}
+
+swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, int32_t k,
+                                int32_t* out_idx, float* out_scores) {
+    if (!ctx) return SWARM_EINVAL;
+    if (!keys || !keys->data || !q || !out_idx) SWARM_REJECT(ctx, "score_select: NULL keys, data, q or out_idx");
+    if (keys->kind != SWARM_KEYS_TOKEN && keys->kind != SWARM_KEYS_PAGE_MINMAX)
+        SWARM_REJECT(ctx, "score_select: unknown key kind %d", keys->kind);
+    if (keys->H < 1 || keys->N < 1 || keys->G < 1 || B < 1)
+        SWARM_REJECT(ctx, "score_select: H=%d N=%d G=%d B=%d must all be >= 1", keys->H, keys->N, keys->G, B);
+    if (keys->d < 8 || keys->d % 8 != 0 || keys->d > 512)
+        SWARM_REJECT(ctx, "score_select: d=%d must be a multiple of 8 in [8,512]", keys->d);
+    if (k < 1 || k > keys->N) SWARM_REJECT(ctx, "score_select: k=%d outside [1,N=%d]", k, keys->N);
+    if ((reinterpret_cast<uintptr_t>(keys->data) & 15) || (reinterpret_cast<uintptr_t>(q) & 15))
+        SWARM_REJECT(ctx, "score_select: keys.data and q must be 16-byte aligned");
+    if ((int64_t)B * keys->H > (int64_t)1 << 24) SWARM_REJECT(ctx, "score_select: B*H too large");
+
+    float* scores = out_scores;
+    if (!scores) {
+        swarm_status st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->scores), &ctx->scores_bytes,
+                                     sizeof(float) * (size_t)B * keys->H * keys->N);
+        if (st != SWARM_OK) return st;
+        scores = ctx->scores;
+    }
+    swarm_status st = launch_score(ctx, keys, q, B, scores);
+    if (st != SWARM_OK) return st;
+    return launch_select(ctx, scores, (int64_t)B * keys->H, keys->N, k, out_idx);
+}
+
+swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int32_t H, int32_t k,
+                                    int32_t N, int32_t* C, uint32_t decay_q16, uint32_t flags) {
+    if (!ctx) return SWARM_EINVAL;
+    if (!idx || !C) SWARM_REJECT(ctx, "coact_accumulate: NULL idx or C");
+    if (H < 1 || N < 1 || k < 1 || k > N) SWARM_REJECT(ctx, "coact_accumulate: H=%d N=%d k=%d invalid", H, N, k);
+    if (rows < 1 || rows > ((int64_t)1 << 24)) SWARM_REJECT(ctx, "coact_accumulate: rows=%lld outside [1,2^24]", (long long)rows);
+    if (decay_q16 > 65536u) SWARM_REJECT(ctx, "coact_accumulate: decay_q16=%u above 65536", decay_q16);
+    if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "coact_accumulate: C must be 16-byte aligned");
+    if (flags & ~SWARM_CHECK_IDX) SWARM_REJECT(ctx, "coact_accumulate: unknown flags 0x%x", flags);
+
+    const int64_t Tpad = (rows + 127) / 128 * 128;   // contraction length, zero-padded to the K tile
+    const int Npad = (N + 255) / 256 * 256;          // rows of A^T, zero-padded to the C tile
+    swarm_status st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->trace), &ctx->trace_bytes,
+                                 (size_t)H * Npad * Tpad);
+    if (st != SWARM_OK) return st;
+    st = launch_trace_scatter(ctx, idx, rows, H, k, N, Npad, Tpad, flags);
+    if (st != SWARM_OK) return st;
+    return launch_coact_syrk(ctx, H, N, Npad, Tpad, C, decay_q16);
+}
+
+swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int32_t S, int32_t H, int32_t N,
+                                const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
+                                const int32_t* weight, const uint32_t* resident,
+                                int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap) {
+    if (!ctx) return SWARM_EINVAL;
+    if (!sel || !e2c || !replicas || !q_off || !q_cluster || !q_load)
+        SWARM_REJECT(ctx, "map_requests: NULL required pointer");
+    if (groups < 1 || groups > ((int64_t)1 << 30) || S < 1 || H < 1 || N < 1 || Nc < 1 || cap < 1)
+        SWARM_REJECT(ctx, "map_requests: groups=%lld S=%d H=%d N=%d Nc=%d cap=%d must all be >= 1", (long long)groups,
+                     S, H, N, Nc, cap);
+    if (R < 1 || R > D || D > 64) SWARM_REJECT(ctx, "map_requests: need 1 <= R=%d <= D=%d <= 64", R, D);
+    if (Nc > (1 << 20)) SWARM_REJECT(ctx, "map_requests: Nc=%d above 2^20", Nc);
+    const size_t lds = ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + 64) * 4;
+    if (lds > 64u * 1024u)
+        SWARM_REJECT(ctx, "map_requests: cap=%d and Nc=%d need %zu bytes of on-chip staging (limit 64 KiB)", cap, Nc, lds);
+    return launch_map(ctx, sel, groups, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load,
+                      cap);
+}
+
+}  // extern "C"

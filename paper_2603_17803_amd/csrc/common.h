@@ -1,0 +1,59 @@
+// Internal declarations shared by the translation units of libswarm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "swarm.h"
+
+struct swarm_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    char err[512] = {0};
+
+    // scratch, grown on demand
+    float* scores = nullptr;       // [B][H][N] when the caller passes no score buffer
+    size_t scores_bytes = 0;
+    int8_t* trace = nullptr;       // A^T, int8 [H][Npad][Tpad]
+    size_t trace_bytes = 0;
+    uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
+};
+
+#define SWARM_HIP(ctx, call)                                                                      \
+    do {                                                                                          \
+        hipError_t e_ = (call);                                                                   \
+        if (e_ != hipSuccess) {                                                                   \
+            snprintf((ctx)->err, sizeof((ctx)->err), "%s failed: %s (%s:%d)", #call,              \
+                     hipGetErrorString(e_), __FILE__, __LINE__);                                  \
+            return SWARM_EHIP;                                                                    \
+        }                                                                                         \
+    } while (0)
+
+#define SWARM_REJECT(ctx, ...)                                                                    \
+    do {                                                                                          \
+        snprintf((ctx)->err, sizeof((ctx)->err), __VA_ARGS__);                                    \
+        return SWARM_EINVAL;                                                                      \
+    } while (0)
+
+// Grows a scratch buffer to at least `bytes` (never shrinks).  Allocation synchronises the stream.
+swarm_status swarm_grow(swarm_ctx* ctx, void** buf, size_t* have, size_t bytes);
+
+// --- kernel launchers (each enqueues on ctx->stream and reports launch errors) ---------------
+swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores);
+swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx);
+swarm_status launch_trace_scatter(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N,
+                                  int Npad, int64_t Tpad, uint32_t flags);
+swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int64_t Tpad, int32_t* C, uint32_t decay_q16);
+swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
+                        int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
+                        const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap);
+
+static inline swarm_status swarm_check_launch(swarm_ctx* ctx, const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        snprintf(ctx->err, sizeof(ctx->err), "launch of %s failed: %s", what, hipGetErrorString(e));
+        return SWARM_EHIP;
+    }
+    return SWARM_OK;
+}

@@ -1,0 +1,107 @@
+// Selection step (Section 2.3): indices of the k highest scores of each row, equal scores won by
+// the lower index, result in ascending index order.
+//
+// Exact radix select on an order-preserving 32-bit image of the fp32 score: four 8-bit digit
+// passes (most significant first) with an LDS histogram each narrow the k-th largest key down to
+// its exact value T and the number `need` of entries equal to T that still belong to the result.
+// One ordered compaction pass then emits every index with key > T and the first `need` indices
+// with key == T; a block-wide prefix scan over contiguous per-thread chunks keeps the output in
+// index order, which makes the tie-break and the ordering deterministic.
+#include "common.h"
+
+namespace {
+
+constexpr int SEL_THREADS = 1024;
+
+// Monotone map fp32 -> uint32: larger float <=> larger key.  -0 maps to the key of +0; every
+// NaN maps to key 0, below -inf.
+__device__ __forceinline__ uint32_t order_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;   // NaN
+    if (u == 0x80000000u) u = 0u;                      // -0 -> +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void topk_select_kernel(const float* __restrict__ scores, int N, int k,
+                                                                  int32_t* __restrict__ out_idx) {
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_digit, s_above;
+    __shared__ uint32_t wave_gt[SEL_THREADS / 64], wave_eq[SEL_THREADS / 64];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* s = scores + (size_t)blockIdx.x * N;
+    int32_t* out = out_idx + (size_t)blockIdx.x * k;
+
+    uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < N; i += SEL_THREADS) {
+            const uint32_t key = order_key(s[i]);
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // lane l owns digits 4l..4l+3; find the digit whose suffix count first reaches `need`
+            const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+            const uint32_t tot = h0 + h1 + h2 + h3;
+            uint32_t incl = tot;                                  // inclusive suffix sum over lanes >= l
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t v = __shfl_down(incl, off, 64);
+                if (lane + off < 64) incl += v;
+            }
+            uint32_t above = incl - tot;                          // entries in digits of higher lanes
+            const uint32_t hh[4] = {h0, h1, h2, h3};
+#pragma unroll
+            for (int j = 3; j >= 0; --j) {
+                if (above < need && need <= above + hh[j]) { s_digit = 4 * lane + j; s_above = above; }
+                above += hh[j];
+            }
+        }
+        __syncthreads();
+        prefix |= s_digit << shift;
+        mask |= 0xffu << shift;
+        need -= s_above;
+        __syncthreads();
+    }
+    const uint32_t T = prefix;
+
+    // ordered compaction: thread t owns the contiguous chunk [t*chunk, (t+1)*chunk)
+    const int chunk = (N + SEL_THREADS - 1) / SEL_THREADS;
+    const int lo = min(tid * chunk, N), hi = min(lo + chunk, N);
+    uint32_t gt = 0, eq = 0;
+    for (int i = lo; i < hi; ++i) {
+        const uint32_t key = order_key(s[i]);
+        gt += key > T;
+        eq += key == T;
+    }
+    uint32_t gt_incl = gt, eq_incl = eq;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t a = __shfl_up(gt_incl, off, 64), b = __shfl_up(eq_incl, off, 64);
+        if (lane >= off) { gt_incl += a; eq_incl += b; }
+    }
+    if (lane == 63) { wave_gt[wave] = gt_incl; wave_eq[wave] = eq_incl; }
+    __syncthreads();
+    uint32_t gt_before = gt_incl - gt, eq_before = eq_incl - eq;
+    for (int w = 0; w < wave; ++w) { gt_before += wave_gt[w]; eq_before += wave_eq[w]; }
+
+    uint32_t pos = gt_before + min(eq_before, need);
+    uint32_t eq_seen = eq_before;
+    for (int i = lo; i < hi; ++i) {
+        const uint32_t key = order_key(s[i]);
+        if (key > T) out[pos++] = i;
+        else if (key == T) {
+            if (eq_seen < need) out[pos++] = i;
+            ++eq_seen;
+        }
+    }
+}
+
+}  // namespace
+
+swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx) {
+    hipLaunchKernelGGL(topk_select_kernel, dim3((unsigned)rows), dim3(SEL_THREADS), 0, ctx->stream, scores, N, k, out_idx);
+    return swarm_check_launch(ctx, "topk_select_kernel");
+}

@@ -1,0 +1,374 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the CPU oracle.
+
+Stages (each compared on the same seeded inputs):
+  1. scores vs oracle scores, within the floating-point tolerance below;
+  2. selection vs the oracle's selection *run on the GPU's own score buffer*: bit-exact;
+  3. co-activation counts vs the oracle's counts from the GPU's selections: bit-exact;
+  4. request queues vs the oracle's queues from the GPU's selections: bit-exact;
+  5. end to end, the GPU selection vs the oracle selection from oracle scores, tie-aware: entries
+     whose oracle score clears the k-th score by more than the tolerance must be selected, nothing
+     below the k-th score minus the tolerance may be, and where the k-th/(k+1)-th gap exceeds the
+     tolerance the two sets are identical.
+
+Score tolerance: 1e-3 relative (products of bf16 values are exact in fp32, accumulation is fp32),
+with a floor of L * 2^-24 * sum|terms| (L = accumulated terms) where the sum itself cancels.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_17803_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def sw():
+    from paper_2603_17803_amd import binding
+    s = binding.Swarm(0)
+    yield s
+    s.close()
+
+
+def dev(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).cuda()
+
+
+def score_tol(ref64, ab, terms):
+    return np.maximum(1e-3 * np.abs(ref64), terms * 2.0 ** -24 * ab)
+
+
+def check_scores(kind, K, q, G, got):
+    ref32, ref64, ab = oracle.score(kind, K, q, G=G, nthreads=8)
+    terms = K.shape[-1] * (2 if kind == "page" else 1) * G
+    tol = score_tol(ref64, ab, terms)
+    err = np.abs(got.astype(np.float64) - ref64)
+    assert (err <= tol).all(), f"max err/tol {np.max(err / np.maximum(tol, 1e-300))}"
+    return ref32, ref64, tol
+
+
+def check_tie_aware(got_idx, ref64, tol, k):
+    """Stage 5 for one row."""
+    order = np.sort(ref64)[::-1]
+    kth, nxt = order[k - 1], (order[k] if k < ref64.size else -np.inf)
+    t = tol.max()
+    sel = np.zeros(ref64.size, bool)
+    sel[got_idx] = True
+    assert sel[ref64 > kth + t].all()
+    assert (ref64[got_idx] >= kth - t).all()
+    if kth - nxt > 2 * t:
+        assert np.array_equal(np.flatnonzero(ref64 >= kth), got_idx)
+
+
+def run_score_select(sw, cfg, t0=0, t1=1, keys=None):
+    K = W.keys(cfg) if keys is None else keys
+    q = W.queries(cfg, t0, t1)
+    Kd = dev(K)
+    out = []
+    for t in range(t1 - t0):
+        idx, sc = sw.score_select(cfg.unit, Kd, dev(q[t]), cfg.k, G=cfg.G, want_scores=True)
+        torch.cuda.synchronize()
+        out.append((q[t], idx.cpu().numpy(), sc.cpu().numpy()))
+    return K, out
+
+
+CASES = [
+    W.CONFIGS["tiny"].scaled(T=3),                                           # one head, token keys, full size
+    W.CONFIGS["tiny"].scaled(N=4096 + 37, k=100, T=2),                       # ragged tail
+    W.CONFIGS["tiny"].scaled(N=50, k=50, T=1),                               # fewer entries than one tile; k = N
+    W.CONFIGS["tiny"].scaled(N=1, k=1, T=1),
+    W.CONFIGS["llama8b_32k"].scaled(T=2),                                    # page summaries, 8 heads
+    W.CONFIGS["llama8b_32k"].scaled(N=777, k=1, T=1, H=3),
+    W.CONFIGS["long_128k"].scaled(N=2048 + 5, T=1, k=256),
+    W.CONFIGS["token_stress"].scaled(N=16384, k=1024, T=1),                  # multi-chunk select
+    W.CONFIGS["drift_batch"].scaled(N=300, B=5, T=1, k=17),                  # streams x grouped query heads
+    W.CONFIGS["drift_batch"].scaled(N=2048, B=3, G=2, H=2, T=1, unit="token", page_size=1),
+    W.CONFIGS["tiny"].scaled(d=8, N=100, k=5, T=1),                          # smallest head dimension
+    W.CONFIGS["tiny"].scaled(d=24, N=100, k=5, T=1),                         # row not a power of two of chunks
+    W.CONFIGS["llama8b_32k"].scaled(d=320, N=100, k=5, T=1, H=2),            # page row longer than one wave-load
+    W.CONFIGS["tiny"].scaled(d=512, N=64, k=3, T=1),
+]
+
+
+@pytest.mark.parametrize("cfg", CASES, ids=lambda c: f"{c.name}-N{c.N}-d{c.d}-B{c.B}-G{c.G}-k{c.k}")
+def test_score_and_select_stages(sw, cfg):
+    K, steps = run_score_select(sw, cfg, 0, cfg.T)
+    for q, idx, sc in steps:
+        ref32, ref64, tol = check_scores(cfg.unit, K, q, cfg.G, sc)
+        # stage 2: exact selection on the GPU's own scores
+        assert np.array_equal(idx, oracle.select(sc, cfg.k, nthreads=8))
+        # stage 5: tie-aware end to end
+        for b in range(cfg.B):
+            for h in range(cfg.H):
+                check_tie_aware(idx[b, h], ref64[b, h], tol[b, h], cfg.k)
+        assert (np.diff(idx, axis=-1) > 0).all()
+
+
+def crafted_scores(sw, values):
+    """Builds d=8 token keys whose scores against q = ones are exactly `values` (bf16-exact)."""
+    v = np.asarray(values, np.float32)
+    K = np.full((1, v.size, 8), 0x8000, np.uint16)             # -0 everywhere: adds nothing, keeps a -0 sum
+    K[0, :, 0] = (v.view(np.uint32) >> 16).astype(np.uint16)
+    assert np.array_equal(W.bf16_to_f32(K[0, :, 0]).view(np.uint32), v.view(np.uint32))
+    q = np.full((1, 1, 8), 0x3F80, np.uint16)
+    return dev(K), dev(q)
+
+
+def test_select_ties_special_values(sw):
+    cases = [
+        (np.zeros(4096, np.float32), 5),
+        (np.array([1, 3, 2, 3, 2, 2, 0, 3], np.float32), 4),
+        (np.array([1, 3, 2, 3, 2, 2, 0, 3], np.float32), 5),
+        (np.array([-0.0, 0.0, -0.0, -1.0, 0.0], np.float32), 2),
+        (np.array([np.nan, -np.inf, 1.0, np.nan, -5.0], np.float32), 3),
+        (np.array([np.nan, -np.inf, 1.0, np.nan, -5.0], np.float32), 4),
+        (np.array([np.inf, 2.0 ** 126, -2.0 ** 126, np.inf], np.float32), 2),
+        (np.repeat(np.array([2.0, -1.0, 2.0, 0.5], np.float32), 1500), 2000),   # ties across thread chunks
+    ]
+    for vals, k in cases:
+        Kd, qd = crafted_scores(sw, vals)
+        idx, sc = sw.score_select("token", Kd, qd, k, want_scores=True)
+        sc = sc.cpu().numpy()
+        got = idx.cpu().numpy()[0, 0]
+        assert np.array_equal(sc[0, 0].view(np.uint32), vals.view(np.uint32)) or np.isnan(vals).any()
+        assert got.tolist() == oracle.select(vals[None], k)[0].tolist(), (vals[:8], k)
+
+
+def test_selection_is_deterministic(sw):
+    cfg = W.CONFIGS["llama8b_32k"].scaled(T=1)
+    _, a = run_score_select(sw, cfg)
+    _, b = run_score_select(sw, cfg)
+    assert np.array_equal(a[0][1], b[0][1]) and np.array_equal(a[0][2].view(np.uint32), b[0][2].view(np.uint32))
+
+
+# --------------------------------------------------------------------------- co-activation
+
+COACT_CASES = [
+    # rows, H, k, N
+    (3, 1, 3, 4),
+    (64, 1, 8, 128),
+    (100, 2, 16, 200),          # ragged N and rows
+    (257, 3, 32, 1000),
+    (700, 1, 64, 1300),
+    (130, 1, 128, 128),         # k = N: every entry in every row
+]
+
+
+@pytest.mark.parametrize("rows,H,k,N", COACT_CASES)
+def test_coact_counts_bit_exact(sw, rows, H, k, N):
+    sel = W.random_selections(rows, H, k, N, seed=rows + N)
+    Cd = torch.full((H, N, N), -7, dtype=torch.int32, device="cuda")
+    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=0)                       # overwrite mode ignores old C
+    ref = oracle.coact_update(sel, N, nthreads=8)
+    assert np.array_equal(Cd.cpu().numpy(), ref)
+    # accumulate a second window, then a decayed third
+    sel2 = W.random_selections(rows // 2 + 1, H, k, N, seed=99)
+    sw.coact_accumulate(dev(sel2), N, Cd, decay_q16=65536)
+    oracle.coact_update(sel2, N, ref, 65536, nthreads=8)
+    assert np.array_equal(Cd.cpu().numpy(), ref)
+    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=64881)
+    oracle.coact_update(sel, N, ref, 64881, nthreads=8)
+    assert np.array_equal(Cd.cpu().numpy(), ref)
+    assert sw.device_status() == 0
+
+
+def test_coact_decay_of_large_counts(sw):
+    N = 64
+    rng = np.random.default_rng(0)
+    C0 = rng.integers(0, 2 ** 31 - 70000, size=(1, N, N), dtype=np.int64).astype(np.int32)
+    sel = W.random_selections(5, 1, 4, N, seed=1, topic_like=False)
+    Cd = dev(C0.copy())
+    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=64881)
+    assert np.array_equal(Cd.cpu().numpy(), oracle.coact_update(sel, N, C0.copy(), 64881))
+
+
+def test_coact_bad_and_repeated_entries_are_flagged_not_fatal(sw):
+    from paper_2603_17803_amd import binding
+    N = 32
+    sel = np.array([[[1, 2, 40]], [[3, 3, 5]], [[-1, 0, 7]]], np.int32)
+    Cd = torch.zeros((1, N, N), dtype=torch.int32, device="cuda")
+    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=0, flags=binding.SWARM_CHECK_IDX)
+    flags = sw.device_status()
+    assert flags & binding.SWARM_DEV_BAD_ENTRY and flags & binding.SWARM_DEV_DUP_ENTRY
+    good = np.zeros((N, N), np.int64)
+    for row in ([1, 2], [3, 5], [0, 7]):                                    # bad entries skipped, repeats count once
+        good[np.ix_(row, row)] += 1
+    assert np.array_equal(Cd.cpu().numpy()[0], good)
+    assert sw.device_status() == 0                                          # flags are cleared by reading
+
+
+# --------------------------------------------------------------------------- request mapping
+
+def run_map(sw, sel, H, N, e2c, Nc, rep, D, weight=None, resident=None, cap=None):
+    out = sw.map_requests(dev(sel), H, N, dev(e2c), Nc, dev(rep), D, None if weight is None else dev(weight),
+                          None if resident is None else dev(resident), cap)
+    torch.cuda.synchronize()
+    got = tuple(o.cpu().numpy() for o in out)
+    ref = oracle.map_requests(sel, H, N, e2c, Nc, rep, D, weight, resident, cap, nthreads=8)
+    for g_, r_, name in zip(got, ref, ("q_off", "q_cluster", "q_load")):
+        assert np.array_equal(g_, r_), name
+    return got
+
+
+def test_map_hand_case(sw):
+    import json, os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "map_hand_case.json")))
+    e2c = np.array([g["e2c"]], np.int32)
+    rep = np.array(g["replicas"], np.int32)
+    wt = np.array(g["weight"], np.int32)
+    sel = np.array(g["sel"], np.int32)
+    off, clu, load = run_map(sw, sel, 1, g["N"], e2c, g["Nc"], rep, g["D"], wt)
+    assert off.tolist() == g["q_off"] and clu.tolist() == g["q_cluster"] and load.tolist() == g["q_load"]
+    res = np.zeros(1, np.uint32)
+    for c in g["resident_clusters"]:
+        res[0] |= np.uint32(1 << c)
+    off, clu, load = run_map(sw, sel, 1, g["N"], e2c, g["Nc"], rep, g["D"], wt, res)
+    assert off.tolist() == g["resident_q_off"] and clu.tolist() == g["resident_q_cluster"]
+
+
+MAP_CASES = [
+    # cfg, groups, S, random replicas, use weights
+    (W.CONFIGS["tiny"], 16, 64, False, True),
+    (W.CONFIGS["llama8b_32k"], 40, 128, True, True),
+    (W.CONFIGS["long_128k"], 24, 256, False, True),
+    (W.CONFIGS["token_stress"].scaled(N=8192), 6, 1024, True, False),
+    (W.CONFIGS["drift_batch"].scaled(N=512), 16, 64 * 16, False, True),      # merged streams, heavy repeats
+    (W.CONFIGS["llama8b_32k"].scaled(D=40, R=7, Nc=300, M=300), 9, 200, True, True),   # more SSDs than a DPP row
+    (W.CONFIGS["llama8b_32k"].scaled(D=3, R=3, Nc=33, M=33), 9, 77, True, False),      # Nc not a multiple of 32
+]
+
+
+@pytest.mark.parametrize("cfg,groups,S,rnd,use_w", MAP_CASES,
+                         ids=lambda v: v.name if isinstance(v, W.Config) else str(v))
+def test_map_queues_bit_exact(sw, cfg, groups, S, rnd, use_w):
+    e2c, weight, rep = W.cluster_tables(cfg, random_replicas=rnd)
+    k = min(S, cfg.N)
+    sel = W.random_selections(groups, 1, k, cfg.N, seed=S)[:, 0]
+    if S > k:
+        sel = np.concatenate([sel, sel[:, : S - k]], axis=1)
+    rng = np.random.default_rng(3)
+    resident = rng.integers(0, 2 ** 32, size=(cfg.H * cfg.Nc + 31) // 32, dtype=np.uint64).astype(np.uint32)
+    resident &= rng.integers(0, 2 ** 32, size=resident.size, dtype=np.uint64).astype(np.uint32)   # ~25 % resident
+    run_map(sw, sel, cfg.H, cfg.N, e2c, cfg.Nc, rep, cfg.D, weight if use_w else None)
+    run_map(sw, sel, cfg.H, cfg.N, e2c, cfg.Nc, rep, cfg.D, weight if use_w else None, resident)
+    assert sw.device_status() == 0
+
+
+def test_map_variable_replication_and_heavy_weights(sw):
+    rng = np.random.default_rng(5)
+    H, N, Nc, D, R = 2, 400, 50, 6, 4
+    e2c = rng.integers(0, Nc, size=(H, N)).astype(np.int32)
+    rep = np.full((H * Nc, R), -1, np.int32)
+    for c in range(H * Nc):
+        rf = int(rng.integers(1, R + 1))
+        slots = rng.permutation(R)[:rf]
+        rep[c, slots] = rng.permutation(D)[:rf]
+    sel = rng.integers(0, N, size=(12, 90)).astype(np.int32)
+    for weight in (rng.integers(0, 20, size=H * Nc).astype(np.int32),
+                   rng.integers(2 ** 24, 2 ** 26, size=H * Nc).astype(np.int32)):    # loads beyond the packed-key range
+        run_map(sw, sel, H, N, e2c, Nc, rep, D, weight)
+
+
+def test_map_identity_clusters_is_entry_level_scheduling(sw):
+    N, D, R = 4096, 8, 3
+    cfg = W.CONFIGS["long_128k"].scaled(N=N, Nc=N, M=N, H=1)
+    rng = np.random.default_rng(6)
+    rep = np.stack([rng.permutation(D)[:R] for _ in range(N)]).astype(np.int32)
+    e2c = np.arange(N, dtype=np.int32)[None]
+    sel = W.random_selections(5, 1, 256, N, seed=8)[:, 0]
+    run_map(sw, sel, 1, N, e2c, N, rep, D)
+
+
+def test_map_bad_data_is_flagged_not_fatal(sw):
+    from paper_2603_17803_amd import binding
+    e2c = np.array([[0, 1, 9, 2]], np.int32)                 # entry 2 maps to cluster 9 >= Nc
+    rep = np.array([[0, 1], [5, -1], [-1, -1]], np.int32)     # cluster 1: SSD 5 >= D; cluster 2: no replica
+    sel = np.array([[0, 1, 2, 3, 7, -3]], np.int32)
+    out = sw.map_requests(dev(sel), 1, 4, dev(e2c), 3, dev(rep), 2)
+    flags = sw.device_status()
+    assert flags == (binding.SWARM_DEV_BAD_ENTRY | binding.SWARM_DEV_BAD_CLUSTER | binding.SWARM_DEV_BAD_SSD)
+    off, clu, load = (o.cpu().numpy() for o in out)
+    assert off.tolist() == [[0, 1, 1]] and clu[0, 0] == 0 and load.tolist() == [[1, 0]]
+    # too small a cap truncates and flags
+    e2c = np.arange(8, dtype=np.int32)[None]
+    rep = np.zeros((8, 1), np.int32)
+    sw.map_requests(dev(np.arange(8, dtype=np.int32)[None]), 1, 8, dev(e2c), 8, dev(rep), 1, cap=4)
+    assert sw.device_status() == binding.SWARM_DEV_CAP
+
+
+# --------------------------------------------------------------------------- whole path
+
+def whole_path(sw, cfg, steps):
+    """Runs the path step by step through the three entry points and checks stages 1-4."""
+    K = W.keys(cfg)
+    Kd = dev(K)
+    e2c, weight, rep = W.cluster_tables(cfg)
+    e2c_d, w_d, rep_d = dev(e2c), dev(weight), dev(rep)
+    rows = steps * cfg.B
+    idx_all = torch.empty((rows, cfg.H, cfg.k), dtype=torch.int32, device="cuda")
+    qs = W.queries(cfg, 0, steps)
+    queues = []
+    for t in range(steps):
+        out_idx = idx_all[t * cfg.B:(t + 1) * cfg.B]
+        _, sc = sw.score_select(cfg.unit, Kd, dev(qs[t]), cfg.k, G=cfg.G, out_idx=out_idx, want_scores=True)
+        # one group per (step, head), the B streams merged: sel[h] = all streams' picks for head h
+        sel = out_idx.permute(1, 0, 2).reshape(cfg.H, cfg.B * cfg.k).contiguous()
+        queues.append((sel, sw.map_requests(sel, cfg.H, cfg.N, e2c_d, cfg.Nc, rep_d, cfg.D, w_d)))
+        if t < 2:
+            check_scores(cfg.unit, K, qs[t], cfg.G, sc.cpu().numpy())
+            assert np.array_equal(out_idx.cpu().numpy(), oracle.select(sc.cpu().numpy(), cfg.k, nthreads=8))
+    Cd = torch.zeros((cfg.H, cfg.N, cfg.N), dtype=torch.int32, device="cuda")
+    sw.coact_accumulate(idx_all, cfg.N, Cd, decay_q16=0)
+    torch.cuda.synchronize()
+    idx_np = idx_all.cpu().numpy()
+    assert np.array_equal(Cd.cpu().numpy(), oracle.coact_update(idx_np, cfg.N, nthreads=8))
+    for sel, out in queues:
+        ref = oracle.map_requests(sel.cpu().numpy(), cfg.H, cfg.N, e2c, cfg.Nc, rep, cfg.D, weight, nthreads=8)
+        for g_, r_ in zip(out, ref):
+            assert np.array_equal(g_.cpu().numpy(), r_)
+    assert sw.device_status() == 0
+    return idx_np, Cd
+
+
+def test_whole_path_tiny_full_size(sw):
+    cfg = W.CONFIGS["tiny"]
+    idx, Cd = whole_path(sw, cfg, cfg.T)
+    c = Cd.cpu().numpy()[0]
+    counts = np.bincount(idx.ravel(), minlength=cfg.N)
+    assert np.array_equal(c, c.T) and np.array_equal(np.diag(c), counts)
+    assert np.array_equal(c.sum(1), cfg.k * counts) and c.sum() == cfg.T * cfg.k ** 2
+
+
+def test_whole_path_pages_scaled(sw):
+    whole_path(sw, W.CONFIGS["llama8b_32k"].scaled(N=1024, T=48), 48)
+
+
+def test_whole_path_batched_grouped_scaled(sw):
+    whole_path(sw, W.CONFIGS["drift_batch"].scaled(N=512, B=4, T=6, k=32), 6)
+
+
+def test_host_side_argument_errors(sw):
+    from paper_2603_17803_amd import binding
+    cfg = W.CONFIGS["tiny"].scaled(N=64, k=8, T=1)
+    Kd = dev(W.keys(cfg))
+    qd = dev(W.queries(cfg, 0, 1)[0])
+    with pytest.raises(binding.SwarmError) as e:
+        sw.score_select("token", Kd, qd, 65)
+    assert e.value.code == binding.SWARM_EINVAL
+    with pytest.raises(binding.SwarmError):
+        sw.score_select("token", Kd, qd, 0)
+    Cd = torch.zeros((1, 64, 64), dtype=torch.int32, device="cuda")
+    sel = dev(W.random_selections(2, 1, 8, 64, seed=1))
+    with pytest.raises(binding.SwarmError):
+        sw.coact_accumulate(sel, 64, Cd, decay_q16=65537)
+    e2c = dev(np.zeros((1, 64), np.int32))
+    with pytest.raises(binding.SwarmError):
+        sw.map_requests(sel[:, 0], 1, 64, e2c, 1, dev(np.zeros((1, 3), np.int32)), 2)      # R > D
+    assert sw.device_status() == 0
