@@ -91,10 +91,11 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_select_kernel(const float* _
     uint32_t eq_seen = eq_before;
     for (int i = lo; i < hi; ++i) {
         const uint32_t key = order_key(s[i]);
-        if (key > T) out[pos++] = i;
-        else if (key == T) {
-            if (eq_seen < need) out[pos++] = i;
-            ++eq_seen;
+        const bool take = key > T || (key == T && eq_seen < need);
+        eq_seen += key == T;
+        if (take) {
+            if (pos < (uint32_t)k) out[pos] = i;      // pos < k always holds; the guard keeps a logic slip in bounds
+            ++pos;
         }
     }
 }

@@ -137,8 +137,9 @@ def test_select_ties_special_values(sw):
         idx, sc = sw.score_select("token", Kd, qd, k, want_scores=True)
         sc = sc.cpu().numpy()
         got = idx.cpu().numpy()[0, 0]
-        assert np.array_equal(sc[0, 0].view(np.uint32), vals.view(np.uint32)) or np.isnan(vals).any()
+        assert np.array_equal(sc[0, 0], vals, equal_nan=True)          # numerically equal (a -0 may come back as +0)
         assert got.tolist() == oracle.select(vals[None], k)[0].tolist(), (vals[:8], k)
+        assert got.tolist() == oracle.select(sc[0], k)[0].tolist()
 
 
 def test_selection_is_deterministic(sw):
