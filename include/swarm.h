@@ -162,6 +162,22 @@ swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t grou
                                 const int32_t* weight, const uint32_t* resident,
                                 int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap);
 
+/*
+ * Replay of a recorded call sequence.  The per-step work of the path is a handful of short kernels,
+ * so a long step-sequential run is bounded by launch cost unless it is recorded once and replayed.
+ * Between swarm_capture_begin and swarm_capture_end every entry point above records its kernels
+ * into a HIP graph instead of running them (the context's stream must not be the NULL stream, and
+ * the recorded calls must not need to grow scratch: run the same sequence once beforehand).
+ * swarm_graph_launch enqueues one replay on the context's stream; pointers and shapes are those
+ * of the recorded calls, so the caller keeps those buffers alive and refreshes their contents.
+ * swarm_device_status must not be called while recording.
+ */
+typedef struct swarm_graph swarm_graph;
+swarm_status swarm_capture_begin(swarm_ctx* ctx);
+swarm_status swarm_capture_end(swarm_ctx* ctx, swarm_graph** out);
+swarm_status swarm_graph_launch(swarm_ctx* ctx, swarm_graph* graph);
+swarm_status swarm_graph_destroy(swarm_graph* graph);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,8 @@ SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
 
 EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score_select",
-           "swarm_coact_accumulate", "swarm_map_requests"]
+           "swarm_coact_accumulate", "swarm_map_requests", "swarm_capture_begin", "swarm_capture_end",
+           "swarm_graph_launch", "swarm_graph_destroy"]
 
 
 class swarm_keys(C.Structure):
@@ -53,6 +54,10 @@ def load() -> C.CDLL:
     L.swarm_score_select.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, i32, vp, vp]
     L.swarm_coact_accumulate.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, u32]
     L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
+    L.swarm_capture_begin.argtypes = [vp]
+    L.swarm_capture_end.argtypes = [vp, C.POINTER(vp)]
+    L.swarm_graph_launch.argtypes = [vp, vp]
+    L.swarm_graph_destroy.argtypes = [vp]
     for name in EXPORTS:
         if name != "swarm_last_error":
             getattr(L, name).restype = C.c_int
@@ -103,6 +108,24 @@ def swarm_map_requests(ctx: int, sel: int, groups: int, S: int, H: int, N: int, 
     return load().swarm_map_requests(C.c_void_p(ctx), C.c_void_p(sel), groups, S, H, N, C.c_void_p(e2c), Nc,
                                      C.c_void_p(replicas), R, D, C.c_void_p(weight), C.c_void_p(resident),
                                      C.c_void_p(q_off), C.c_void_p(q_cluster), C.c_void_p(q_load), cap)
+
+
+def swarm_capture_begin(ctx: int) -> int:
+    return load().swarm_capture_begin(C.c_void_p(ctx))
+
+
+def swarm_capture_end(ctx: int) -> Tuple[int, Optional[int]]:
+    g = C.c_void_p()
+    rc = load().swarm_capture_end(C.c_void_p(ctx), C.byref(g))
+    return rc, g.value
+
+
+def swarm_graph_launch(ctx: int, graph: int) -> int:
+    return load().swarm_graph_launch(C.c_void_p(ctx), C.c_void_p(graph))
+
+
+def swarm_graph_destroy(graph: int) -> int:
+    return load().swarm_graph_destroy(C.c_void_p(graph))
 
 
 # ---- tensor layer ---------------------------------------------------------------------------
@@ -204,6 +227,17 @@ class Swarm:
                                 self._dev(q_load, torch.int32, "q_load"), cap)
         self._check("swarm_map_requests", rc)
         return q_off, q_cluster, q_load
+
+    def capture_begin(self):
+        self._check("swarm_capture_begin", swarm_capture_begin(self.ctx))
+
+    def capture_end(self) -> int:
+        rc, g = swarm_capture_end(self.ctx)
+        self._check("swarm_capture_end", rc)
+        return g
+
+    def graph_launch(self, graph: int):
+        self._check("swarm_graph_launch", swarm_graph_launch(self.ctx, graph))
 
     def device_status(self) -> int:
         """Synchronises, returns and clears the sticky SWARM_DEV_* flags."""

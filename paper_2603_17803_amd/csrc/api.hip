@@ -9,6 +9,10 @@ static char g_create_err[512] = "";
 
 swarm_status swarm_grow(swarm_ctx* ctx, void** buf, size_t* have, size_t bytes) {
     if (*have >= bytes) return SWARM_OK;
+    if (ctx->capturing) {
+        snprintf(ctx->err, sizeof(ctx->err), "scratch must grow to %zu bytes while recording; run the sequence once first", bytes);
+        return SWARM_EINVAL;
+    }
     SWARM_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (*buf) SWARM_HIP(ctx, hipFree(*buf));
     *buf = nullptr;
@@ -79,6 +83,7 @@ const char* swarm_last_error(const swarm_ctx* ctx) { return ctx ? ctx->err : g_c
 
 swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags) {
     if (!ctx) return SWARM_EINVAL;
+    if (ctx->capturing) SWARM_REJECT(ctx, "device_status: not while recording");
     uint32_t host = 0;
     SWARM_HIP(ctx, hipMemcpyAsync(&host, ctx->dev_flags, sizeof host, hipMemcpyDeviceToHost, ctx->stream));
     SWARM_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -158,6 +163,52 @@ swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t grou
         SWARM_REJECT(ctx, "map_requests: cap=%d and Nc=%d need %zu bytes of on-chip staging (limit 64 KiB)", cap, Nc, lds);
     return launch_map(ctx, sel, groups, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load,
                       cap);
+}
+
+swarm_status swarm_capture_begin(swarm_ctx* ctx) {
+    if (!ctx) return SWARM_EINVAL;
+    if (ctx->capturing) SWARM_REJECT(ctx, "capture_begin: already recording");
+    if (!ctx->stream) SWARM_REJECT(ctx, "capture_begin: the NULL stream cannot be recorded");
+    SWARM_HIP(ctx, hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal));
+    ctx->capturing = true;
+    return SWARM_OK;
+}
+
+swarm_status swarm_capture_end(swarm_ctx* ctx, swarm_graph** out) {
+    if (!ctx || !out) return SWARM_EINVAL;
+    *out = nullptr;
+    if (!ctx->capturing) SWARM_REJECT(ctx, "capture_end: not recording");
+    ctx->capturing = false;
+    hipGraph_t graph = nullptr;
+    SWARM_HIP(ctx, hipStreamEndCapture(ctx->stream, &graph));
+    hipGraphExec_t exec = nullptr;
+    hipError_t e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        snprintf(ctx->err, sizeof(ctx->err), "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+        return SWARM_EHIP;
+    }
+    swarm_graph* g = new (std::nothrow) swarm_graph();
+    if (!g) { (void)hipGraphExecDestroy(exec); (void)hipGraphDestroy(graph); return SWARM_ENOMEM; }
+    g->graph = graph;
+    g->exec = exec;
+    *out = g;
+    return SWARM_OK;
+}
+
+swarm_status swarm_graph_launch(swarm_ctx* ctx, swarm_graph* graph) {
+    if (!ctx || !graph) return SWARM_EINVAL;
+    if (ctx->capturing) SWARM_REJECT(ctx, "graph_launch: not while recording");
+    SWARM_HIP(ctx, hipGraphLaunch(graph->exec, ctx->stream));
+    return SWARM_OK;
+}
+
+swarm_status swarm_graph_destroy(swarm_graph* graph) {
+    if (!graph) return SWARM_EINVAL;
+    if (graph->exec) (void)hipGraphExecDestroy(graph->exec);
+    if (graph->graph) (void)hipGraphDestroy(graph->graph);
+    delete graph;
+    return SWARM_OK;
 }
 
 }  // extern "C"

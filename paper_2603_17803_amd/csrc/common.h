@@ -7,6 +7,11 @@
 
 #include "swarm.h"
 
+struct swarm_graph {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+
 struct swarm_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
@@ -18,6 +23,7 @@ struct swarm_ctx {
     int8_t* trace = nullptr;       // A^T, int8 [H][Npad][Tpad]
     size_t trace_bytes = 0;
     uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
+    bool capturing = false;
 };
 
 #define SWARM_HIP(ctx, call)                                                                      \
