@@ -159,7 +159,7 @@ def main():
         "config": {"workload": cfg.name, "H": H, "pages_per_head": N, "decode_steps": T, "k": k, "clusters": cfg.Nc,
                    "ssds": cfg.D, "replicas": cfg.R, "rotating_key_buffers": len(layers),
                    "graph_replay": not args.no_graph},
-        "roofline": {"kernel": "score_kernel+topk_select_kernel (one decode step)", "bound": "hbm",
+        "roofline": {"kernel": "score_select_kernel (fused score + top-k of one decode step)", "bound": "hbm",
                      "achieved": round(sel_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(sel_gbs / HBM_PEAK_GBS, 4), "traffic": None,
                      "bytes_per_launch": sweep_bytes, "us_per_launch": round(sel_us, 3)},

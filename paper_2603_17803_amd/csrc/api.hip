@@ -57,8 +57,11 @@ swarm_status swarm_create(swarm_ctx** out, int device, void* hip_stream) {
     if (!ctx) return SWARM_ENOMEM;
     ctx->device = device;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
-    e = hipMalloc(reinterpret_cast<void**>(&ctx->dev_flags), 256);
-    if (e == hipSuccess) e = hipMemsetAsync(ctx->dev_flags, 0, 256, ctx->stream);
+    // one allocation: the flag word, then the arrival counters of the fused kernel (H * streams <= 65535 * 4)
+    const size_t small_bytes = 256 + sizeof(uint32_t) * 65536 * SWARM_FUSED_MAX_STREAMS;
+    e = hipMalloc(reinterpret_cast<void**>(&ctx->dev_flags), small_bytes);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->dev_flags, 0, small_bytes, ctx->stream);
+    if (e == hipSuccess) ctx->done = ctx->dev_flags + 64;
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) {
         snprintf(g_create_err, sizeof g_create_err, "context set-up failed: %s", hipGetErrorString(e));
@@ -112,6 +115,7 @@ swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const vo
     if (k < 1 || k > keys->N) SWARM_REJECT(ctx, "score_select: k=%d outside [1,N=%d]", k, keys->N);
     if ((reinterpret_cast<uintptr_t>(keys->data) & 15) || (reinterpret_cast<uintptr_t>(q) & 15))
         SWARM_REJECT(ctx, "score_select: keys.data and q must be 16-byte aligned");
+    if (out_scores && (reinterpret_cast<uintptr_t>(out_scores) & 3)) SWARM_REJECT(ctx, "score_select: out_scores misaligned");
     if ((int64_t)B * keys->H > (int64_t)1 << 24) SWARM_REJECT(ctx, "score_select: B*H too large");
 
     float* scores = out_scores;
@@ -121,6 +125,7 @@ swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const vo
         if (st != SWARM_OK) return st;
         scores = ctx->scores;
     }
+    if (score_select_can_fuse(keys, B)) return launch_score_select_fused(ctx, keys, q, B, k, scores, out_idx);
     swarm_status st = launch_score(ctx, keys, q, B, scores);
     if (st != SWARM_OK) return st;
     return launch_select(ctx, scores, (int64_t)B * keys->H, keys->N, k, out_idx);

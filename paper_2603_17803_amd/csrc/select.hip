@@ -1,29 +1,29 @@
-// Selection step (Section 2.3): indices of the k highest scores of each row, equal scores won by
-// the lower index, result in ascending index order.
+// Selection step (Section 2.3) as a stand-alone kernel: one 1024-thread block per score row.
 //
-// Exact radix select on an order-preserving 32-bit image of the fp32 score: four 8-bit digit
-// passes (most significant first) with an LDS histogram each narrow the k-th largest key down to
-// its exact value T and the number `need` of entries equal to T that still belong to the result.
-// One ordered compaction pass then emits every index with key > T and the first `need` indices
-// with key == T; a block-wide prefix scan over contiguous per-thread chunks keeps the output in
-// index order, which makes the tie-break and the ordering deterministic.
+// Rows of up to 65536 scores are held in registers and selected by selcore::block_select (value
+// binning + exact refinement, see select_core.h).  Longer rows use the streaming kernel below: an
+// exact radix select that re-reads the row from memory for each of its four 8-bit digit passes.
 #include "common.h"
+#include "select_core.h"
 
 namespace {
 
-constexpr int SEL_THREADS = 1024;
+using selcore::order_key;
 
-// Monotone map fp32 -> uint32: larger float <=> larger key.  -0 maps to the key of +0; every
-// NaN maps to key 0, below -inf.
-__device__ __forceinline__ uint32_t order_key(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;   // NaN
-    if (u == 0x80000000u) u = 0u;                      // -0 -> +0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+template <int IPT>
+__global__ __launch_bounds__(selcore::NT) void topk_select_kernel(const float* __restrict__ scores, int N, int k,
+                                                                  int32_t* __restrict__ out_idx) {
+    __shared__ selcore::Smem sm;
+    uint32_t key[IPT];
+    selcore::load_keys<IPT>(scores + (size_t)blockIdx.x * N, N, key);
+    selcore::block_select<IPT>(key, N, k, out_idx + (size_t)blockIdx.x * k, sm);
 }
 
-__global__ __launch_bounds__(SEL_THREADS) void topk_select_kernel(const float* __restrict__ scores, int N, int k,
-                                                                  int32_t* __restrict__ out_idx) {
+constexpr int SEL_THREADS = 1024;
+
+// Streaming fallback for rows longer than 65536 entries.
+__global__ __launch_bounds__(SEL_THREADS) void topk_select_stream_kernel(const float* __restrict__ scores, int N, int k,
+                                                                         int32_t* __restrict__ out_idx) {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_digit, s_above;
     __shared__ uint32_t wave_gt[SEL_THREADS / 64], wave_eq[SEL_THREADS / 64];
@@ -103,6 +103,13 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_select_kernel(const float* _
 }  // namespace
 
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx) {
-    hipLaunchKernelGGL(topk_select_kernel, dim3((unsigned)rows), dim3(SEL_THREADS), 0, ctx->stream, scores, N, k, out_idx);
+    const dim3 grid((unsigned)rows), block(selcore::NT);
+    hipStream_t st = ctx->stream;
+    if (N <= 4 * selcore::NT) hipLaunchKernelGGL(topk_select_kernel<4>, grid, block, 0, st, scores, N, k, out_idx);
+    else if (N <= 8 * selcore::NT) hipLaunchKernelGGL(topk_select_kernel<8>, grid, block, 0, st, scores, N, k, out_idx);
+    else if (N <= 16 * selcore::NT) hipLaunchKernelGGL(topk_select_kernel<16>, grid, block, 0, st, scores, N, k, out_idx);
+    else if (N <= 32 * selcore::NT) hipLaunchKernelGGL(topk_select_kernel<32>, grid, block, 0, st, scores, N, k, out_idx);
+    else if (N <= 64 * selcore::NT) hipLaunchKernelGGL(topk_select_kernel<64>, grid, block, 0, st, scores, N, k, out_idx);
+    else hipLaunchKernelGGL(topk_select_stream_kernel, grid, block, 0, st, scores, N, k, out_idx);
     return swarm_check_launch(ctx, "topk_select_kernel");
 }

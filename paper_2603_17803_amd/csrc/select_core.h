@@ -1,0 +1,233 @@
+// Block-level exact top-k selection on register-resident scores (device code, gfx950).
+//
+// Selection step (Section 2.3): the k highest scores of a row, equal scores won by the lower
+// index, result in ascending index order.
+//
+// A block of 1024 threads holds the row as IPT consecutive scores per thread.  Scores are mapped
+// to order-preserving 32-bit keys.  One pass bins every score *linearly in value* between the
+// row's minimum and maximum into 2048 LDS counters (float subtraction, scaling and truncation are
+// all monotone, so bin order agrees with score order); a scan finds the bin b* that holds the k-th
+// largest score.  Bins above b* are selected outright; inside b* (a handful of scores for any
+// smooth distribution) the exact threshold key T and the number of entries equal to T that still
+// belong to the result are found by ranking the candidates against each other, or -- when b*
+// holds more candidates than the ranking buffer, e.g. under massive ties -- by an exact 4 x 8-bit
+// radix select restricted to b*.  A final ordered compaction (block prefix scan over the
+// contiguous per-thread chunks) writes the indices in ascending order, which also makes the
+// lowest-index tie-break deterministic.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace selcore {
+
+constexpr int NT = 1024;        // threads per selecting block
+constexpr int NW = NT / 64;     // waves
+constexpr int NB = 2048;        // value bins
+constexpr int CMAX = 1024;      // candidates ranked pairwise
+
+struct Smem {
+    uint32_t hist[NB];
+    uint32_t cand[CMAX];
+    uint32_t wave_a[NW], wave_b[NW];
+    float wave_hi[NW], wave_lo[NW];
+    uint32_t cand_count, bstar, above, thr_key, thr_need;
+    uint32_t digit, digit_above;
+};
+
+// Monotone map fp32 -> uint32: larger float <=> larger key.  -0 maps to the key of +0; every
+// NaN maps to key 0, below -inf.
+__device__ __forceinline__ uint32_t order_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;
+    if (u == 0x80000000u) u = 0u;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Value used for binning only: finite, and monotone in the key (NaN and -inf share the bottom).
+__device__ __forceinline__ float bin_value(uint32_t key) {
+    const uint32_t bits = (key & 0x80000000u) ? (key & 0x7fffffffu) : ~key;
+    float v = __uint_as_float(bits);
+    if (key == 0u) v = -3.0e38f;
+    v = fminf(fmaxf(v, -3.0e38f), 3.0e38f);
+    return v * 0.25f;                                   // keeps hi - v finite
+}
+
+__device__ __forceinline__ int bin_of(uint32_t key, float hi, float scale) {
+    const float x = (hi - bin_value(key)) * scale;      // >= 0, non-increasing in the score
+    return (int)fminf(x, (float)(NB - 1));
+}
+
+// Exclusive block scan of two counters at once; returns totals through *ta, *tb when non-null.
+__device__ __forceinline__ void block_excl_scan2(uint32_t a, uint32_t b, uint32_t& ea, uint32_t& eb, Smem& sm,
+                                                 int lane, int wave) {
+    uint32_t ia = a, ib = b;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t xa = __shfl_up(ia, off, 64), xb = __shfl_up(ib, off, 64);
+        if (lane >= off) { ia += xa; ib += xb; }
+    }
+    if (lane == 63) { sm.wave_a[wave] = ia; sm.wave_b[wave] = ib; }
+    __syncthreads();
+    ea = ia - a;
+    eb = ib - b;
+    for (int w = 0; w < wave; ++w) { ea += sm.wave_a[w]; eb += sm.wave_b[w]; }
+}
+
+// key[e] is the key of index tid*IPT + e; slots at or beyond N must hold key 0.
+// All NT threads of the block must call this.  out receives k ascending indices.
+template <int IPT>
+__device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, int k, int32_t* __restrict__ out,
+                                             Smem& sm) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int base = tid * IPT;
+
+    // row extrema of the binning value
+    float hi = -3.0e38f, lo = 3.0e38f;
+#pragma unroll
+    for (int e = 0; e < IPT; ++e) {
+        if (base + e < N) {
+            const float v = bin_value(key[e]);
+            hi = fmaxf(hi, v);
+            lo = fminf(lo, v);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+        lo = fminf(lo, __shfl_xor(lo, off, 64));
+    }
+    if (lane == 0) { sm.wave_hi[wave] = hi; sm.wave_lo[wave] = lo; }
+    sm.hist[tid] = 0;
+    sm.hist[tid + NT] = 0;
+    if (tid == 0) { sm.cand_count = 0; sm.thr_key = 0; sm.thr_need = 0xffffffffu; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { hi = fmaxf(hi, sm.wave_hi[w]); lo = fminf(lo, sm.wave_lo[w]); }
+    const float range = hi - lo;
+    const float scale = range > 0.f ? fminf((float)NB / range, 1.0e30f) : 0.f;
+
+    // value histogram
+#pragma unroll
+    for (int e = 0; e < IPT; ++e) atomicAdd(&sm.hist[bin_of(key[e], hi, scale)], 1u);
+    __syncthreads();
+
+    // bin b* holding the k-th largest: cumulative count from bin 0 (highest scores) first reaches k
+    {
+        const uint32_t h0 = sm.hist[2 * tid], h1 = sm.hist[2 * tid + 1];
+        uint32_t before, unused;
+        block_excl_scan2(h0 + h1, 0u, before, unused, sm, lane, wave);
+        if (before < (uint32_t)k && (uint32_t)k <= before + h0) { sm.bstar = 2 * tid; sm.above = before; }
+        else if (before + h0 < (uint32_t)k && (uint32_t)k <= before + h0 + h1) { sm.bstar = 2 * tid + 1; sm.above = before + h0; }
+    }
+    __syncthreads();
+    const int bstar = (int)sm.bstar;
+    const uint32_t need = (uint32_t)k - sm.above;       // entries of bin b* that belong to the result
+    const uint32_t c = sm.hist[bstar];
+
+    if (need < c) {
+        if (c <= (uint32_t)CMAX) {
+            // rank the candidates of b* against each other
+#pragma unroll
+            for (int e = 0; e < IPT; ++e)
+                if (bin_of(key[e], hi, scale) == bstar) sm.cand[atomicAdd(&sm.cand_count, 1u)] = key[e];
+            __syncthreads();
+            if ((uint32_t)tid < c) {
+                const uint32_t mine = sm.cand[tid];
+                uint32_t gt = 0, eq = 0;
+                for (uint32_t j = 0; j < c; ++j) {
+                    const uint32_t other = sm.cand[j];
+                    gt += other > mine;
+                    eq += other == mine;
+                }
+                if (gt < need && need <= gt + eq) { sm.thr_key = mine; sm.thr_need = need - gt; }
+            }
+            __syncthreads();
+        } else {
+            // exact radix select restricted to bin b* (hist[0..256) reused as digit counters)
+            uint32_t prefix = 0, mask = 0, rem = need;
+            for (int shift = 24; shift >= 0; shift -= 8) {
+                __syncthreads();
+                if (tid < 256) sm.hist[tid] = 0;
+                __syncthreads();
+#pragma unroll
+                for (int e = 0; e < IPT; ++e)
+                    if (bin_of(key[e], hi, scale) == bstar && (key[e] & mask) == prefix)
+                        atomicAdd(&sm.hist[(key[e] >> shift) & 255u], 1u);
+                __syncthreads();
+                if (wave == 0) {
+                    const uint32_t h0 = sm.hist[4 * lane], h1 = sm.hist[4 * lane + 1], h2 = sm.hist[4 * lane + 2],
+                                   h3 = sm.hist[4 * lane + 3];
+                    const uint32_t tot = h0 + h1 + h2 + h3;
+                    uint32_t incl = tot;
+#pragma unroll
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const uint32_t v = __shfl_down(incl, off, 64);
+                        if (lane + off < 64) incl += v;
+                    }
+                    uint32_t above = incl - tot;
+                    const uint32_t hh[4] = {h0, h1, h2, h3};
+#pragma unroll
+                    for (int j = 3; j >= 0; --j) {
+                        if (above < rem && rem <= above + hh[j]) { sm.digit = 4 * lane + j; sm.digit_above = above; }
+                        above += hh[j];
+                    }
+                }
+                __syncthreads();
+                prefix |= sm.digit << shift;
+                mask |= 0xffu << shift;
+                rem -= sm.digit_above;
+            }
+            __syncthreads();
+            if (tid == 0) { sm.thr_key = prefix; sm.thr_need = rem; }
+            __syncthreads();
+        }
+    }
+    const uint32_t T = sm.thr_key, need_eq = sm.thr_need;   // need == c: T = 0, every candidate is taken
+
+    // ordered compaction
+    uint32_t gt = 0, eq = 0;
+#pragma unroll
+    for (int e = 0; e < IPT; ++e) {
+        const int b = bin_of(key[e], hi, scale);
+        gt += (b < bstar) || (b == bstar && key[e] > T);
+        eq += (b == bstar && key[e] == T);
+    }
+    uint32_t gt_before, eq_before;
+    block_excl_scan2(gt, eq, gt_before, eq_before, sm, lane, wave);
+    uint32_t pos = gt_before + min(eq_before, need_eq);
+    uint32_t eq_seen = eq_before;
+#pragma unroll
+    for (int e = 0; e < IPT; ++e) {
+        const int b = bin_of(key[e], hi, scale);
+        const bool is_eq = (b == bstar && key[e] == T);
+        const bool take = (b < bstar) || (b == bstar && key[e] > T) || (is_eq && eq_seen < need_eq);
+        eq_seen += is_eq;
+        if (take) {
+            if (pos < (uint32_t)k) out[pos] = base + e;     // pos < k always holds; the guard keeps a slip in bounds
+            ++pos;
+        }
+    }
+}
+
+// Loads IPT consecutive scores of a row into keys (slots beyond N get key 0).
+template <int IPT>
+__device__ __forceinline__ void load_keys(const float* __restrict__ row, int N, uint32_t (&key)[IPT]) {
+    const int base = threadIdx.x * IPT;
+    if (((reinterpret_cast<uintptr_t>(row) & 15) == 0) && base + IPT <= N) {
+        const float4* p = reinterpret_cast<const float4*>(row + base);
+#pragma unroll
+        for (int e = 0; e < IPT / 4; ++e) {
+            const float4 v = p[e];
+            key[4 * e] = order_key(v.x);
+            key[4 * e + 1] = order_key(v.y);
+            key[4 * e + 2] = order_key(v.z);
+            key[4 * e + 3] = order_key(v.w);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < IPT; ++e) key[e] = (base + e < N) ? order_key(row[base + e]) : 0u;
+    }
+}
+
+}  // namespace selcore
