@@ -104,6 +104,12 @@ swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const vo
                                 int32_t* out_idx, float* out_scores);
 
 /*
+ * The scoring half of swarm_score_select on its own (Section 2.3, relevance scores): same formulas,
+ * same arguments, no selection.  out_scores: device, fp32 [B][H][N], required.
+ */
+swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, float* out_scores);
+
+/*
  * Co-activation accumulation (Section 5.1, Step 1: element (i,j) counts the number of times entries
  * i and j are activated together; the diagonal is an entry's own activation count).
  *

@@ -18,7 +18,7 @@ SWARM_KEYS_TOKEN, SWARM_KEYS_PAGE_MINMAX = 0, 1
 SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
 
-EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score_select",
+EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score", "swarm_score_select",
            "swarm_coact_accumulate", "swarm_map_requests", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
 
@@ -52,6 +52,7 @@ def load() -> C.CDLL:
     L.swarm_last_error.restype = C.c_char_p
     L.swarm_device_status.argtypes = [vp, C.POINTER(u32)]
     L.swarm_score_select.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, i32, vp, vp]
+    L.swarm_score.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, vp]
     L.swarm_coact_accumulate.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, u32]
     L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_capture_begin.argtypes = [vp]
@@ -94,6 +95,11 @@ def swarm_score_select(ctx: int, kind: int, data: int, H: int, N: int, d: int, G
     ks = swarm_keys(kind, data, H, N, d, G)
     return load().swarm_score_select(C.c_void_p(ctx), C.byref(ks), C.c_void_p(q), B, k, C.c_void_p(out_idx),
                                      C.c_void_p(out_scores))
+
+
+def swarm_score(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q: int, B: int, out_scores: int) -> int:
+    ks = swarm_keys(kind, data, H, N, d, G)
+    return load().swarm_score(C.c_void_p(ctx), C.byref(ks), C.c_void_p(q), B, C.c_void_p(out_scores))
 
 
 def swarm_coact_accumulate(ctx: int, idx: int, rows: int, H: int, k: int, N: int, Cptr: int, decay_q16: int,
@@ -187,6 +193,22 @@ class Swarm:
                                 None if out_scores is None else self._dev(out_scores, torch.float32, "out_scores"))
         self._check("swarm_score_select", rc)
         return out_idx, out_scores
+
+    def score(self, kind: str, keys, q, G: int = 1, out_scores=None):
+        """Scores only: returns fp32 [B][H][N]."""
+        torch = self.torch
+        b16 = (torch.bfloat16, torch.int16, torch.uint16)
+        H, N, d = keys.shape[0], keys.shape[1], keys.shape[-1]
+        B = q.shape[0]
+        if tuple(q.shape) != (B, H * G, d):
+            raise ValueError(f"q has shape {tuple(q.shape)}, expected {(B, H * G, d)}")
+        if out_scores is None:
+            out_scores = torch.empty((B, H, N), dtype=torch.float32, device=self.device)
+        rc = swarm_score(self.ctx, SWARM_KEYS_TOKEN if kind == "token" else SWARM_KEYS_PAGE_MINMAX,
+                         self._dev(keys, b16, "keys"), H, N, d, G, self._dev(q, b16, "q"), B,
+                         self._dev(out_scores, torch.float32, "out_scores"))
+        self._check("swarm_score", rc)
+        return out_scores
 
     def coact_accumulate(self, idx, N: int, Cm, decay_q16: int = 65536, flags: int = 0):
         """idx int32 [rows][H][k]; Cm int32 [H][N][N] updated in place."""

@@ -57,11 +57,8 @@ swarm_status swarm_create(swarm_ctx** out, int device, void* hip_stream) {
     if (!ctx) return SWARM_ENOMEM;
     ctx->device = device;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
-    // one allocation: the flag word, then the arrival counters of the fused kernel (H * streams <= 65535 * 4)
-    const size_t small_bytes = 256 + sizeof(uint32_t) * 65536 * SWARM_FUSED_MAX_STREAMS;
-    e = hipMalloc(reinterpret_cast<void**>(&ctx->dev_flags), small_bytes);
-    if (e == hipSuccess) e = hipMemsetAsync(ctx->dev_flags, 0, small_bytes, ctx->stream);
-    if (e == hipSuccess) ctx->done = ctx->dev_flags + 64;
+    e = hipMalloc(reinterpret_cast<void**>(&ctx->dev_flags), 256);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->dev_flags, 0, 256, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) {
         snprintf(g_create_err, sizeof g_create_err, "context set-up failed: %s", hipGetErrorString(e));
@@ -102,31 +99,45 @@ swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags) {
     return SWARM_OK;
 }
 
+static swarm_status check_score_args(swarm_ctx* ctx, const char* fn, const swarm_keys* keys, const void* q, int32_t B) {
+    if (!keys || !keys->data || !q) SWARM_REJECT(ctx, "%s: NULL keys, data or q", fn);
+    if (keys->kind != SWARM_KEYS_TOKEN && keys->kind != SWARM_KEYS_PAGE_MINMAX)
+        SWARM_REJECT(ctx, "%s: unknown key kind %d", fn, keys->kind);
+    if (keys->H < 1 || keys->N < 1 || keys->G < 1 || B < 1)
+        SWARM_REJECT(ctx, "%s: H=%d N=%d G=%d B=%d must all be >= 1", fn, keys->H, keys->N, keys->G, B);
+    if (keys->d < 8 || keys->d % 8 != 0 || keys->d > 512)
+        SWARM_REJECT(ctx, "%s: d=%d must be a multiple of 8 in [8,512]", fn, keys->d);
+    if ((reinterpret_cast<uintptr_t>(keys->data) & 15) || (reinterpret_cast<uintptr_t>(q) & 15))
+        SWARM_REJECT(ctx, "%s: keys.data and q must be 16-byte aligned", fn);
+    if ((int64_t)B * keys->H > (int64_t)1 << 24) SWARM_REJECT(ctx, "%s: B*H too large", fn);
+    return SWARM_OK;
+}
+
+swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, float* out_scores) {
+    if (!ctx) return SWARM_EINVAL;
+    swarm_status st = check_score_args(ctx, "score", keys, q, B);
+    if (st != SWARM_OK) return st;
+    if (!out_scores || (reinterpret_cast<uintptr_t>(out_scores) & 3)) SWARM_REJECT(ctx, "score: NULL or misaligned out_scores");
+    return launch_score(ctx, keys, q, B, out_scores);
+}
+
 swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, int32_t k,
                                 int32_t* out_idx, float* out_scores) {
     if (!ctx) return SWARM_EINVAL;
-    if (!keys || !keys->data || !q || !out_idx) SWARM_REJECT(ctx, "score_select: NULL keys, data, q or out_idx");
-    if (keys->kind != SWARM_KEYS_TOKEN && keys->kind != SWARM_KEYS_PAGE_MINMAX)
-        SWARM_REJECT(ctx, "score_select: unknown key kind %d", keys->kind);
-    if (keys->H < 1 || keys->N < 1 || keys->G < 1 || B < 1)
-        SWARM_REJECT(ctx, "score_select: H=%d N=%d G=%d B=%d must all be >= 1", keys->H, keys->N, keys->G, B);
-    if (keys->d < 8 || keys->d % 8 != 0 || keys->d > 512)
-        SWARM_REJECT(ctx, "score_select: d=%d must be a multiple of 8 in [8,512]", keys->d);
+    swarm_status st = check_score_args(ctx, "score_select", keys, q, B);
+    if (st != SWARM_OK) return st;
+    if (!out_idx) SWARM_REJECT(ctx, "score_select: NULL out_idx");
     if (k < 1 || k > keys->N) SWARM_REJECT(ctx, "score_select: k=%d outside [1,N=%d]", k, keys->N);
-    if ((reinterpret_cast<uintptr_t>(keys->data) & 15) || (reinterpret_cast<uintptr_t>(q) & 15))
-        SWARM_REJECT(ctx, "score_select: keys.data and q must be 16-byte aligned");
     if (out_scores && (reinterpret_cast<uintptr_t>(out_scores) & 3)) SWARM_REJECT(ctx, "score_select: out_scores misaligned");
-    if ((int64_t)B * keys->H > (int64_t)1 << 24) SWARM_REJECT(ctx, "score_select: B*H too large");
 
     float* scores = out_scores;
     if (!scores) {
-        swarm_status st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->scores), &ctx->scores_bytes,
-                                     sizeof(float) * (size_t)B * keys->H * keys->N);
+        st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->scores), &ctx->scores_bytes,
+                        sizeof(float) * (size_t)B * keys->H * keys->N);
         if (st != SWARM_OK) return st;
         scores = ctx->scores;
     }
-    if (score_select_can_fuse(keys, B)) return launch_score_select_fused(ctx, keys, q, B, k, scores, out_idx);
-    swarm_status st = launch_score(ctx, keys, q, B, scores);
+    st = launch_score(ctx, keys, q, B, scores);
     if (st != SWARM_OK) return st;
     return launch_select(ctx, scores, (int64_t)B * keys->H, keys->N, k, out_idx);
 }

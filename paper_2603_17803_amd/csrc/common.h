@@ -23,7 +23,6 @@ struct swarm_ctx {
     int8_t* trace = nullptr;       // A^T, int8 [H][Npad][Tpad]
     size_t trace_bytes = 0;
     uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
-    uint32_t* done = nullptr;      // per (stream, head) arrival counters of the fused score+select kernel (zero between launches)
     bool capturing = false;
 };
 
@@ -48,11 +47,6 @@ swarm_status swarm_grow(swarm_ctx* ctx, void** buf, size_t* have, size_t bytes);
 
 // --- kernel launchers (each enqueues on ctx->stream and reports launch errors) ---------------
 swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores);
-// Fused path: one launch scores and selects.  Usable when score_select_can_fuse() holds.
-constexpr int SWARM_FUSED_MAX_STREAMS = 4;
-bool score_select_can_fuse(const swarm_keys* keys, int B);
-swarm_status launch_score_select_fused(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, int k,
-                                       float* scores, int32_t* out_idx);
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx);
 swarm_status launch_trace_scatter(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N,
                                   int Npad, int64_t Tpad, uint32_t flags);

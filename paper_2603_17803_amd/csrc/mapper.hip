@@ -4,42 +4,21 @@
 //
 // One wavefront per group.  The merge is an LDS bitmap (atomic-or per selected entry), compacted
 // in ascending cluster id.  The greedy assignment is an inherently sequential chain over the
-// distinct clusters; each link is a wave-level argmin: lane d holds bucket d's load, candidate
-// lanes compete with (load, lane) packed in one word and a DPP min-reduction picks the winner.
+// distinct clusters, so the kernel is built around the length of one link: the per-item data
+// (candidate-SSD mask, weight) is staged 64 items at a time in registers, one item per lane, and
+// handed to the chain through v_readlane; lane d carries bucket d's load packed as
+// (load << 6 | d), so one DPP min-reduction over the candidate lanes yields the least-loaded
+// replica with ties to the lower SSD id, and only the compare-and-add of the winner stays on the
+// dependent path.  Bucket positions are computed afterwards, in parallel, from the winners.
 #include "common.h"
+#include "wave_ops.h"
 
 namespace {
 
+using waveops::low_lanes_min;
+using waveops::wave_excl_scan;
+
 constexpr uint32_t INF32 = 0xffffffffu;
-
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_min(uint32_t v) {
-    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
-    return min(v, o);
-}
-
-// Minimum over the first 2^STEPS lanes (valid in every one of them); other lanes hold INF32.
-template <int STEPS>
-__device__ __forceinline__ uint32_t low_lanes_min(uint32_t v) {
-    v = dpp_min<0xB1>(v);                       // quad_perm [1,0,3,2]
-    v = dpp_min<0x4E>(v);                       // quad_perm [2,3,0,1]
-    if (STEPS >= 3) v = dpp_min<0x141>(v);      // row_half_mirror
-    if (STEPS >= 4) v = dpp_min<0x140>(v);      // row_mirror
-    if (STEPS >= 5) v = min(v, (uint32_t)__shfl_xor((int)v, 16, 64));
-    if (STEPS >= 6) v = min(v, (uint32_t)__shfl_xor((int)v, 32, 64));
-    return v;
-}
-
-__device__ __forceinline__ uint32_t wave_excl_scan(uint32_t v, int lane, uint32_t* total) {
-    uint32_t incl = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off, 64);
-        if (lane >= off) incl += o;
-    }
-    *total = __shfl(incl, 63, 64);
-    return incl - v;
-}
 
 struct MapArgs {
     const int32_t* sel; int S; int H; int N; const int32_t* e2c; int Nc; const int32_t* replicas; int R; int D;
@@ -47,28 +26,80 @@ struct MapArgs {
     uint32_t* dev_flags;
 };
 
-// The greedy chain.  PACKED: bucket loads stay below 2^26, so (load << 6 | lane) fits one word and
-// a single min-reduction yields the least-loaded candidate with ties to the lower SSD id.
-template <int STEPS, bool PACKED>
-__device__ __forceinline__ void greedy_chain(int m, int lane, const uint32_t* order, const uint32_t* mask_lo,
-                                             const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign,
-                                             uint32_t& load, uint32_t& cnt) {
-    for (int it = 0; it < m; ++it) {
+// Chain over items [0, m) in visiting order.  keybase = (load << 6) | lane.  On return assign[i]
+// holds (ssd << 24) | position-in-bucket for every routed item and INF32 for unroutable ones;
+// cnt is the bucket length of SSD `lane`.
+//
+// Items are staged 32 at a time, one per lane (lanes 0..31), and handed to the dependent chain by
+// v_readlane.  Per item the chain is: candidate select, DPP min over the SSD lanes, compare, add.
+// The SSD lane that wins item j sets bit j of its `won` word; bucket positions come from those
+// words afterwards, off the chain.
+template <int STEPS>
+__device__ __forceinline__ void greedy_chain_packed(uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
+                                                    const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign,
+                                                    uint32_t& keybase, uint32_t& cnt, int D) {
+    const uint32_t lane5 = (uint32_t)lane & 31u;
+    for (uint32_t base = 0; base < m; base += 32) {
+        const uint32_t n = min(32u, m - base);
+        uint32_t it = 0, mlo = 0, mhi = 0, w6 = 0;
+        if ((uint32_t)lane < n) {
+            it = order[base + lane];
+            mlo = mask_lo[it];
+            mhi = mask_hi[it];
+            w6 = (mlo | mhi) ? (wgt[it] << 6) : 0u;         // an unroutable item adds no load
+        }
+        uint32_t won = 0;
+        // Slots past n hold an empty mask: every lane then "wins" with weight 0, which changes nothing,
+        // so the unrolled groups of 8 need no per-item bound.
+        for (uint32_t q = 0; q < n; q += 8) {
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                const uint32_t j = q + u;
+                const uint32_t s_lo = (uint32_t)__builtin_amdgcn_readlane((int)mlo, (int)j);
+                const uint32_t s_w6 = (uint32_t)__builtin_amdgcn_readlane((int)w6, (int)j);
+                uint32_t bits = s_lo;
+                if (STEPS > 5) {
+                    const uint32_t s_hi = (uint32_t)__builtin_amdgcn_readlane((int)mhi, (int)j);
+                    bits = lane >= 32 ? s_hi : s_lo;
+                }
+                const uint32_t not_cand = ((bits >> lane5) & 1u) - 1u;      // 0 for a candidate SSD lane, all ones otherwise
+                const uint32_t bumped = keybase + s_w6;                     // off the dependent path
+                const uint32_t key = keybase | not_cand;
+                const uint32_t best = low_lanes_min<STEPS>(key);
+                const bool i_win = key == best;                  // the winning SSD lane (every lane for an empty mask)
+                keybase = i_win ? bumped : keybase;
+                won |= i_win ? (1u << j) : 0u;
+            }
+        }
+        // bucket positions of this chunk's items, in item order
+        const bool routable = (mlo | mhi) != 0u;
+        const uint32_t valid = (uint32_t)__ballot(routable);      // lanes >= 32 stage nothing, so this is a 32-bit item mask
+        uint32_t my_assign = INF32;
+        for (int dsk = 0; dsk < D; ++dsk) {
+            const uint32_t w_d = (uint32_t)__builtin_amdgcn_readlane((int)won, dsk);
+            const uint32_t c_d = (uint32_t)__builtin_amdgcn_readlane((int)cnt, dsk);
+            if (routable && lane < 32 && ((w_d >> lane) & 1u))
+                my_assign = ((uint32_t)dsk << 24) | (c_d + (uint32_t)__popc(w_d & ((1u << lane) - 1u) & valid));
+        }
+        if ((uint32_t)lane < n) assign[it] = my_assign;
+        cnt += __popc(won & valid);
+    }
+}
+
+// Fallback for bucket loads that may exceed 2^26: loads are compared in full, ties resolved by ballot.
+template <int STEPS>
+__device__ __forceinline__ void greedy_chain_wide(uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
+                                                  const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign,
+                                                  uint32_t& load, uint32_t& cnt) {
+    for (uint32_t it = 0; it < m; ++it) {
         const uint32_t i = order[it];
         const uint64_t mask = ((uint64_t)mask_hi[i] << 32) | mask_lo[i];
         if (mask == 0) { if (lane == 0) assign[i] = INF32; continue; }
         const bool cand = (mask >> lane) & 1ull;
-        int winner;
-        if (PACKED) {
-            const uint32_t key = cand ? ((load << 6) | (uint32_t)lane) : INF32;
-            winner = (int)(low_lanes_min<STEPS>(key) & 63u);
-            winner = __builtin_amdgcn_readfirstlane(winner);
-        } else {
-            const uint32_t key = cand ? load : INF32;
-            const uint32_t best = low_lanes_min<STEPS>(key);
-            const uint64_t tie = __ballot(cand && key == __builtin_amdgcn_readfirstlane((int)best));
-            winner = __ffsll((unsigned long long)tie) - 1;
-        }
+        const uint32_t key = cand ? load : INF32;
+        const uint32_t best = low_lanes_min<STEPS>(key);
+        const uint64_t tie = __ballot(cand && key == (uint32_t)__builtin_amdgcn_readfirstlane((int)best));
+        const int winner = __ffsll((unsigned long long)tie) - 1;
         if (lane == winner) {
             assign[i] = ((uint32_t)winner << 24) | cnt;
             load += wgt[i];
@@ -77,8 +108,54 @@ __device__ __forceinline__ void greedy_chain(int m, int lane, const uint32_t* or
     }
 }
 
-__global__ __launch_bounds__(64) void map_requests_kernel(MapArgs a) {
-    extern __shared__ uint32_t smem[];
+constexpr int MAP_THREADS = 256;
+
+// Copies n words from global memory to LDS with batches of independent loads (all loads of a batch
+// are in flight together, so a small table costs one memory round trip).  16-byte loads when the
+// source allows it.
+__device__ __forceinline__ void stage_words(int32_t* __restrict__ dst, const int32_t* __restrict__ src, int n, int tid) {
+    constexpr int BATCH = 8;
+    if (((reinterpret_cast<uintptr_t>(src) & 15) == 0) && (n & 3) == 0) {
+        const int n4 = n >> 2;
+        const int4* s4 = reinterpret_cast<const int4*>(src);
+        int4* d4 = reinterpret_cast<int4*>(dst);
+        for (int base = 0; base < n4; base += BATCH * MAP_THREADS) {
+            int4 v[BATCH];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int i = base + u * MAP_THREADS + tid;
+                v[u] = (i < n4) ? s4[i] : make_int4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int i = base + u * MAP_THREADS + tid;
+                if (i < n4) d4[i] = v[u];
+            }
+        }
+    } else {
+        for (int base = 0; base < n; base += BATCH * MAP_THREADS) {
+            int32_t v[BATCH];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int i = base + u * MAP_THREADS + tid;
+                v[u] = (i < n) ? src[i] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int i = base + u * MAP_THREADS + tid;
+                if (i < n) dst[i] = v[u];
+            }
+        }
+    }
+}
+
+// Block of 4 waves.  All waves cooperate on staging and on the merge; wave 0 alone runs the
+// compaction, the chain and the emission (the chain is a single-wave algorithm).  When the head's
+// lookup tables are small they are staged in LDS by one burst of independent loads issued at kernel
+// start, so that the whole kernel pays one memory round trip instead of three dependent ones
+// (selection -> cluster of entry -> replica row).
+__global__ __launch_bounds__(MAP_THREADS) void map_requests_kernel(MapArgs a, int stage_e2c, int stage_tab) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
     const int nwords = (a.Nc + 31) / 32;
     uint32_t* bitmap = smem;
     uint32_t* list = bitmap + nwords;
@@ -88,30 +165,60 @@ __global__ __launch_bounds__(64) void map_requests_kernel(MapArgs a) {
     uint32_t* order = wgt + a.cap;
     uint32_t* assign = order + a.cap;
     uint32_t* off = assign + a.cap;                 // 64 words
+    int32_t* s_e2c = reinterpret_cast<int32_t*>(smem + ((off + 64 - smem + 3) & ~3));   // N words when staged (16-byte aligned)
+    int32_t* s_rep = s_e2c + (stage_e2c ? ((a.N + 3) & ~3) : 0);                // Nc*R words when staged
+    int32_t* s_wgt = s_rep + (stage_tab ? ((a.Nc * a.R + 3) & ~3) : 0);         // Nc words when staged
 
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t g = blockIdx.x;
     const int h = (int)(g % a.H);
+    const int64_t cbase = (int64_t)h * a.Nc;
     uint32_t flags = 0;
 
-    for (int w = lane; w < nwords; w += 64) bitmap[w] = 0;
+    // burst of independent loads: the selection into registers, the tables into LDS
+    const int32_t* sel = a.sel + g * a.S;
+    const int32_t* e2c = a.e2c + (size_t)h * a.N;
+    constexpr int SEL_REGS = 4;
+    int32_t my_sel[SEL_REGS];
+#pragma unroll
+    for (int r = 0; r < SEL_REGS; ++r) {
+        const int s0 = tid + r * MAP_THREADS;
+        my_sel[r] = (s0 < a.S) ? sel[s0] : -1;
+    }
+    if (stage_tab) {
+        stage_words(s_rep, a.replicas + cbase * a.R, a.Nc * a.R, tid);
+        if (a.weight) stage_words(s_wgt, a.weight + cbase, a.Nc, tid);
+        else for (int i = tid; i < a.Nc; i += MAP_THREADS) s_wgt[i] = 1;
+    }
+    if (stage_e2c) stage_words(s_e2c, e2c, a.N, tid);
+    for (int w = tid; w < nwords; w += MAP_THREADS) bitmap[w] = 0;
     __syncthreads();
 
     // merge: one bit per activated, non-resident cluster
-    const int32_t* sel = a.sel + g * a.S;
-    const int32_t* e2c = a.e2c + (size_t)h * a.N;
-    for (int s = lane; s < a.S; s += 64) {
-        const int32_t e = sel[s];
+    for (int s0 = tid, r = 0; s0 < a.S; s0 += MAP_THREADS, ++r) {
+        int32_t e;
+        if (r < SEL_REGS) {
+            e = my_sel[0];
+#pragma unroll
+            for (int rr = 1; rr < SEL_REGS; ++rr) e = (r == rr) ? my_sel[rr] : e;
+        } else {
+            e = sel[s0];
+        }
         if (e < 0 || e >= a.N) { flags |= SWARM_DEV_BAD_ENTRY; continue; }
-        const int32_t c = e2c[e];
+        const int32_t c = stage_e2c ? s_e2c[e] : e2c[e];
         if (c < 0 || c >= a.Nc) { flags |= SWARM_DEV_BAD_CLUSTER; continue; }
         if (a.resident) {
-            const int64_t gc = (int64_t)h * a.Nc + c;
+            const int64_t gc = cbase + c;
             if ((a.resident[gc >> 5] >> (gc & 31)) & 1u) continue;
         }
         atomicOr(&bitmap[c >> 5], 1u << (c & 31));
     }
     __syncthreads();
+
+    if (wave != 0) {                                 // the rest is single-wave work
+        if (flags) atomicOr(a.dev_flags, flags);
+        return;
+    }
 
     // compaction in ascending cluster id
     uint32_t m = 0;
@@ -119,7 +226,7 @@ __global__ __launch_bounds__(64) void map_requests_kernel(MapArgs a) {
         const int w = w0 + lane;
         uint32_t bits = (w < nwords) ? bitmap[w] : 0u;
         uint32_t total;
-        uint32_t pos = m + wave_excl_scan(__popc(bits), lane, &total);
+        uint32_t pos = m + wave_excl_scan(__popc(bits), &total);
         while (bits) {
             const int bit = __ffs(bits) - 1;
             bits &= bits - 1;
@@ -129,46 +236,49 @@ __global__ __launch_bounds__(64) void map_requests_kernel(MapArgs a) {
         m += total;
     }
     if (m > (uint32_t)a.cap) { flags |= SWARM_DEV_CAP; m = a.cap; }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
     // per item: candidate SSD mask, weight, replication factor
-    const int64_t cbase = (int64_t)h * a.Nc;
     uint32_t rf_min = INF32, rf_max = 0, wsum = 0;
     for (uint32_t i = lane; i < m; i += 64) {
-        const int64_t gc = cbase + list[i];
+        const uint32_t c = list[i];
+        const int64_t gc = cbase + c;
         uint64_t mask = 0;
         for (int r = 0; r < a.R; ++r) {
-            const int32_t dsk = a.replicas[gc * a.R + r];
+            const int32_t dsk = stage_tab ? s_rep[c * a.R + r] : a.replicas[gc * a.R + r];
             if (dsk >= a.D) flags |= SWARM_DEV_BAD_SSD;
             else if (dsk >= 0) mask |= 1ull << dsk;
         }
         if (mask == 0) flags |= SWARM_DEV_BAD_SSD;
         mask_lo[i] = (uint32_t)mask;
         mask_hi[i] = (uint32_t)(mask >> 32);
-        const uint32_t wv = a.weight ? (uint32_t)max(a.weight[gc], 0) : 1u;
+        const int32_t wraw = stage_tab ? s_wgt[c] : (a.weight ? a.weight[gc] : 1);
+        const uint32_t wv = (uint32_t)max(wraw, 0);
         wgt[i] = wv;
-        wsum += min(wv, 1u << 26);
+        wsum = min(wsum + min(wv, 1u << 26), 1u << 26);       // saturating: only "below 2^26" matters
         const uint32_t rf = __popcll(mask);
         order[i] = rf;                               // replication factor for now
+        assign[i] = INF32;
         rf_min = min(rf_min, rf);
         rf_max = max(rf_max, rf);
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        rf_min = min(rf_min, (uint32_t)__shfl_xor((int)rf_min, o, 64));
-        rf_max = max(rf_max, (uint32_t)__shfl_xor((int)rf_max, o, 64));
-        const uint32_t ws = (uint32_t)__shfl_xor((int)wsum, o, 64);
-        wsum = (wsum + ws > (1u << 26)) ? (1u << 26) : wsum + ws;
+    rf_min = waveops::wave_min_u32(rf_min);
+    rf_max = ~waveops::wave_min_u32(~rf_max);
+    {
+        const bool any_big = __ballot(wsum >= (1u << 26)) != 0ull;
+        uint32_t total;
+        (void)wave_excl_scan(min(wsum, (1u << 26) - 1u), &total);     // <= 64 * (2^26 - 1): no wrap
+        wsum = any_big ? (1u << 26) : total;
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
     // visiting order: stable by replication factor (identity when all factors agree)
     if (m > 0 && rf_min == rf_max) {
         for (uint32_t i = lane; i < m; i += 64) order[i] = i;
     } else if (m > 0) {
-        uint32_t* rfv = assign;                      // assign is free until the chain runs
+        uint32_t* rfv = assign;                      // assign is rewritten below, before the chain runs
         for (uint32_t i = lane; i < m; i += 64) rfv[i] = order[i];
-        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         uint32_t outpos = 0;
         for (uint32_t v = rf_min; v <= rf_max; ++v) {
             for (uint32_t i0 = 0; i0 < m; i0 += 64) {
@@ -179,27 +289,30 @@ __global__ __launch_bounds__(64) void map_requests_kernel(MapArgs a) {
                 outpos += __popcll(b);
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        for (uint32_t i = lane; i < m; i += 64) assign[i] = INF32;
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
     // greedy least-loaded assignment
     uint32_t load = 0, cnt = 0;
-    const bool packed = wsum < (1u << 26);
     const int D = a.D;
-    if (packed) {
-        if (D <= 4) greedy_chain<2, true>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
-        else if (D <= 8) greedy_chain<3, true>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
-        else if (D <= 16) greedy_chain<4, true>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
-        else greedy_chain<6, true>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
+    if (wsum < (1u << 26)) {
+        uint32_t keybase = (uint32_t)lane;
+        if (D <= 4) greedy_chain_packed<2>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
+        else if (D <= 8) greedy_chain_packed<3>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
+        else if (D <= 16) greedy_chain_packed<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
+        else greedy_chain_packed<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
+        load = keybase >> 6;
     } else {
-        if (D <= 16) greedy_chain<4, false>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
-        else greedy_chain<6, false>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
+        if (D <= 16) greedy_chain_wide<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
+        else greedy_chain_wide<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
     // emit buckets SSD-major, insertion order inside a bucket
     uint32_t total;
-    const uint32_t my_off = wave_excl_scan(lane < D ? cnt : 0u, lane, &total);
+    const uint32_t my_off = wave_excl_scan(lane < D ? cnt : 0u, &total);
     off[lane] = my_off;
     int32_t* q_off = a.q_off + g * (D + 1);
     if (lane < D) {
@@ -207,7 +320,7 @@ __global__ __launch_bounds__(64) void map_requests_kernel(MapArgs a) {
         a.q_load[g * D + lane] = (int32_t)load;
     }
     if (lane == 0) q_off[D] = (int32_t)total;
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
     int32_t* qc = a.q_cluster + g * a.cap;
     for (uint32_t i = lane; i < m; i += 64) {
         const uint32_t as = assign[i];
@@ -220,11 +333,20 @@ __global__ __launch_bounds__(64) void map_requests_kernel(MapArgs a) {
 
 }  // namespace
 
+size_t map_lds_base_bytes(int Nc, int cap) { return ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + 64) * 4; }
+
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                         const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap) {
     MapArgs a{sel, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags};
-    const size_t lds = ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + 64) * 4;
-    hipLaunchKernelGGL(map_requests_kernel, dim3((unsigned)groups), dim3(64), lds, ctx->stream, a);
+    size_t lds = map_lds_base_bytes(Nc, cap);
+    const size_t budget = 64u * 1024u;
+    int stage_tab = 0, stage_e2c = 0;
+    const size_t tab_bytes = ((size_t)Nc * R + 3) / 4 * 16 + ((size_t)Nc + 3) / 4 * 16, e2c_bytes = ((size_t)N + 3) / 4 * 16;
+    lds = (lds + 15) / 16 * 16;
+    if (lds + tab_bytes <= budget) { stage_tab = 1; lds += tab_bytes; }
+    if (lds + e2c_bytes <= budget) { stage_e2c = 1; lds += e2c_bytes; }
+    hipLaunchKernelGGL(map_requests_kernel, dim3((unsigned)groups), dim3(MAP_THREADS), lds, ctx->stream, a, stage_e2c,
+                       stage_tab);
     return swarm_check_launch(ctx, "map_requests_kernel");
 }

@@ -10,7 +10,6 @@
 // group of LPR lanes covers one row, a wave covers 64/LPR consecutive rows per load (1 KiB
 // contiguous), and the per-row partial sums are combined with a lane butterfly.
 #include "common.h"
-#include "select_core.h"
 
 namespace {
 
@@ -122,107 +121,9 @@ __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ ro
 }
 
 
-// Fused score + select for d = 128 rows.  The grid is (blocks per head, H, B); each 1024-thread
-// block scores 16 * UNROLL * 64/LPR consecutive rows and writes them to the score buffer.  The
-// block that finishes a (stream, head) row last -- elected through a device-scope counter --
-// re-reads that row's scores and runs the selection, so one launch covers the whole step.
-template <int LPR, int UNROLL, bool PAGE, int IPT>
-__global__ __launch_bounds__(1024) void score_select_kernel(const u32x4* __restrict__ rows, const uint16_t* __restrict__ q,
-                                                            float* __restrict__ scores, int N, int H, int G, int k,
-                                                            int32_t* __restrict__ out_idx, uint32_t* __restrict__ done) {
-    constexpr int CH = LPR;                      // 16-byte chunks per row (d = 128)
-    constexpr int d = PAGE ? CH * 4 : CH * 8;
-    constexpr int RPW = 64 / LPR;
-    constexpr int RPB = 16 * UNROLL * RPW;
-    __shared__ selcore::Smem sm;
-    __shared__ uint32_t s_last;
-
-    const int h = blockIdx.y, b = blockIdx.z;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int sub = lane % LPR, grp = lane / LPR;
-    const size_t bh = (size_t)b * H + h;
-
-    float w[8];
-    load_weights<PAGE>(q + bh * (size_t)G * d, G, d, sub, w);
-
-    const int row0 = blockIdx.x * RPB + wave * UNROLL * RPW + grp;
-    const u32x4* base = rows + (size_t)h * N * CH;
-    u32x4 x[UNROLL];
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        const int n = row0 + u * RPW;
-        if (n < N) x[u] = __builtin_nontemporal_load(base + (size_t)n * CH + sub);
-        else x[u] = u32x4{0, 0, 0, 0};
-    }
-    float p[UNROLL];
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u) p[u] = dot8(x[u], w);
-#pragma unroll
-    for (int off = LPR / 2; off >= 1; off >>= 1) {
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) p[u] += __shfl_xor(p[u], off, 64);
-    }
-    float* srow = scores + bh * N;
-    {
-        float v = p[0];
-#pragma unroll
-        for (int u = 1; u < UNROLL; ++u) v = (sub == u) ? p[u] : v;
-        const int n = row0 + sub * RPW;
-        if (sub < UNROLL && n < N) srow[n] = v;
-    }
-
-    // publish this block's scores, then elect the last block of the row
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(&done[bh], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        const bool last = prev == gridDim.x - 1;
-        if (last) __hip_atomic_store(&done[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
-        s_last = last;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-
-    uint32_t key[IPT];
-    selcore::load_keys<IPT>(srow, N, key);
-    selcore::block_select<IPT>(key, N, k, out_idx + bh * k, sm);
-}
-
-template <int LPR, int UNROLL, bool PAGE, int IPT>
-void launch_fused_one(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int k,
-                      int32_t* out_idx, uint32_t* done) {
-    constexpr int RPB = 16 * UNROLL * (64 / LPR);
-    dim3 grid((keys->N + RPB - 1) / RPB, keys->H, B);
-    hipLaunchKernelGGL((score_select_kernel<LPR, UNROLL, PAGE, IPT>), grid, dim3(1024), 0, st,
-                       static_cast<const u32x4*>(keys->data), static_cast<const uint16_t*>(q), scores, keys->N, keys->H,
-                       keys->G, k, out_idx, done);
-}
-
-template <int LPR, int UNROLL, bool PAGE>
-void launch_fused_ipt(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int k,
-                      int32_t* out_idx, uint32_t* done) {
-    const int N = keys->N;
-    if (N <= 4096) launch_fused_one<LPR, UNROLL, PAGE, 4>(st, keys, q, B, scores, k, out_idx, done);
-    else if (N <= 8192) launch_fused_one<LPR, UNROLL, PAGE, 8>(st, keys, q, B, scores, k, out_idx, done);
-    else if (N <= 16384) launch_fused_one<LPR, UNROLL, PAGE, 16>(st, keys, q, B, scores, k, out_idx, done);
-    else if (N <= 32768) launch_fused_one<LPR, UNROLL, PAGE, 32>(st, keys, q, B, scores, k, out_idx, done);
-    else launch_fused_one<LPR, UNROLL, PAGE, 64>(st, keys, q, B, scores, k, out_idx, done);
-}
-
-template <int LPR, bool PAGE>
-void launch_fused(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int k, int32_t* out_idx,
-                  uint32_t* done) {
-    // fewer rows per block when the sweep would otherwise leave compute units idle
-    constexpr int RPB8 = 16 * 8 * (64 / LPR);
-    const long blocks8 = (long)((keys->N + RPB8 - 1) / RPB8) * keys->H * B;
-    if (blocks8 >= 256) launch_fused_ipt<LPR, 8, PAGE>(st, keys, q, B, scores, k, out_idx, done);
-    else launch_fused_ipt<LPR, 2, PAGE>(st, keys, q, B, scores, k, out_idx, done);
-}
-
 template <int LPR, int NCH, bool PAGE>
 void launch_one(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int CH) {
-    constexpr int UNROLL = (NCH == 2) ? 4 : 8;
+    constexpr int UNROLL = (NCH == 2 || LPR >= 16) ? 4 : 8;
     constexpr int RPB = 4 * UNROLL * (64 / LPR);
     dim3 grid((keys->N + RPB - 1) / RPB, keys->H, B);
     hipLaunchKernelGGL((score_kernel<LPR, NCH, UNROLL, PAGE>), grid, dim3(256), 0, st,
@@ -254,15 +155,4 @@ swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q,
     if (page) dispatch<true>(ctx->stream, keys, q, B, scores, CH);
     else dispatch<false>(ctx->stream, keys, q, B, scores, CH);
     return swarm_check_launch(ctx, "score_kernel");
-}
-
-bool score_select_can_fuse(const swarm_keys* keys, int B) {
-    return keys->d == 128 && keys->N <= 65536 && B <= SWARM_FUSED_MAX_STREAMS && keys->H <= 65535;
-}
-
-swarm_status launch_score_select_fused(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, int k,
-                                       float* scores, int32_t* out_idx) {
-    if (keys->kind == SWARM_KEYS_PAGE_MINMAX) launch_fused<32, true>(ctx->stream, keys, q, B, scores, k, out_idx, ctx->done);
-    else launch_fused<16, false>(ctx->stream, keys, q, B, scores, k, out_idx, ctx->done);
-    return swarm_check_launch(ctx, "score_select_kernel");
 }

@@ -19,7 +19,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "wave_ops.h"
+
 namespace selcore {
+
+using waveops::wave_incl_scan;
+using waveops::wave_max;
+using waveops::wave_min;
 
 constexpr int NT = 1024;        // threads per selecting block
 constexpr int NW = NT / 64;     // waves
@@ -58,20 +64,21 @@ __device__ __forceinline__ int bin_of(uint32_t key, float hi, float scale) {
     return (int)fminf(x, (float)(NB - 1));
 }
 
-// Exclusive block scan of two counters at once; returns totals through *ta, *tb when non-null.
+
+// Exclusive block scan of two counters at once.
 __device__ __forceinline__ void block_excl_scan2(uint32_t a, uint32_t b, uint32_t& ea, uint32_t& eb, Smem& sm,
                                                  int lane, int wave) {
-    uint32_t ia = a, ib = b;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t xa = __shfl_up(ia, off, 64), xb = __shfl_up(ib, off, 64);
-        if (lane >= off) { ia += xa; ib += xb; }
-    }
+    const uint32_t ia = wave_incl_scan(a), ib = wave_incl_scan(b);
     if (lane == 63) { sm.wave_a[wave] = ia; sm.wave_b[wave] = ib; }
     __syncthreads();
     ea = ia - a;
     eb = ib - b;
-    for (int w = 0; w < wave; ++w) { ea += sm.wave_a[w]; eb += sm.wave_b[w]; }
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {                 // independent broadcast reads; earlier waves only
+        const uint32_t ta = sm.wave_a[w], tb = sm.wave_b[w];
+        ea += (w < wave) ? ta : 0u;
+        eb += (w < wave) ? tb : 0u;
+    }
 }
 
 // key[e] is the key of index tid*IPT + e; slots at or beyond N must hold key 0.
@@ -92,11 +99,8 @@ __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, 
             lo = fminf(lo, v);
         }
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        hi = fmaxf(hi, __shfl_xor(hi, off, 64));
-        lo = fminf(lo, __shfl_xor(lo, off, 64));
-    }
+    hi = wave_max(hi);
+    lo = wave_min(lo);
     if (lane == 0) { sm.wave_hi[wave] = hi; sm.wave_lo[wave] = lo; }
     sm.hist[tid] = 0;
     sm.hist[tid + NT] = 0;
