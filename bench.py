@@ -153,9 +153,9 @@ def main():
     row_bytes = (2 if cfg.unit == "page" else 1) * cfg.d * 2
     sweep_bytes = H * N * row_bytes + H * cfg.G * cfg.d * 2 + H * N * 4      # key side + queries in, fp32 scores out
     score_gbs = sweep_bytes / (score_us * 1e-6) / 1e9
-    Tpad = (T + 127) // 128 * 128
-    tiles = (N + 127) // 128
-    issued_ops = 2.0 * H * (tiles * (tiles + 1) // 2) * 128 * 128 * Tpad       # MFMA ops actually issued (upper triangle)
+    Tpad = (T + 255) // 256 * 256
+    tiles = (N + 255) // 256
+    issued_ops = 2.0 * H * (tiles * (tiles + 1) // 2) * 256 * 256 * Tpad       # MFMA ops actually issued (upper triangle)
     dense_ops = 2.0 * H * N * N * T
     coact_tops = issued_ops / (coact_ms * 1e-3) / 1e12
 

@@ -130,7 +130,7 @@ swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, 
  * flags  SWARM_CHECK_IDX additionally flags repeated entries (SWARM_DEV_DUP_ENTRY); a repeated
  *        entry counts once either way, because the trace is binary.
  * Errors: SWARM_EINVAL as above or decay_q16 > 65536; SWARM_ENOMEM if the trace (H*N*rows bytes,
- * rows rounded up to 128) cannot be allocated.
+ * rows rounded up to 256, N to 256) cannot be allocated.
  */
 swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int32_t H, int32_t k,
                                     int32_t N, int32_t* C, uint32_t decay_q16, uint32_t flags);

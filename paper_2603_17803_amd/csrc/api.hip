@@ -74,6 +74,7 @@ swarm_status swarm_destroy(swarm_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->scores) (void)hipFree(ctx->scores);
     if (ctx->trace) (void)hipFree(ctx->trace);
+    if (ctx->tile_order) (void)hipFree(ctx->tile_order);
     if (ctx->dev_flags) (void)hipFree(ctx->dev_flags);
     delete ctx;
     return SWARM_OK;
@@ -152,7 +153,7 @@ swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t 
     if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "coact_accumulate: C must be 16-byte aligned");
     if (flags & ~SWARM_CHECK_IDX) SWARM_REJECT(ctx, "coact_accumulate: unknown flags 0x%x", flags);
 
-    const int64_t Tpad = (rows + 127) / 128 * 128;   // contraction length, zero-padded to the K tile
+    const int64_t Tpad = (rows + 255) / 256 * 256;   // contraction length, zero-padded to two K chunks
     const int Npad = (N + 255) / 256 * 256;          // rows of A^T, zero-padded to the C tile
     swarm_status st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->trace), &ctx->trace_bytes,
                                  (size_t)H * Npad * Tpad);

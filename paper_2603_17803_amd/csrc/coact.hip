@@ -6,6 +6,8 @@
 // The product runs on the int8 matrix cores (v_mfma_i32_32x32x32_i8) with exact int32
 // accumulation.  C is symmetric, so only tiles on or above the diagonal are computed and each
 // off-diagonal tile is stored twice (once transposed).
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace {
@@ -42,8 +44,14 @@ __global__ void check_distinct_kernel(const int32_t* __restrict__ idx, int k, ui
     if (dup) atomicOr(dev_flags, SWARM_DEV_DUP_ENTRY);
 }
 
+// floor((old * decay_q16 + 2^15) / 2^16) with a 64-bit product, spelled in 32-bit halves
+// (decay_q16 <= 65536, so the result fits int32).
 __device__ __forceinline__ int32_t decayed(int32_t old, uint32_t decay_q16) {
-    return (int32_t)(((int64_t)old * (int64_t)decay_q16 + 32768) >> 16);
+    const uint32_t lo = (uint32_t)old * decay_q16;
+    const int32_t hi = __mulhi(old, (int32_t)decay_q16);
+    const uint32_t lo2 = lo + 32768u;
+    const int32_t hi2 = hi + (lo2 < lo ? 1 : 0);
+    return (int32_t)(((uint32_t)hi2 << 16) | (lo2 >> 16));
 }
 
 // MODE 0: C = acc.  MODE 1: C += acc.  MODE 2: C = decayed(C) + acc.
@@ -54,80 +62,237 @@ __device__ __forceinline__ void store_c(int32_t* p, int32_t acc, uint32_t decay_
     else *p = decayed(*p, decay_q16) + acc;
 }
 
-constexpr int TILE = 128;      // C tile edge per workgroup
-constexpr int KC = 64;         // contraction bytes staged per iteration
-constexpr int LDS_ROW = KC + 16;   // padded LDS row (bytes)
+// 4 x 4 transpose across the four lanes of a quad: on entry lane k holds x[m] = M[m][k] (one column
+// of a 4 x 4 block), on return it holds M[k][0..3] (one row), so that the row can leave as one
+// 16-byte store.  Two butterfly steps on the DPP path.
+__device__ __forceinline__ v4i quad_transpose(const v4i x, int lane) {
+    const bool b0 = lane & 1, b1 = lane & 2;
+    v4i z, y;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int t = __builtin_amdgcn_update_dpp(0, x[m ^ 1], 0xB1, 0xF, 0xF, false);     // quad_perm [1,0,3,2]
+        z[m] = (((m & 1) != 0) == b0) ? x[m] : t;
+    }
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int t = __builtin_amdgcn_update_dpp(0, z[m ^ 2], 0x4E, 0xF, 0xF, false);     // quad_perm [2,3,0,1]
+        y[m] = (((m & 2) != 0) == b1) ? z[m] : t;
+    }
+    return y;
+}
 
-// 256 threads = 4 waves in a 2x2 arrangement, each wave owns a 64x64 corner = 2x2 MFMA tiles.
+constexpr int TILE = 256;          // C tile edge per workgroup
+constexpr int KC = 128;            // contraction bytes staged per iteration (one cache line per trace row)
+constexpr int STAGE_BYTES = TILE * KC;                 // one operand tile in LDS
+constexpr int SYRK_LDS_BYTES = 2 * 2 * STAGE_BYTES;    // double buffer x (A, B) = 128 KiB
+
+// 16-byte chunk c of row r lives at chunk position c ^ (r & 7): the eight rows that one quarter of
+// a fragment read touches then fall into eight different 16-byte bank groups.
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * KC + ((chunk ^ (row & 7)) << 4); }
+
+// C tile of 256 x 256 per workgroup; 4 waves in a 2 x 2 arrangement, each owning 128 x 128 =
+// 4 x 4 MFMA tiles (256 accumulator registers).  The contraction runs in 128-byte chunks (four
+// 32-byte MFMA k-steps) through a two-deep LDS ring.  Chunk c+1 travels from memory straight into
+// the idle LDS buffer (global_load ... lds, no staging registers, no LDS write instructions)
+// while chunk c feeds the matrix cores; operand fragments of k-step s+1 are read from LDS while
+// the 16 MFMAs of k-step s run.
+// A direct-to-LDS load writes lane i's 16 bytes at (wave-uniform base) + 16 * i, i.e. one
+// instruction fills 8 consecutive 128-byte LDS rows; the bank swizzle of lds_off() is obtained by
+// choosing which 16 bytes of the row each lane fetches.
+// Workgroups are numbered so that the eight L2 slices (one per XCD, workgroups are dealt to them
+// round-robin) each walk a contiguous run of the tile schedule.
 template <int MODE>
-__global__ __launch_bounds__(256) void coact_syrk_kernel(const int8_t* __restrict__ At, int N, int Npad, int64_t Tpad,
-                                                         int32_t* __restrict__ C, uint32_t decay_q16) {
-    const int ti = blockIdx.y, tj = blockIdx.x, h = blockIdx.z;
-    if (tj < ti) return;                                       // lower triangle comes from the mirror store
-    __shared__ __attribute__((aligned(16))) int8_t lds_a[TILE * LDS_ROW];
-    __shared__ __attribute__((aligned(16))) int8_t lds_b[TILE * LDS_ROW];
+__global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __restrict__ At, int N, int Npad, int64_t Tpad,
+                                                            int32_t* __restrict__ C, uint32_t decay_q16, int nt,
+                                                            int tiles_per_head, int total_tiles, int per_xcd,
+                                                            const int32_t* __restrict__ tile_order, int stagger_unit) {
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int t = xcd * per_xcd + slot;
+    if (slot >= per_xcd || t >= total_tiles) return;
+    const int h = t / tiles_per_head;
+    const int32_t packed = tile_order[t - h * tiles_per_head];
+    const int ti = packed >> 16, tj = packed & 0xffff;
+    const bool diag = ti == tj;
+    // Every tile costs the same, so workgroups that start together would also store together and
+    // turn the run into alternating compute-only and store-only phases.  The workgroups of the first
+    // round start up to half a tile apart instead; later rounds inherit the offsets.
+    if (slot < 32) {
+        const int naps = (slot & 7) * stagger_unit;
+        for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
+    }
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wy = wave >> 1, wx = wave & 1;
-    const int8_t* a_rows = At + ((size_t)h * Npad + (size_t)ti * TILE) * Tpad;
-    const int8_t* b_rows = At + ((size_t)h * Npad + (size_t)tj * TILE) * Tpad;
 
-    // staging: thread t copies 16 bytes of row t/4 (and t/4 + 64), byte column (t%4)*16
-    const int srow = tid >> 2, scol = (tid & 3) * 16;
+    // memory -> LDS: wave w fills rows [64w, 64w + 64) of both operand tiles, 8 rows per instruction
+    const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;            // LDS row within the group of 8; logical chunk fetched
+    const int8_t* a_src = At + ((size_t)h * Npad + (size_t)ti * TILE + wave * 64 + lrow) * Tpad + lchunk * 16;
+    const int8_t* b_src = At + ((size_t)h * Npad + (size_t)tj * TILE + wave * 64 + lrow) * Tpad + lchunk * 16;
+    const size_t row8 = (size_t)8 * Tpad;
+    const int nchunks = (int)(Tpad / KC);
+    auto issue_chunk = [&](int buf, int chunk) {
+        const int64_t k0 = (int64_t)chunk * KC;
+        int8_t* la = lds + buf * 2 * STAGE_BYTES + wave * 64 * KC;
+        int8_t* lb = la + STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_src + i * row8 + k0),
+                                             (__attribute__((address_space(3))) void*)(la + i * 8 * KC), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b_src + i * row8 + k0),
+                                             (__attribute__((address_space(3))) void*)(lb + i * 8 * KC), 16, 0, 0);
+        }
+    };
 
-    v16i acc[2][2];
+    v16i acc[4][4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    const int frow = lane & 31, fk = (lane >> 5) * 16;         // MFMA operand fragment: row, byte offset in a 32-byte k-step
-    for (int64_t k0 = 0; k0 < Tpad; k0 += KC) {
-        const v4i a0 = *reinterpret_cast<const v4i*>(a_rows + (size_t)srow * Tpad + k0 + scol);
-        const v4i a1 = *reinterpret_cast<const v4i*>(a_rows + (size_t)(srow + 64) * Tpad + k0 + scol);
-        const v4i b0 = *reinterpret_cast<const v4i*>(b_rows + (size_t)srow * Tpad + k0 + scol);
-        const v4i b1 = *reinterpret_cast<const v4i*>(b_rows + (size_t)(srow + 64) * Tpad + k0 + scol);
-        __syncthreads();                                       // previous iteration's reads are done
-        *reinterpret_cast<v4i*>(lds_a + srow * LDS_ROW + scol) = a0;
-        *reinterpret_cast<v4i*>(lds_a + (srow + 64) * LDS_ROW + scol) = a1;
-        *reinterpret_cast<v4i*>(lds_b + srow * LDS_ROW + scol) = b0;
-        *reinterpret_cast<v4i*>(lds_b + (srow + 64) * LDS_ROW + scol) = b1;
-        __syncthreads();
+    // fragment addressing: lane l reads row l%32 of an MFMA tile, bytes [16*(l/32), +16) of the 32-byte
+    // k-step.  The swizzle term only depends on the k-step; the tile index is a constant byte offset.
+    const int frow = lane & 31, fhalf = lane >> 5;
+    int fa_base[4], fb_base[4];
 #pragma unroll
-        for (int ks = 0; ks < KC; ks += 32) {
-            v4i fa[2], fb[2];
+    for (int ks = 0; ks < 4; ++ks) {
+        fa_base[ks] = lds_off(wy * 128 + frow, 2 * ks + fhalf);
+        fb_base[ks] = STAGE_BYTES + lds_off(wx * 128 + frow, 2 * ks + fhalf);
+    }
+    v4i fa[2][4], fb[2][4];
+    auto read_frags = [&](int buf, int ks, int set) {
+        const int8_t* base = lds + buf * 2 * STAGE_BYTES;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                fa[i] = *reinterpret_cast<const v4i*>(lds_a + (wy * 64 + i * 32 + frow) * LDS_ROW + ks + fk);
-                fb[i] = *reinterpret_cast<const v4i*>(lds_b + (wx * 64 + i * 32 + frow) * LDS_ROW + ks + fk);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) {
+            fa[set][i] = *reinterpret_cast<const v4i*>(base + fa_base[ks] + i * 32 * KC);
+            fb[set][i] = *reinterpret_cast<const v4i*>(base + fb_base[ks] + i * 32 * KC);
         }
+    };
+    auto mfma16 = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+    };
+    // one k-step: prefetch the next k-step's fragments (interleaved one read per MFMA), then 16 MFMAs
+    auto kstep_with_prefetch = [&](int buf, int ks_next, int cur) {
+        read_frags(buf, ks_next, cur ^ 1);
+        mfma16(cur);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        _Pragma("unroll") for (int g = 0; g < 8; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
+    };
+
+    issue_chunk(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's rows have landed in LDS
+    __syncthreads();
+
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) issue_chunk(buf ^ 1, c + 1);       // the other buffer was last read before the previous barrier
+        read_frags(buf, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);     // the first k-step's fragments cannot be hidden: issue them together
+        kstep_with_prefetch(buf, 1, 0);
+        kstep_with_prefetch(buf, 2, 1);
+        kstep_with_prefetch(buf, 3, 0);
+        mfma16(1);
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0) before the barrier publishes the next buffer
+        __syncthreads();
     }
 
-    // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4
+    // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4, i.e. a lane
+    // holds 4 consecutive rows of one column per register quadruple.  All of C leaves in 16-byte
+    // stores that cover whole 128-byte lines (streaming stores when C is not read back):
+    //  - direct tile: a quad transpose turns the 4 rows x 1 column of a lane into 1 row x 4 columns;
+    //    the 8 quads of a half-wave then cover 128 contiguous bytes of that row;
+    //  - mirrored tile: each wave transposes 32 mirror rows x 128 columns at a time through its own
+    //    slice of the (now idle) LDS and writes them out as 512-byte row segments.
     int32_t* Ch = C + (size_t)h * N * N;
-    const int col_in = lane & 31, row_in = (lane >> 5) * 4;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int gi = ti * TILE + wy * 64 + i * 32 + (r >> 2) * 8 + row_in + (r & 3);
-                const int gj = tj * TILE + wx * 64 + j * 32 + col_in;
-                if (gi < N && gj < N) {
-                    const int32_t v = acc[i][j][r];
-                    store_c<MODE>(Ch + (size_t)gi * N + gj, v, decay_q16);
-                    if (tj != ti) store_c<MODE>(Ch + (size_t)gj * N + gi, v, decay_q16);
-                }
+    const int col_in = lane & 31, half = lane >> 5, row_in = half * 4;
+    const int qcol = col_in & ~3, qrow = lane & 3;
+    const bool vec_ok = (N & 3) == 0;
+    auto rmw4 = [&](int32_t* p, v4i v) {
+        if (MODE == 0) {
+            __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(p));
+        } else {
+            const v4i o = *reinterpret_cast<const v4i*>(p);
+            if (MODE == 1) v += o;
+            else {
+                v.x += decayed(o.x, decay_q16); v.y += decayed(o.y, decay_q16);
+                v.z += decayed(o.z, decay_q16); v.w += decayed(o.w, decay_q16);
             }
+            *reinterpret_cast<v4i*>(p) = v;
+        }
+    };
+    if (vec_ok) {
+        // direct tile
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int gjq = tj * TILE + wx * 128 + j * 32 + qcol;
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int gi = ti * TILE + wy * 128 + i * 32 + rq * 8 + row_in + qrow;
+                    const v4i v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
+                    const v4i vt = quad_transpose(v, lane);              // row gi, columns gjq .. gjq + 3
+                    if (gi < N && gjq < N) rmw4(Ch + (size_t)gi * N + gjq, vt);
+                }
+                asm volatile("" ::: "memory");              // one MFMA tile at a time: keeps the register footprint of the epilogue small
+            }
+        // mirrored tile, through LDS
+        if (!diag) {
+            constexpr int TROW = 512 + 16;                               // padded row: 16-byte writes of 8 lanes hit 8 bank groups
+            int8_t* tbuf = lds + wave * (32 * TROW);
+            const int gi_base = ti * TILE + wy * 128;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int rq = 0; rq < 4; ++rq) {
+                        const v4i v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
+                        *reinterpret_cast<v4i*>(tbuf + col_in * TROW + (i * 32 + rq * 8 + row_in) * 4) = v;
+                        if (rq == 3) asm volatile("" ::: "memory");
+                    }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                const int gj_base = tj * TILE + wx * 128 + j * 32;
+#pragma unroll
+                for (int sidx = 0; sidx < 16; ++sidx) {
+                    const int r = 2 * sidx + half;
+                    const v4i v = *reinterpret_cast<const v4i*>(tbuf + r * TROW + col_in * 16);
+                    const int gj = gj_base + r, gi = gi_base + col_in * 4;
+                    if (gj < N && gi < N) rmw4(Ch + (size_t)gj * N + gi, v);
+                    if ((sidx & 3) == 3) asm volatile("" ::: "memory");
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int gj = tj * TILE + wx * 128 + j * 32 + col_in;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int gi = ti * TILE + wy * 128 + i * 32 + (r >> 2) * 8 + row_in + (r & 3);
+                    if (gi < N && gj < N) {
+                        store_c<MODE>(Ch + (size_t)gi * N + gj, acc[i][j][r], decay_q16);
+                        if (!diag) store_c<MODE>(Ch + (size_t)gj * N + gi, acc[i][j][r], decay_q16);
+                    }
+                }
+                if (MODE != 0) asm volatile("" ::: "memory");
+            }
+    }
 }
 
 }  // namespace
@@ -152,18 +317,72 @@ swarm_status launch_trace_scatter(swarm_ctx* ctx, const int32_t* idx, int64_t ro
     return swarm_check_launch(ctx, "trace_scatter_kernel");
 }
 
+// Order in which the upper-triangle tiles are handed out: super-blocks of 4 x 8 tiles, so that the
+// ~32 workgroups resident on one XCD share 4 A panels and 8 B panels in its L2.
+static swarm_status ensure_tile_order(swarm_ctx* ctx, int nt) {
+    if (ctx->tile_order && ctx->tile_order_nt == nt) return SWARM_OK;
+    const size_t count = (size_t)nt * (nt + 1) / 2;
+    int32_t* host = static_cast<int32_t*>(malloc(count * sizeof(int32_t)));
+    if (!host) return SWARM_ENOMEM;
+    size_t n = 0;
+    for (int bi = 0; bi < nt; bi += 4)
+        for (int bj = bi / 8 * 8; bj < nt; bj += 8)
+            for (int ti = bi; ti < bi + 4 && ti < nt; ++ti)
+                for (int tj = (bj > ti ? bj : ti); tj < bj + 8 && tj < nt; ++tj) host[n++] = (ti << 16) | tj;
+    swarm_status st = SWARM_OK;
+    if (n != count) {
+        snprintf(ctx->err, sizeof(ctx->err), "coact: tile order covers %zu of %zu tiles", n, count);
+        st = SWARM_EINVAL;
+    }
+    if (st == SWARM_OK) {
+        size_t have = ctx->tile_order ? (size_t)ctx->tile_order_nt * (ctx->tile_order_nt + 1) / 2 * 4 : 0;
+        st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->tile_order), &have, count * 4);
+    }
+    if (st == SWARM_OK) {
+        hipError_t e = hipMemcpyAsync(ctx->tile_order, host, count * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) {
+            snprintf(ctx->err, sizeof(ctx->err), "coact: tile order upload failed: %s", hipGetErrorString(e));
+            st = SWARM_EHIP;
+        } else {
+            ctx->tile_order_nt = nt;
+        }
+    }
+    free(host);
+    return st;
+}
+
 swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int64_t Tpad, int32_t* C, uint32_t decay_q16) {
     const int nt = Npad / TILE;
-    if (nt > 65535 || H > 65535) {
-        snprintf(ctx->err, sizeof(ctx->err), "coact: N=%d or H=%d too large for the launch grid", N, H);
+    const int64_t tiles_per_head = (int64_t)nt * (nt + 1) / 2;
+    const int64_t total = tiles_per_head * H;
+    if (total > (int64_t)1 << 30 || nt > 32767) {
+        snprintf(ctx->err, sizeof(ctx->err), "coact: N=%d, H=%d give too many tiles for one launch", N, H);
         return SWARM_EINVAL;
     }
-    dim3 grid(nt, nt, H), block(256);
+    swarm_status st = ensure_tile_order(ctx, nt);
+    if (st != SWARM_OK) return st;
+    const int per_xcd = (int)((total + 7) / 8);
+    static bool lds_opt_in = false;
+    if (!lds_opt_in) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&coact_syrk_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize, SYRK_LDS_BYTES);
+        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&coact_syrk_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, SYRK_LDS_BYTES);
+        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&coact_syrk_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, SYRK_LDS_BYTES);
+        if (e != hipSuccess) {
+            snprintf(ctx->err, sizeof(ctx->err), "coact: cannot opt in to %d bytes of LDS: %s", SYRK_LDS_BYTES, hipGetErrorString(e));
+            return SWARM_EHIP;
+        }
+        lds_opt_in = true;
+    }
+    dim3 grid((unsigned)(per_xcd * 8)), block(256);
+    const int tph = (int)tiles_per_head, tot = (int)total;
+    // one nap = s_sleep 127 = 8128 cycles; a tile takes about 4000 cycles per 128-byte chunk
+    const int stagger_unit = per_xcd >= 64 ? (int)(Tpad / KC / 16) : 0;
     if (decay_q16 == 0u)
-        hipLaunchKernelGGL(coact_syrk_kernel<0>, grid, block, 0, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16);
+        hipLaunchKernelGGL(coact_syrk_kernel<0>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order, stagger_unit);
     else if (decay_q16 == 65536u)
-        hipLaunchKernelGGL(coact_syrk_kernel<1>, grid, block, 0, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16);
+        hipLaunchKernelGGL(coact_syrk_kernel<1>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order, stagger_unit);
     else
-        hipLaunchKernelGGL(coact_syrk_kernel<2>, grid, block, 0, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16);
+        hipLaunchKernelGGL(coact_syrk_kernel<2>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order, stagger_unit);
     return swarm_check_launch(ctx, "coact_syrk_kernel");
 }

@@ -23,6 +23,8 @@ struct swarm_ctx {
     int8_t* trace = nullptr;       // A^T, int8 [H][Npad][Tpad]
     size_t trace_bytes = 0;
     uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
+    int32_t* tile_order = nullptr; // co-activation tile schedule for tile_order_nt tiles per edge
+    int tile_order_nt = 0;
     bool capturing = false;
 };
 
