@@ -190,22 +190,36 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
         __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
     };
 
+    auto mfma_half = [&](int set, int half_idx) {
+#pragma unroll
+        for (int i = 2 * half_idx; i < 2 * half_idx + 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+    };
+
     issue_chunk(0, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's rows have landed in LDS
     __syncthreads();
+    read_frags(0, 0, 0);
 
+    // Per chunk: the loads of the next chunk are issued first and get (almost) the whole chunk's MFMA
+    // time to land; the hand-over barrier sits 8 MFMAs before the end of the chunk, and those last
+    // 8 MFMAs cover the LDS latency of the next chunk's first fragments.
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
         if (c + 1 < nchunks) issue_chunk(buf ^ 1, c + 1);       // the other buffer was last read before the previous barrier
-        read_frags(buf, 0, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);     // the first k-step's fragments cannot be hidden: issue them together
         kstep_with_prefetch(buf, 1, 0);
         kstep_with_prefetch(buf, 2, 1);
         kstep_with_prefetch(buf, 3, 0);
-        mfma16(1);
-        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0) before the barrier publishes the next buffer
+        mfma_half(1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0): the next buffer has landed
         __syncthreads();
+        read_frags(buf ^ 1, 0, 0);             // after the last chunk this reads stale but valid LDS and is never used
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_half(1, 1);
     }
 
     // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4, i.e. a lane
