@@ -86,19 +86,19 @@ constexpr int KC = 128;            // contraction bytes staged per iteration (on
 constexpr int STAGE_BYTES = TILE * KC;                 // one operand tile in LDS
 constexpr int SYRK_LDS_BYTES = 2 * 2 * STAGE_BYTES;    // double buffer x (A, B) = 128 KiB
 
-// 16-byte chunk c of row r lives at chunk position c ^ (r & 7): the eight rows that one quarter of
-// a fragment read touches then fall into eight different 16-byte bank groups.
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * KC + ((chunk ^ (row & 7)) << 4); }
+// 16-byte chunk c of row r lives at chunk position c ^ ((r >> 1) & 7).  The LDS has 64 four-byte banks,
+// so a 16-byte access is served 16 lanes at a time; the 16 rows such a group touches when it reads one
+// logical chunk then fall into 16 different 16-byte bank groups (row parity picks the half, the
+// swizzled chunk the slot), and a 128-byte row written by 8 lanes stays one contiguous line.
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * KC + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
 // C tile of 256 x 256 per workgroup; 4 waves in a 2 x 2 arrangement, each owning 128 x 128 =
 // 4 x 4 MFMA tiles (256 accumulator registers).  The contraction runs in 128-byte chunks (four
-// 32-byte MFMA k-steps) through a two-deep LDS ring.  Chunk c+1 travels from memory straight into
-// the idle LDS buffer (global_load ... lds, no staging registers, no LDS write instructions)
-// while chunk c feeds the matrix cores; operand fragments of k-step s+1 are read from LDS while
-// the 16 MFMAs of k-step s run.
-// A direct-to-LDS load writes lane i's 16 bytes at (wave-uniform base) + 16 * i, i.e. one
-// instruction fills 8 consecutive 128-byte LDS rows; the bank swizzle of lds_off() is obtained by
-// choosing which 16 bytes of the row each lane fetches.
+// 32-byte MFMA k-steps) through a two-deep LDS ring fed from registers: chunk c+2 is in flight from
+// memory into registers, chunk c+1 is being written into the idle LDS buffer, chunk c feeds the
+// matrix cores; operand fragments of k-step s+1 are read from LDS while the 16 MFMAs of k-step s
+// run.  (Direct-to-LDS loads were measured slower here: their LDS writes arrive 64 bytes per clock
+// and, together with the fragment reads, saturate the LDS port.)
 // Workgroups are numbered so that the eight L2 slices (one per XCD, workgroups are dealt to them
 // round-robin) each walk a contiguous run of the tile schedule.
 template <int MODE>
@@ -126,23 +126,34 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wy = wave >> 1, wx = wave & 1;
 
-    // memory -> LDS: wave w fills rows [64w, 64w + 64) of both operand tiles, 8 rows per instruction
-    const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;            // LDS row within the group of 8; logical chunk fetched
-    const int8_t* a_src = At + ((size_t)h * Npad + (size_t)ti * TILE + wave * 64 + lrow) * Tpad + lchunk * 16;
-    const int8_t* b_src = At + ((size_t)h * Npad + (size_t)tj * TILE + wave * 64 + lrow) * Tpad + lchunk * 16;
-    const size_t row8 = (size_t)8 * Tpad;
+    // memory -> registers -> LDS: thread t moves 16-byte chunk t%8 of rows t/8 + 32*i, i = 0..7, of both
+    // operand tiles (8 lanes cover one 128-byte line of a trace row).  The registers hold chunk c+2
+    // while chunk c+1 sits in the idle LDS buffer and chunk c feeds the matrix cores.
+    const int srow = tid >> 3, schunk = tid & 7;
+    const int8_t* a_src = At + ((size_t)h * Npad + (size_t)ti * TILE + srow) * Tpad + schunk * 16;
+    const int8_t* b_src = At + ((size_t)h * Npad + (size_t)tj * TILE + srow) * Tpad + schunk * 16;
+    const size_t row32 = (size_t)32 * Tpad;
     const int nchunks = (int)(Tpad / KC);
-    auto issue_chunk = [&](int buf, int chunk) {
-        const int64_t k0 = (int64_t)chunk * KC;
-        int8_t* la = lds + buf * 2 * STAGE_BYTES + wave * 64 * KC;
-        int8_t* lb = la + STAGE_BYTES;
+    const int st_base = lds_off(srow, schunk);              // rows srow + 32*i share the swizzle term: constant byte offsets
+    v4i sta[2][8], stb[2][8];                               // two register sets, indexed by chunk parity
+    // loads number l0 .. l1-1 of the 16 that make up one chunk (0..7: A rows, 8..15: B rows)
+    auto load_part = [&](int set, int chunk, int l0, int l1) {
+        const int64_t k0 = (int64_t)min(chunk, nchunks - 1) * KC;      // clamped: a redundant reload past the end is harmless
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_src + i * row8 + k0),
-                                             (__attribute__((address_space(3))) void*)(la + i * 8 * KC), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b_src + i * row8 + k0),
-                                             (__attribute__((address_space(3))) void*)(lb + i * 8 * KC), 16, 0, 0);
+        for (int l = l0; l < l1; ++l) {
+            if (l < 8) sta[set][l] = *reinterpret_cast<const v4i*>(a_src + l * row32 + k0);
+            else stb[set][l - 8] = *reinterpret_cast<const v4i*>(b_src + (l - 8) * row32 + k0);
         }
+    };
+    auto store_a = [&](int set, int buf) {
+        int8_t* la = lds + buf * 2 * STAGE_BYTES + st_base;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<v4i*>(la + i * 32 * KC) = sta[set][i];
+    };
+    auto store_b = [&](int set, int buf) {
+        int8_t* lb = lds + buf * 2 * STAGE_BYTES + STAGE_BYTES + st_base;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<v4i*>(lb + i * 32 * KC) = stb[set][i];
     };
 
     v16i acc[4][4];
@@ -178,18 +189,6 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
             for (int j = 0; j < 4; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
     };
-    // one k-step: prefetch the next k-step's fragments (interleaved one read per MFMA), then 16 MFMAs
-    auto kstep_with_prefetch = [&](int buf, int ks_next, int cur) {
-        read_frags(buf, ks_next, cur ^ 1);
-        mfma16(cur);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        _Pragma("unroll") for (int g = 0; g < 8; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
-    };
-
     auto mfma_half = [&](int set, int half_idx) {
 #pragma unroll
         for (int i = 2 * half_idx; i < 2 * half_idx + 2; ++i)
@@ -197,29 +196,66 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
             for (int j = 0; j < 4; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
     };
+    // Scheduling hint for one k-step of 16 MFMAs: after MFMA i comes one fragment read (i < 8), one LDS
+    // store (i >= 8, when the step carries stores) and one global load after every fourth MFMA, so
+    // that no unit sees a burst.
+    auto interleave16 = [&](bool with_stores) {
+        _Pragma("unroll") for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            else if (with_stores) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            if ((i & 3) == 3) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+    };
 
-    issue_chunk(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's rows have landed in LDS
+    load_part(0, 0, 0, 16);
+    load_part(1, 1, 0, 16);
+    store_a(0, 0);
+    store_b(0, 0);
+    load_part(0, 2, 0, 4);
     __syncthreads();
     read_frags(0, 0, 0);
 
-    // Per chunk: the loads of the next chunk are issued first and get (almost) the whole chunk's MFMA
-    // time to land; the hand-over barrier sits 8 MFMAs before the end of the chunk, and those last
-    // 8 MFMAs cover the LDS latency of the next chunk's first fragments.
-    for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
-        if (c + 1 < nchunks) issue_chunk(buf ^ 1, c + 1);       // the other buffer was last read before the previous barrier
-        kstep_with_prefetch(buf, 1, 0);
-        kstep_with_prefetch(buf, 2, 1);
-        kstep_with_prefetch(buf, 3, 0);
+    // Chunk c computes out of LDS buffer c%2.  Register set (c+1)%2 holds chunk c+1: it is written to the
+    // other LDS buffer during the second and third k-step and starts refilling with chunk c+3 in the
+    // fourth.  Register set c%2 keeps refilling with chunk c+2 during the first three k-steps.  The 16
+    // loads of a chunk are thus spread one per four MFMAs over a whole chunk time, and land at least a
+    // chunk time before they are needed.  The hand-over barrier sits 8 MFMAs before the end of the
+    // chunk; those last 8 MFMAs cover the LDS latency of the next chunk's first fragments.
+    auto chunk_body = [&](int c, int buf) {                 // buf = c % 2, passed as a literal
+        const int nset = buf ^ 1;
+        read_frags(buf, 1, 1);
+        load_part(buf, c + 2, 4, 8);
+        mfma16(0);
+        interleave16(false);
+
+        read_frags(buf, 2, 0);
+        store_a(nset, nset);                   // the other buffer was last read before the previous barrier
+        load_part(buf, c + 2, 8, 12);
+        mfma16(1);
+        interleave16(true);
+
+        read_frags(buf, 3, 1);
+        store_b(nset, nset);
+        load_part(buf, c + 2, 12, 16);
+        mfma16(0);
+        interleave16(true);
+
+        load_part(nset, c + 3, 0, 4);
         mfma_half(1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0): the next buffer has landed
         __syncthreads();
-        read_frags(buf ^ 1, 0, 0);             // after the last chunk this reads stale but valid LDS and is never used
+        read_frags(nset, 0, 0);                // after the last chunk this reads stale but valid LDS and is never used
         __builtin_amdgcn_sched_barrier(0);
         mfma_half(1, 1);
+    };
+    for (int c = 0; c < nchunks; c += 2) {                  // nchunks is even
+        chunk_body(c, 0);
+        chunk_body(c + 1, 1);
     }
 
     // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4, i.e. a lane
