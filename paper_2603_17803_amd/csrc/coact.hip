@@ -62,25 +62,6 @@ __device__ __forceinline__ void store_c(int32_t* p, int32_t acc, uint32_t decay_
     else *p = decayed(*p, decay_q16) + acc;
 }
 
-// 4 x 4 transpose across the four lanes of a quad: on entry lane k holds x[m] = M[m][k] (one column
-// of a 4 x 4 block), on return it holds M[k][0..3] (one row), so that the row can leave as one
-// 16-byte store.  Two butterfly steps on the DPP path.
-__device__ __forceinline__ v4i quad_transpose(const v4i x, int lane) {
-    const bool b0 = lane & 1, b1 = lane & 2;
-    v4i z, y;
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-        const int t = __builtin_amdgcn_update_dpp(0, x[m ^ 1], 0xB1, 0xF, 0xF, false);     // quad_perm [1,0,3,2]
-        z[m] = (((m & 1) != 0) == b0) ? x[m] : t;
-    }
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-        const int t = __builtin_amdgcn_update_dpp(0, z[m ^ 2], 0x4E, 0xF, 0xF, false);     // quad_perm [2,3,0,1]
-        y[m] = (((m & 2) != 0) == b1) ? z[m] : t;
-    }
-    return y;
-}
-
 constexpr int TILE = 256;          // C tile edge per workgroup
 constexpr int KC = 128;            // contraction bytes staged per iteration (one cache line per trace row)
 constexpr int STAGE_BYTES = TILE * KC;                 // one operand tile in LDS
@@ -105,7 +86,7 @@ template <int MODE>
 __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __restrict__ At, int N, int Npad, int64_t Tpad,
                                                             int32_t* __restrict__ C, uint32_t decay_q16, int nt,
                                                             int tiles_per_head, int total_tiles, int per_xcd,
-                                                            const int32_t* __restrict__ tile_order, int stagger_unit) {
+                                                            const int32_t* __restrict__ tile_order) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int t = xcd * per_xcd + slot;
@@ -114,13 +95,6 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
     const int32_t packed = tile_order[t - h * tiles_per_head];
     const int ti = packed >> 16, tj = packed & 0xffff;
     const bool diag = ti == tj;
-    // Every tile costs the same, so workgroups that start together would also store together and
-    // turn the run into alternating compute-only and store-only phases.  The workgroups of the first
-    // round start up to half a tile apart instead; later rounds inherit the offsets.
-    if (slot < 32) {
-        const int naps = (slot & 7) * stagger_unit;
-        for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
-    }
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -260,14 +234,10 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
 
     // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4, i.e. a lane
     // holds 4 consecutive rows of one column per register quadruple.  All of C leaves in 16-byte
-    // stores that cover whole 128-byte lines (streaming stores when C is not read back):
-    //  - direct tile: a quad transpose turns the 4 rows x 1 column of a lane into 1 row x 4 columns;
-    //    the 8 quads of a half-wave then cover 128 contiguous bytes of that row;
-    //  - mirrored tile: each wave transposes 32 mirror rows x 128 columns at a time through its own
-    //    slice of the (now idle) LDS and writes them out as 512-byte row segments.
+    // stores that cover whole 128-byte lines (streaming stores when C is not read back); the
+    // re-layout for both the direct and the mirrored tile goes through the (now idle) LDS.
     int32_t* Ch = C + (size_t)h * N * N;
     const int col_in = lane & 31, half = lane >> 5, row_in = half * 4;
-    const int qcol = col_in & ~3, qrow = lane & 3;
     const bool vec_ok = (N & 3) == 0;
     auto rmw4 = [&](int32_t* p, v4i v) {
         if (MODE == 0) {
@@ -283,38 +253,39 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
         }
     };
     if (vec_ok) {
-        // direct tile
+        // One block of 32 columns (j) x 128 rows at a time: the wave parks it in its own slice of the
+        // idle LDS as [column][row] and reads it back twice, once along rows of that layout for the
+        // mirrored tile and once across them (four 4-byte reads -> 4 consecutive columns of one row)
+        // for the direct tile.
+        constexpr int TROW = 512 + 16;                                   // padded: 16-byte accesses of 16 lanes hit 16 bank groups
+        int8_t* tbuf = lds + wave * (32 * TROW);
+        const int gi_base = ti * TILE + wy * 128;
+        const int drow = lane >> 3, dq = lane & 7;                       // direct read-out: row within a group of 8, group of 4 columns
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int gjq = tj * TILE + wx * 128 + j * 32 + qcol;
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
-                    const int gi = ti * TILE + wy * 128 + i * 32 + rq * 8 + row_in + qrow;
                     const v4i v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
-                    const v4i vt = quad_transpose(v, lane);              // row gi, columns gjq .. gjq + 3
-                    if (gi < N && gjq < N) rmw4(Ch + (size_t)gi * N + gjq, vt);
+                    *reinterpret_cast<v4i*>(tbuf + col_in * TROW + (i * 32 + rq * 8 + row_in) * 4) = v;
+                    if (rq == 3) asm volatile("" ::: "memory");
                 }
-                asm volatile("" ::: "memory");              // one MFMA tile at a time: keeps the register footprint of the epilogue small
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const int gj_base = tj * TILE + wx * 128 + j * 32;
+            // direct tile: rows gi_base + 0..127, columns gj_base + 0..31
+#pragma unroll
+            for (int sidx = 0; sidx < 16; ++sidx) {
+                const int r = sidx * 8 + drow;
+                const int8_t* src = tbuf + (dq * 4) * TROW + r * 4;
+                const v4i v = {*reinterpret_cast<const int*>(src), *reinterpret_cast<const int*>(src + TROW),
+                               *reinterpret_cast<const int*>(src + 2 * TROW), *reinterpret_cast<const int*>(src + 3 * TROW)};
+                const int gi = gi_base + r, gj = gj_base + dq * 4;
+                if (gi < N && gj < N) rmw4(Ch + (size_t)gi * N + gj, v);
+                if ((sidx & 3) == 3) asm volatile("" ::: "memory");
             }
-        // mirrored tile, through LDS
-        if (!diag) {
-            constexpr int TROW = 512 + 16;                               // padded row: 16-byte writes of 8 lanes hit 8 bank groups
-            int8_t* tbuf = lds + wave * (32 * TROW);
-            const int gi_base = ti * TILE + wy * 128;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int rq = 0; rq < 4; ++rq) {
-                        const v4i v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
-                        *reinterpret_cast<v4i*>(tbuf + col_in * TROW + (i * 32 + rq * 8 + row_in) * 4) = v;
-                        if (rq == 3) asm volatile("" ::: "memory");
-                    }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                const int gj_base = tj * TILE + wx * 128 + j * 32;
+            // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..127
+            if (!diag) {
 #pragma unroll
                 for (int sidx = 0; sidx < 16; ++sidx) {
                     const int r = 2 * sidx + half;
@@ -323,8 +294,8 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
                     if (gj < N && gi < N) rmw4(Ch + (size_t)gj * N + gi, v);
                     if ((sidx & 3) == 3) asm volatile("" ::: "memory");
                 }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
     } else {
 #pragma unroll
@@ -426,13 +397,11 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int64_t T
     }
     dim3 grid((unsigned)(per_xcd * 8)), block(256);
     const int tph = (int)tiles_per_head, tot = (int)total;
-    // one nap = s_sleep 127 = 8128 cycles; a tile takes about 4000 cycles per 128-byte chunk
-    const int stagger_unit = per_xcd >= 64 ? (int)(Tpad / KC / 16) : 0;
     if (decay_q16 == 0u)
-        hipLaunchKernelGGL(coact_syrk_kernel<0>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order, stagger_unit);
+        hipLaunchKernelGGL(coact_syrk_kernel<0>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order);
     else if (decay_q16 == 65536u)
-        hipLaunchKernelGGL(coact_syrk_kernel<1>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order, stagger_unit);
+        hipLaunchKernelGGL(coact_syrk_kernel<1>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order);
     else
-        hipLaunchKernelGGL(coact_syrk_kernel<2>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order, stagger_unit);
+        hipLaunchKernelGGL(coact_syrk_kernel<2>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order);
     return swarm_check_launch(ctx, "coact_syrk_kernel");
 }
