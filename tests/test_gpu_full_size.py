@@ -1,0 +1,171 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch shapes bench.py uses.
+
+At these sizes the oracle cannot produce every output in seconds, so each stage is checked on
+sampled outputs the oracle computes one by one, plus properties that hold at any size:
+  scores     : sampled decode steps against the oracle, within the score tolerance;
+  selections : the oracle's select on the GPU's own scores for the sampled steps, bit-exact; every
+               step: k distinct ascending indices;
+  C          : symmetric; diagonal = activation counts (independent histogram of the selections);
+               row sums = k * diagonal; grand total = rows * k^2; sampled entries against the count
+               of steps that hold both entries, bit-exact;
+  queues     : sampled groups against the oracle, bit-exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_17803_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def dev(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(a).cuda()
+
+
+@pytest.fixture(scope="module")
+def sw():
+    from paper_2603_17803_amd import binding
+    s = binding.Swarm(0)
+    yield s
+    s.close()
+
+
+def run_full(sw, cfg, sample_steps, rng):
+    K = W.keys(cfg)
+    qs = W.queries(cfg, 0, cfg.T)
+    e2c, weight, rep = W.cluster_tables(cfg)
+    Kd, q_d = dev(K), dev(qs)
+    e2c_d, w_d, rep_d = dev(e2c), dev(weight), dev(rep)
+    T, H, N, k = cfg.T, cfg.H, cfg.N, cfg.k
+    idx_all = torch.empty((T, H, k), dtype=torch.int32, device="cuda")
+    cap = min(k, cfg.Nc)
+    q_off = torch.empty((T, H, cfg.D + 1), dtype=torch.int32, device="cuda")
+    q_clu = torch.empty((T, H, cap), dtype=torch.int32, device="cuda")
+    q_load = torch.empty((T, H, cfg.D), dtype=torch.int32, device="cuda")
+    sampled = set(int(t) for t in sample_steps)
+    kept_scores = {}
+    for t in range(T):
+        want = t in sampled
+        _, sc = sw.score_select(cfg.unit, Kd, q_d[t], k, G=cfg.G, out_idx=idx_all[t:t + 1], want_scores=want)
+        if want:
+            kept_scores[t] = sc
+        sw.map_requests(idx_all[t], H, N, e2c_d, cfg.Nc, rep_d, cfg.D, w_d, cap=cap,
+                        out=(q_off[t], q_clu[t], q_load[t]))
+    Cm = torch.empty((H, N, N), dtype=torch.int32, device="cuda")
+    sw.coact_accumulate(idx_all, N, Cm, decay_q16=0)
+    torch.cuda.synchronize()
+    assert sw.device_status() == 0
+
+    idx = idx_all.cpu().numpy()
+    # selections: k distinct ascending, in range, every step
+    assert (np.diff(idx, axis=-1) > 0).all() and idx.min() >= 0 and idx.max() < N
+
+    for t in sorted(sampled):
+        sc = kept_scores[t].cpu().numpy()
+        _, ref64, ab = oracle.score(cfg.unit, K, qs[t], G=cfg.G, nthreads=8)
+        terms = cfg.d * (2 if cfg.unit == "page" else 1) * cfg.G
+        tol = np.maximum(1e-3 * np.abs(ref64), terms * 2.0 ** -24 * ab)
+        assert (np.abs(sc - ref64) <= tol).all()
+        assert np.array_equal(idx[t][None], oracle.select(sc, k, nthreads=8))
+        ref_q = oracle.map_requests(idx[t], H, N, e2c, cfg.Nc, rep, cfg.D, weight, cap=cap, nthreads=8)
+        for got, ref in zip((q_off[t], q_clu[t], q_load[t]), ref_q):
+            assert np.array_equal(got.cpu().numpy(), ref)
+
+    # co-activation properties, on the device (torch is only the container here)
+    for h in range(H):
+        c = Cm[h]
+        counts = torch.bincount(idx_all[:, h].reshape(-1).long(), minlength=N).to(torch.int64)
+        assert torch.equal(torch.diagonal(c).to(torch.int64), counts)
+        rs = torch.zeros(N, dtype=torch.int64, device="cuda")
+        step = max(1, (1 << 27) // N)
+        for r0 in range(0, N, step):                          # symmetric, block by block
+            blk = c[r0:r0 + step]
+            assert torch.equal(blk, c[:, r0:r0 + step].t())
+            rs[r0:r0 + step] = blk.sum(dim=1, dtype=torch.int64)
+        assert torch.equal(rs, k * counts)
+        assert int(rs.sum()) == T * k * k
+        # sampled entries: half among the frequently selected entries, half anywhere
+        hot = torch.argsort(counts, descending=True)[:256].cpu().numpy()
+        ii = np.concatenate([rng.choice(hot, 24), rng.integers(0, N, 24)])
+        jj = np.concatenate([rng.choice(hot, 24), rng.integers(0, N, 24)])
+        sel_h = idx[:, h, :]
+        member = {int(e): (sel_h == e).any(axis=1) for e in set(ii.tolist()) | set(jj.tolist())}
+        got = c[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()].cpu().numpy()
+        want = np.array([int((member[int(a)] & member[int(b)]).sum()) for a, b in zip(ii, jj)])
+        assert np.array_equal(got, want)
+    del Cm
+    torch.cuda.empty_cache()
+
+
+def test_long_context_full_size(sw):
+    """The benchmark's workload: 8 heads x 8192 page summaries, 4096 steps, k = 256, C 8 x 8192^2."""
+    cfg = W.CONFIGS["long_128k"]
+    rng = np.random.default_rng(11)
+    run_full(sw, cfg, rng.choice(cfg.T, 6, replace=False), rng)
+
+
+def test_llama_layer_full_size(sw):
+    cfg = W.CONFIGS["llama8b_32k"]
+    rng = np.random.default_rng(12)
+    run_full(sw, cfg, rng.choice(cfg.T, 6, replace=False), rng)
+
+
+def test_token_stress_full_size(sw):
+    """One head, 65536 token keys, 8192 steps, k = 1024: the 65536 x 65536 int32 co-activation build (16 GiB)."""
+    cfg = W.CONFIGS["token_stress"]
+    rng = np.random.default_rng(13)
+    run_full(sw, cfg, rng.choice(cfg.T, 3, replace=False), rng)
+
+
+def test_select_rows_longer_than_the_register_path(sw):
+    """More than 65536 entries per row takes the streaming select kernel."""
+    cfg = W.CONFIGS["tiny"].scaled(N=70000, k=300, T=1, d=8)
+    K = W.keys(cfg)
+    q = W.queries(cfg, 0, 1)[0]
+    idx, sc = sw.score_select("token", dev(K), dev(q), cfg.k, want_scores=True)
+    sc = sc.cpu().numpy()
+    assert np.array_equal(idx.cpu().numpy(), oracle.select(sc, cfg.k))
+    _, ref64, ab = oracle.score("token", K, q)
+    assert (np.abs(sc - ref64) <= np.maximum(1e-3 * np.abs(ref64), 8 * 2.0 ** -24 * ab)).all()
+
+
+def test_drifting_batch_decayed_windows_scaled(sw):
+    """Batched, grouped-query scoring with a decayed co-activation update per window (the drifting
+    workload at reduced size: 8 streams, 4 query heads per KV head, 5 windows of 16 steps)."""
+    cfg = W.CONFIGS["drift_batch"].scaled(N=384, B=8, T=80, k=24, phase_len=32, decay_window=16, M=64, Nc=64)
+    K = W.keys(cfg)
+    Kd = dev(K)
+    e2c, weight, rep = W.cluster_tables(cfg)
+    e2c_d, w_d, rep_d = dev(e2c), dev(weight), dev(rep)
+    Cd = torch.zeros((cfg.H, cfg.N, cfg.N), dtype=torch.int32, device="cuda")
+    Cref = np.zeros((cfg.H, cfg.N, cfg.N), np.int32)
+    for w0 in range(0, cfg.T, cfg.decay_window):
+        qs = W.queries(cfg, w0, w0 + cfg.decay_window)
+        rows = cfg.decay_window * cfg.B
+        idx_win = torch.empty((rows, cfg.H, cfg.k), dtype=torch.int32, device="cuda")
+        for t in range(cfg.decay_window):
+            out_idx = idx_win[t * cfg.B:(t + 1) * cfg.B]
+            _, sc = sw.score_select("page", Kd, dev(qs[t]), cfg.k, G=cfg.G, out_idx=out_idx, want_scores=True)
+            sel = out_idx.permute(1, 0, 2).reshape(cfg.H, cfg.B * cfg.k).contiguous()     # streams of a step merged per head
+            got = sw.map_requests(sel, cfg.H, cfg.N, e2c_d, cfg.Nc, rep_d, cfg.D, w_d)
+            if t % 5 == 0:
+                sc_h = sc.cpu().numpy()
+                _, ref64, ab = oracle.score("page", K, qs[t], G=cfg.G, nthreads=8)
+                tol = np.maximum(1e-3 * np.abs(ref64), 2 * cfg.d * cfg.G * 2.0 ** -24 * ab)
+                assert (np.abs(sc_h - ref64) <= tol).all()
+                assert np.array_equal(out_idx.cpu().numpy(), oracle.select(sc_h, cfg.k, nthreads=8))
+                ref = oracle.map_requests(sel.cpu().numpy(), cfg.H, cfg.N, e2c, cfg.Nc, rep, cfg.D, weight, nthreads=8)
+                for g_, r_ in zip(got, ref):
+                    assert np.array_equal(g_.cpu().numpy(), r_)
+        decay = 65536 if w0 == 0 else cfg.decay_q16
+        sw.coact_accumulate(idx_win, cfg.N, Cd, decay_q16=decay)
+        oracle.coact_update(idx_win.cpu().numpy(), cfg.N, Cref, decay, nthreads=8)
+        assert np.array_equal(Cd.cpu().numpy(), Cref)
+    assert np.array_equal(Cref, np.transpose(Cref, (0, 2, 1)))
+    assert sw.device_status() == 0
