@@ -24,6 +24,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 INT8_MFMA_PEAK_TOPS = 5000.0
+# HBM bytes per score_kernel launch from FETCH_SIZE / WRITE_SIZE counter runs, calibrated on plain copies
+# (profiles/score_kernel_long_128k_hbm_traffic.txt).  Valid for the kernel as profiled; None for other workloads.
+SCORE_KERNEL_HBM_TRAFFIC = {"long_128k": 33854000}
 
 
 def main():
@@ -170,7 +173,7 @@ def main():
                    "graph_replay": not args.no_graph},
         "roofline": {"kernel": "score_kernel (one decode step's sweep of the page summaries)", "bound": "hbm",
                      "achieved": round(score_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(score_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(score_gbs / HBM_PEAK_GBS, 4), "traffic": SCORE_KERNEL_HBM_TRAFFIC.get(cfg.name),
                      "bytes_per_launch": sweep_bytes, "us_per_launch": round(score_us, 3)},
         "roofline_coact": {"kernel": "coact_syrk_kernel", "bound": "mfma", "achieved": round(coact_tops, 1),
                            "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(coact_tops / INT8_MFMA_PEAK_TOPS, 4),
