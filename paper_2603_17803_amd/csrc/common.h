@@ -20,6 +20,8 @@ struct swarm_ctx {
     // scratch, grown on demand
     float* scores = nullptr;       // [B][H][N] when the caller passes no score buffer
     size_t scores_bytes = 0;
+    uint16_t* weights = nullptr;   // folded query weights of the batched scorer: bf16 hi then lo, each [B][H][L]
+    size_t weights_bytes = 0;
     int8_t* trace = nullptr;       // A^T, int8 [H][Npad][Tpad]
     size_t trace_bytes = 0;
     uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
@@ -48,6 +50,7 @@ struct swarm_ctx {
 swarm_status swarm_grow(swarm_ctx* ctx, void** buf, size_t* have, size_t bytes);
 
 // --- kernel launchers (each enqueues on ctx->stream and reports launch errors) ---------------
+constexpr int SWARM_BATCHED_MIN_STREAMS = 8;   // from this many streams on, scoring runs as a GEMM on the matrix cores
 swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores);
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx);
 swarm_status launch_trace_scatter(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N,

@@ -150,6 +150,118 @@ void dispatch(hipStream_t st, const swarm_keys* keys, const void* q, int B, floa
     return launch_one<1, 1, PAGE>(st, keys, q, B, scores, CH);
 }
 
+
+// ---- many streams per call: the sweep becomes a small GEMM on the bf16 matrix cores -------------
+//
+// s[b][n] = sum_c w[b][c] * row[n][c] with w the (folded) query weights of stream b.  The weights
+// are sums of up to G bf16 values, so they are carried as a bf16 pair hi + lo (relative error
+// 2^-17, far inside the score tolerance) and every 16-wide k-step issues two MFMAs per tile.
+// Each wave owns 32 entries x up to 128 streams; entries are read from memory once per 128 streams.
+// The contraction index is free to be visited in any order as long as both operands agree: lane
+// half 0 walks the first half of the row, lane half 1 the second half, 8 values per k-step, so
+// every lane reads one contiguous run of its row.
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;      // NaN stays NaN
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// whi/wlo: bf16 [B][H][L], L = d (token) or 2d (page: min-half weights, then max-half weights)
+template <bool PAGE>
+__global__ void fold_weights_kernel(const uint16_t* __restrict__ q, int G, int d, int L, int64_t total,
+                                    uint16_t* __restrict__ whi, uint16_t* __restrict__ wlo) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % L);
+    const int64_t bh = i / L;
+    const bool max_half = PAGE && c >= d;
+    const int ch = max_half ? c - d : c;
+    float w = 0.f;
+    for (int g = 0; g < G; ++g) {
+        float x = bf16_lo(q[(bh * G + g) * d + ch]);
+        if (PAGE) x = max_half ? fmaxf(x, 0.f) : fminf(x, 0.f);
+        w += x;
+    }
+    const uint32_t hi = f32_to_bf16_rne(w);
+    const float rest = w - bf16_lo(hi);
+    whi[i] = (uint16_t)hi;
+    wlo[i] = (uint16_t)f32_to_bf16_rne(rest);
+}
+
+constexpr int SB_TILES = 4;     // stream tiles of 32 per wave
+
+// grid (ceil(N / 128), H, ceil(B / 128)); 4 waves, wave w scores entries [128 x + 32 w, +32).
+// KSTEPS = L / 16 k-steps, each consuming 8 values from each half of the row.
+template <int KSTEPS>
+__global__ __launch_bounds__(256) void score_batched_kernel(const u32x4* __restrict__ rows, const u32x4* __restrict__ whi,
+                                                            const u32x4* __restrict__ wlo, float* __restrict__ out,
+                                                            int N, int H, int B) {
+    constexpr int CH = KSTEPS * 2;               // 16-byte chunks per row (and per weight vector)
+    const int h = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r32 = lane & 31, hf = lane >> 5;
+    const int n0 = blockIdx.x * 128 + wave * 32;
+    const int b0 = blockIdx.z * (32 * SB_TILES);
+    const int n = min(n0 + r32, N - 1);                                     // clamped; stores are masked
+    const u32x4* arow = rows + ((size_t)h * N + n) * CH + hf * KSTEPS;
+
+    u32x4 a[KSTEPS];
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) a[s] = __builtin_nontemporal_load(arow + s);
+
+    f32x16 acc[SB_TILES];
+#pragma unroll
+    for (int t = 0; t < SB_TILES; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    const int ntiles = min(SB_TILES, (B - b0 + 31) / 32);
+#pragma unroll
+    for (int t = 0; t < SB_TILES; ++t) {
+        if (t < ntiles) {
+            const int b = min(b0 + t * 32 + r32, B - 1);
+            const u32x4* wh = whi + ((size_t)b * H + h) * CH + hf * KSTEPS;
+            const u32x4* wl = wlo + ((size_t)b * H + h) * CH + hf * KSTEPS;
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const u32x4 bh_ = wh[s], bl_ = wl[s];
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[s]), __builtin_bit_cast(bf16x8, bh_), acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[s]), __builtin_bit_cast(bf16x8, bl_), acc[t], 0, 0, 0);
+            }
+        }
+    }
+    // result tile: lane l, register r -> stream b0 + 32 t + l%32, entry n0 + 8*(r/4) + 4*(l/32) + r%4
+#pragma unroll
+    for (int t = 0; t < SB_TILES; ++t) {
+        const int b = b0 + t * 32 + r32;
+        if (t < ntiles && b < B) {
+            float* o = out + ((size_t)b * H + h) * N;
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int nn = n0 + rq * 8 + hf * 4;
+                if (nn + 3 < N && ((reinterpret_cast<uintptr_t>(o + nn) & 15) == 0)) {
+                    *reinterpret_cast<float4*>(o + nn) = make_float4(acc[t][rq * 4], acc[t][rq * 4 + 1], acc[t][rq * 4 + 2], acc[t][rq * 4 + 3]);
+                } else {
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        if (nn + rr < N) o[nn + rr] = acc[t][rq * 4 + rr];
+                }
+            }
+        }
+    }
+}
+
+template <int KSTEPS>
+void launch_batched(hipStream_t st, const swarm_keys* keys, const uint16_t* whi, const uint16_t* wlo, int B, float* scores) {
+    dim3 grid((keys->N + 127) / 128, keys->H, (B + 32 * SB_TILES - 1) / (32 * SB_TILES));
+    hipLaunchKernelGGL((score_batched_kernel<KSTEPS>), grid, dim3(256), 0, st, static_cast<const u32x4*>(keys->data),
+                       reinterpret_cast<const u32x4*>(whi), reinterpret_cast<const u32x4*>(wlo), scores, keys->N, keys->H, B);
+}
+
 }  // namespace
 
 swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores) {
@@ -158,7 +270,29 @@ swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q,
         return SWARM_EINVAL;
     }
     const bool page = keys->kind == SWARM_KEYS_PAGE_MINMAX;
-    const int CH = (page ? 2 * keys->d : keys->d) / 8;
+    const int L = page ? 2 * keys->d : keys->d;
+    const int CH = L / 8;
+    // many streams: matrix-core path (row lengths of 128 and 256 values, i.e. d = 128 or page rows of d = 64 / 128)
+    if (B >= SWARM_BATCHED_MIN_STREAMS && (L == 128 || L == 256) && keys->H <= 65535) {
+        const size_t wbytes = (size_t)B * keys->H * L * sizeof(uint16_t);
+        swarm_status st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->weights), &ctx->weights_bytes, 2 * wbytes);
+        if (st != SWARM_OK) return st;
+        uint16_t* whi = ctx->weights;
+        uint16_t* wlo = ctx->weights + (size_t)B * keys->H * L;
+        const int64_t total = (int64_t)B * keys->H * L;
+        const unsigned blocks = (unsigned)((total + 255) / 256);
+        if (page)
+            hipLaunchKernelGGL(fold_weights_kernel<true>, dim3(blocks), dim3(256), 0, ctx->stream, static_cast<const uint16_t*>(q),
+                               keys->G, keys->d, L, total, whi, wlo);
+        else
+            hipLaunchKernelGGL(fold_weights_kernel<false>, dim3(blocks), dim3(256), 0, ctx->stream, static_cast<const uint16_t*>(q),
+                               keys->G, keys->d, L, total, whi, wlo);
+        st = swarm_check_launch(ctx, "fold_weights_kernel");
+        if (st != SWARM_OK) return st;
+        if (L == 256) launch_batched<16>(ctx->stream, keys, whi, wlo, B, scores);
+        else launch_batched<8>(ctx->stream, keys, whi, wlo, B, scores);
+        return swarm_check_launch(ctx, "score_batched_kernel");
+    }
     if (page) dispatch<true>(ctx->stream, keys, q, B, scores, CH);
     else dispatch<false>(ctx->stream, keys, q, B, scores, CH);
     return swarm_check_launch(ctx, "score_kernel");

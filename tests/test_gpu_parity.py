@@ -90,6 +90,10 @@ CASES = [
     W.CONFIGS["token_stress"].scaled(N=16384, k=1024, T=1),                  # multi-chunk select
     W.CONFIGS["drift_batch"].scaled(N=300, B=5, T=1, k=17),                  # streams x grouped query heads
     W.CONFIGS["drift_batch"].scaled(N=2048, B=3, G=2, H=2, T=1, unit="token", page_size=1),
+    W.CONFIGS["drift_batch"].scaled(N=2048, T=1),                            # 64 streams x 4 query heads: matrix-core scorer
+    W.CONFIGS["drift_batch"].scaled(N=300 + 7, B=40, T=1, k=9, H=3),         # ragged entries and streams
+    W.CONFIGS["drift_batch"].scaled(N=515, B=9, G=2, H=2, T=1, k=33, unit="token", page_size=1),   # token rows, batched
+    W.CONFIGS["drift_batch"].scaled(N=200, B=130, G=1, H=1, T=1, k=4),       # more than one block of streams
     W.CONFIGS["tiny"].scaled(d=8, N=100, k=5, T=1),                          # smallest head dimension
     W.CONFIGS["tiny"].scaled(d=24, N=100, k=5, T=1),                         # row not a power of two of chunks
     W.CONFIGS["llama8b_32k"].scaled(d=320, N=100, k=5, T=1, H=2),            # page row longer than one wave-load
