@@ -44,24 +44,13 @@ __global__ void check_distinct_kernel(const int32_t* __restrict__ idx, int k, ui
     if (dup) atomicOr(dev_flags, SWARM_DEV_DUP_ENTRY);
 }
 
-// floor((old * decay_q16 + 2^15) / 2^16) with a 64-bit product, spelled in 32-bit halves
-// (decay_q16 <= 65536, so the result fits int32).
+// floor((old * decay_q16 + 2^15) / 2^16) with a 64-bit intermediate (one 64-bit multiply-add and a
+// funnel shift; decay_q16 <= 65536, so the result fits int32).
 __device__ __forceinline__ int32_t decayed(int32_t old, uint32_t decay_q16) {
-    const uint32_t lo = (uint32_t)old * decay_q16;
-    const int32_t hi = __mulhi(old, (int32_t)decay_q16);
-    const uint32_t lo2 = lo + 32768u;
-    const int32_t hi2 = hi + (lo2 < lo ? 1 : 0);
-    return (int32_t)(((uint32_t)hi2 << 16) | (lo2 >> 16));
+    return (int32_t)(((int64_t)old * (int64_t)decay_q16 + 32768) >> 16);
 }
 
 // MODE 0: C = acc.  MODE 1: C += acc.  MODE 2: C = decayed(C) + acc.
-template <int MODE>
-__device__ __forceinline__ void store_c(int32_t* p, int32_t acc, uint32_t decay_q16) {
-    if (MODE == 0) *p = acc;
-    else if (MODE == 1) *p += acc;
-    else *p = decayed(*p, decay_q16) + acc;
-}
-
 constexpr int TILE = 256;          // C tile edge per workgroup
 constexpr int KC = 128;            // contraction bytes staged per iteration (one cache line per trace row)
 constexpr int STAGE_BYTES = TILE * KC;                 // one operand tile in LDS
@@ -82,7 +71,7 @@ __device__ __forceinline__ int lds_off(int row, int chunk) { return row * KC + (
 // and, together with the fragment reads, saturate the LDS port.)
 // Workgroups are numbered so that the eight L2 slices (one per XCD, workgroups are dealt to them
 // round-robin) each walk a contiguous run of the tile schedule.
-template <int MODE>
+template <int MODE, bool VEC>
 __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __restrict__ At, int N, int Npad, int64_t Tpad,
                                                             int32_t* __restrict__ C, uint32_t decay_q16, int nt,
                                                             int tiles_per_head, int total_tiles, int per_xcd,
@@ -232,13 +221,19 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
         chunk_body(c + 1, 1);
     }
 
-    // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4, i.e. a lane
-    // holds 4 consecutive rows of one column per register quadruple.  All of C leaves in 16-byte
-    // stores that cover whole 128-byte lines (streaming stores when C is not read back); the
-    // re-layout for both the direct and the mirrored tile goes through the (now idle) LDS.
+    // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4.  One
+    // register of a wave is therefore two whole 128-byte lines of the direct tile (32 consecutive
+    // columns of two rows): the direct tile leaves straight from the accumulators in 4-byte stores,
+    // with nothing to wait for.  In the mirrored tile a lane's register quadruple is 16 contiguous
+    // bytes but the lines are spread over lanes, so that tile is re-laid out through the (now idle)
+    // LDS and leaves in 16-byte stores that cover whole lines.  Streaming stores when C is not read.
     int32_t* Ch = C + (size_t)h * N * N;
     const int col_in = lane & 31, half = lane >> 5, row_in = half * 4;
-    const bool vec_ok = (N & 3) == 0;
+    auto rmw1 = [&](int32_t* p, int32_t v) {
+        if (MODE == 0) __builtin_nontemporal_store(v, p);
+        else if (MODE == 1) *p += v;
+        else *p = decayed(*p, decay_q16) + v;
+    };
     auto rmw4 = [&](int32_t* p, v4i v) {
         if (MODE == 0) {
             __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(p));
@@ -252,67 +247,50 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
             *reinterpret_cast<v4i*>(p) = v;
         }
     };
-    if (vec_ok) {
-        // One block of 32 columns (j) x 128 rows at a time: the wave parks it in its own slice of the
-        // idle LDS as [column][row] and reads it back twice, once along rows of that layout for the
-        // mirrored tile and once across them (four 4-byte reads -> 4 consecutive columns of one row)
-        // for the direct tile.
-        constexpr int TROW = 512 + 16;                                   // padded: 16-byte accesses of 16 lanes hit 16 bank groups
-        int8_t* tbuf = lds + wave * (32 * TROW);
-        const int gi_base = ti * TILE + wy * 128;
-        const int drow = lane >> 3, dq = lane & 7;                       // direct read-out: row within a group of 8, group of 4 columns
+    constexpr int TROW = 512 + 16;                                       // padded: 16-byte accesses of 16 lanes hit 16 bank groups
+    int8_t* tbuf = lds + wave * (32 * TROW);
+    const int gi_base = ti * TILE + wy * 128;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 4; ++j) {
+        const int gj_base = tj * TILE + wx * 128 + j * 32;
+        // park the 128 x 32 block as [column][row] for the mirrored tile; the LDS executes one wave's
+        // accesses in order, so the block of the previous j has been read by then
+        if (VEC && !diag) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
                     const v4i v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
                     *reinterpret_cast<v4i*>(tbuf + col_in * TROW + (i * 32 + rq * 8 + row_in) * 4) = v;
-                    if (rq == 3) asm volatile("" ::: "memory");
                 }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            const int gj_base = tj * TILE + wx * 128 + j * 32;
-            // direct tile: rows gi_base + 0..127, columns gj_base + 0..31
+        }
+        // direct tile: rows gi_base + 0..127, columns gj_base + 0..31
+        const int gjc = gj_base + col_in;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int gi = gi_base + i * 32 + (r >> 2) * 8 + row_in + (r & 3);
+                if (gi < N && gjc < N) {
+                    rmw1(Ch + (size_t)gi * N + gjc, acc[i][j][r]);
+                    if (!VEC && !diag) rmw1(Ch + (size_t)gjc * N + gi, acc[i][j][r]);    // rows of C not 16-byte aligned: element-wise mirror
+                }
+            }
+            if (MODE != 0) asm volatile("" ::: "memory");
+        }
+        // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..127
+        if (VEC && !diag) {
 #pragma unroll
             for (int sidx = 0; sidx < 16; ++sidx) {
-                const int r = sidx * 8 + drow;
-                const int8_t* src = tbuf + (dq * 4) * TROW + r * 4;
-                const v4i v = {*reinterpret_cast<const int*>(src), *reinterpret_cast<const int*>(src + TROW),
-                               *reinterpret_cast<const int*>(src + 2 * TROW), *reinterpret_cast<const int*>(src + 3 * TROW)};
-                const int gi = gi_base + r, gj = gj_base + dq * 4;
-                if (gi < N && gj < N) rmw4(Ch + (size_t)gi * N + gj, v);
-                if ((sidx & 3) == 3) asm volatile("" ::: "memory");
-            }
-            // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..127
-            if (!diag) {
-#pragma unroll
-                for (int sidx = 0; sidx < 16; ++sidx) {
-                    const int r = 2 * sidx + half;
-                    const v4i v = *reinterpret_cast<const v4i*>(tbuf + r * TROW + col_in * 16);
-                    const int gj = gj_base + r, gi = gi_base + col_in * 4;
-                    if (gj < N && gi < N) rmw4(Ch + (size_t)gj * N + gi, v);
-                    if ((sidx & 3) == 3) asm volatile("" ::: "memory");
-                }
+                const int r = 2 * sidx + half;
+                const v4i v = *reinterpret_cast<const v4i*>(tbuf + r * TROW + col_in * 16);
+                const int gj = gj_base + r, gi = gi_base + col_in * 4;
+                if (gj < N && gi < N) rmw4(Ch + (size_t)gj * N + gi, v);
+                if ((sidx & 7) == 7) asm volatile("" ::: "memory");
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int gj = tj * TILE + wx * 128 + j * 32 + col_in;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int gi = ti * TILE + wy * 128 + i * 32 + (r >> 2) * 8 + row_in + (r & 3);
-                    if (gi < N && gj < N) {
-                        store_c<MODE>(Ch + (size_t)gi * N + gj, acc[i][j][r], decay_q16);
-                        if (!diag) store_c<MODE>(Ch + (size_t)gj * N + gi, acc[i][j][r], decay_q16);
-                    }
-                }
-                if (MODE != 0) asm volatile("" ::: "memory");
-            }
     }
 }
 
@@ -384,24 +362,29 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int64_t T
     swarm_status st = ensure_tile_order(ctx, nt);
     if (st != SWARM_OK) return st;
     const int per_xcd = (int)((total + 7) / 8);
+    const int mode = decay_q16 == 0u ? 0 : decay_q16 == 65536u ? 1 : 2;
+    const bool vec = (N & 3) == 0;
+    using kernel_t = void (*)(const int8_t*, int, int, int64_t, int32_t*, uint32_t, int, int, int, int, const int32_t*);
+    static const kernel_t kernels[3][2] = {{coact_syrk_kernel<0, false>, coact_syrk_kernel<0, true>},
+                                           {coact_syrk_kernel<1, false>, coact_syrk_kernel<1, true>},
+                                           {coact_syrk_kernel<2, false>, coact_syrk_kernel<2, true>}};
     static bool lds_opt_in = false;
     if (!lds_opt_in) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&coact_syrk_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize, SYRK_LDS_BYTES);
-        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&coact_syrk_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, SYRK_LDS_BYTES);
-        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&coact_syrk_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, SYRK_LDS_BYTES);
-        if (e != hipSuccess) {
-            snprintf(ctx->err, sizeof(ctx->err), "coact: cannot opt in to %d bytes of LDS: %s", SYRK_LDS_BYTES, hipGetErrorString(e));
-            return SWARM_EHIP;
-        }
+        for (int m = 0; m < 3; ++m)
+            for (int v = 0; v < 2; ++v) {
+                const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[m][v]),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, SYRK_LDS_BYTES);
+                if (e != hipSuccess) {
+                    snprintf(ctx->err, sizeof(ctx->err), "coact: cannot opt in to %d bytes of LDS: %s", SYRK_LDS_BYTES, hipGetErrorString(e));
+                    return SWARM_EHIP;
+                }
+            }
         lds_opt_in = true;
     }
     dim3 grid((unsigned)(per_xcd * 8)), block(256);
     const int tph = (int)tiles_per_head, tot = (int)total;
-    if (decay_q16 == 0u)
-        hipLaunchKernelGGL(coact_syrk_kernel<0>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order);
-    else if (decay_q16 == 65536u)
-        hipLaunchKernelGGL(coact_syrk_kernel<1>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order);
-    else
-        hipLaunchKernelGGL(coact_syrk_kernel<2>, grid, block, SYRK_LDS_BYTES, ctx->stream, ctx->trace, N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd, ctx->tile_order);
+    hipLaunchKernelGGL(kernels[mode][vec ? 1 : 0], grid, block, SYRK_LDS_BYTES, ctx->stream,
+                       static_cast<const int8_t*>(ctx->trace), N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd,
+                       static_cast<const int32_t*>(ctx->tile_order));
     return swarm_check_launch(ctx, "coact_syrk_kernel");
 }
