@@ -8,7 +8,10 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswarm.so")
 SOURCES = ["api.hip", "score.hip", "select.hip", "coact.hip", "mapper.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the fully unrolled epilogues of the co-activation kernel exceed the default budget of "#pragma unroll";
+         # a loop left rolled there indexes the accumulator array dynamically and sends it to scratch memory
+         "-mllvm", "-pragma-unroll-threshold=200000"]
 
 
 def build(verbose: bool = False) -> str:

@@ -154,14 +154,13 @@ swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t 
     if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "coact_accumulate: C must be 16-byte aligned");
     if (flags & ~SWARM_CHECK_IDX) SWARM_REJECT(ctx, "coact_accumulate: unknown flags 0x%x", flags);
 
-    const int64_t Tpad = (rows + 255) / 256 * 256;   // contraction length, zero-padded to two K chunks
-    const int Npad = (N + 255) / 256 * 256;          // rows of A^T, zero-padded to the C tile
-    swarm_status st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->trace), &ctx->trace_bytes,
-                                 (size_t)H * Npad * Tpad);
+    const int nchunks = (int)((rows + 511) / 512 * 4);   // contraction in chunks of 128 trace rows, zero-padded to a multiple of 4 chunks
+    const int Npad = (N + 255) / 256 * 256;               // entries, zero-padded to the C tile
+    swarm_status st = swarm_grow(ctx, &ctx->trace, &ctx->trace_bytes, (size_t)H * nchunks * Npad * 16);
     if (st != SWARM_OK) return st;
-    st = launch_trace_scatter(ctx, idx, rows, H, k, N, Npad, Tpad, flags);
+    st = launch_trace_build(ctx, idx, rows, H, k, N, Npad, nchunks, flags);
     if (st != SWARM_OK) return st;
-    return launch_coact_syrk(ctx, H, N, Npad, Tpad, C, decay_q16);
+    return launch_coact_syrk(ctx, H, N, Npad, nchunks, C, decay_q16);
 }
 
 swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int32_t S, int32_t H, int32_t N,

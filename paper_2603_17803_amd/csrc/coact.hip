@@ -1,12 +1,19 @@
-// Trace scatter and co-activation accumulation (Section 5.1, Step 1): C[i][j] = number of trace
+// Activation trace and co-activation accumulation (Section 5.1, Step 1): C[i][j] = number of trace
 // rows in which entries i and j are both activated, i.e. C = A^T A for the binary trace A.
 //
-// The trace is kept entry-major, At[h][n][t] (int8 0/1), so that both operands of the product are
-// rows of the same matrix with the contraction index t contiguous: C[i][j] = <At[i], At[j]>.
-// The product runs on the int8 matrix cores (v_mfma_i32_32x32x32_i8) with exact int32
-// accumulation.  C is symmetric, so only tiles on or above the diagonal are computed and each
-// off-diagonal tile is stored twice (once transposed).
+// The trace is binary, so it is kept in memory as bits: for every head and every run of 128 trace
+// rows ("chunk") one 16-byte word per entry, bits[h][chunk][entry], bit s = "entry activated in trace
+// row 128*chunk + s".  Both operands of the product are entry panels of this one array.  On the way
+// to the matrix cores a workgroup expands the bits of its two 256-entry panels to int8 0/1 rows in
+// LDS (contraction index contiguous), and the product runs on v_mfma_i32_32x32x32_i8 with exact
+// int32 accumulation.  Feeding int8 from memory instead would make every workgroup pull
+// 512 bytes per contraction byte-step through the L2, which at this tile size is within 15% of
+// the L2's bandwidth at full matrix-core rate; the bit form needs an eighth of it.
+// C is symmetric, so only tiles on or above the diagonal are computed and each off-diagonal tile is
+// stored twice (once transposed).
 #include <stdlib.h>
+
+#include <type_traits>
 
 #include "common.h"
 
@@ -15,22 +22,36 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-__global__ void fill_zero_kernel(uint4* __restrict__ p, size_t n16) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
-}
+constexpr int TRACE_SPAN = 8192;   // entries one trace-building workgroup covers (128 KiB of LDS)
 
-// One thread per selected entry: At[h][e][row] = 1.
-__global__ void trace_scatter_kernel(const int32_t* __restrict__ idx, int64_t total, int H, int k, int N, int Npad,
-                                     int64_t Tpad, int8_t* __restrict__ At, uint32_t* __restrict__ dev_flags) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total) return;
-    const int64_t rh = i / k;
-    const int64_t row = rh / H;
-    const int h = (int)(rh % H);
-    const int32_t e = idx[i];
-    if (e < 0 || e >= N) { atomicOr(dev_flags, SWARM_DEV_BAD_ENTRY); return; }
-    At[((size_t)h * Npad + e) * Tpad + row] = 1;
+// One workgroup per (chunk, head, span of entries): the 128 selections of the chunk are merged into
+// an LDS image of the chunk's bit words, which then leaves as one contiguous, fully written block
+// (no separate clearing pass, no global atomics).
+__global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __restrict__ idx, int64_t rows, int H, int k, int N,
+                                                           int Npad, int nchunks, uint4* __restrict__ bits,
+                                                           uint32_t* __restrict__ dev_flags) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t words[];          // [span][4]
+    const int chunk = blockIdx.x, h = blockIdx.y;
+    const int e0 = blockIdx.z * TRACE_SPAN;
+    const int span = min(TRACE_SPAN, Npad - e0);
+    for (int i = threadIdx.x; i < span * 4; i += blockDim.x) words[i] = 0u;
+    __syncthreads();
+    const int64_t row0 = (int64_t)chunk * 128;
+    const int nrows = (int)min((int64_t)128, rows - row0);                       // <= 0 for a chunk of pure padding
+    bool bad = false;
+    for (int s = 0; s < nrows; ++s) {
+        const int32_t* sel = idx + ((row0 + s) * H + h) * (int64_t)k;
+        for (int j = threadIdx.x; j < k; j += blockDim.x) {
+            const int32_t e = sel[j];
+            if (e < 0 || e >= N) bad = true;
+            else if (e >= e0 && e < e0 + span) atomicOr(&words[(e - e0) * 4 + (s >> 5)], 1u << (s & 31));
+        }
+    }
+    if (bad && blockIdx.z == 0) atomicOr(dev_flags, SWARM_DEV_BAD_ENTRY);
+    __syncthreads();
+    uint4* out = bits + ((size_t)h * nchunks + chunk) * Npad + e0;
+    const uint4* src = reinterpret_cast<const uint4*>(words);
+    for (int i = threadIdx.x; i < span; i += blockDim.x) out[i] = src[i];
 }
 
 // Optional validation: flags a repeated entry inside one (row, head) selection.
@@ -56,24 +77,30 @@ constexpr int KC = 128;            // contraction bytes staged per iteration (on
 constexpr int STAGE_BYTES = TILE * KC;                 // one operand tile in LDS
 constexpr int SYRK_LDS_BYTES = 2 * 2 * STAGE_BYTES;    // double buffer x (A, B) = 128 KiB
 
-// 16-byte chunk c of row r lives at chunk position c ^ ((r >> 1) & 7).  The LDS has 64 four-byte banks,
-// so a 16-byte access is served 16 lanes at a time; the 16 rows such a group touches when it reads one
-// logical chunk then fall into 16 different 16-byte bank groups (row parity picks the half, the
-// swizzled chunk the slot), and a 128-byte row written by 8 lanes stays one contiguous line.
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * KC + ((chunk ^ ((row >> 1) & 7)) << 4); }
+// Operand rows in LDS are 128 bytes; 16-byte piece c of row r lives at slot c ^ swz(r).  Measured on
+// gfx950: a 16-byte LDS read is served 16 consecutive lanes at a time across 64 four-byte banks, a
+// 16-byte write 8 consecutive lanes at a time with only the slot (address bits 4..6) telling lanes
+// apart.  Fragment reads take one piece of 16 consecutive rows, expansion writes one piece of 8
+// consecutive rows (thread = row): swz must differ on rows of equal parity within 16 rows (reads:
+// parity picks the bank half) and on all rows within 8 (writes).  swz(r) = bits 1..2 of r, with bit 2
+// = bit 3 of r xor bit 0 of r, does both.
+__device__ __forceinline__ int lds_swz(int row) { return ((row >> 1) & 3) | ((((row >> 3) ^ row) & 1) << 2); }
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * KC + ((chunk ^ lds_swz(row)) << 4); }
+
+// Expansion of trace bits to bytes of 0/1, four at a time: a nibble times (1 + 2^7 + 2^14 + 2^21) puts
+// bit b at bit 8b (the four shifted copies do not overlap, so nothing carries); a mask drops the rest.
 
 // C tile of 256 x 256 per workgroup; 4 waves in a 2 x 2 arrangement, each owning 128 x 128 =
-// 4 x 4 MFMA tiles (256 accumulator registers).  The contraction runs in 128-byte chunks (four
-// 32-byte MFMA k-steps) through a two-deep LDS ring fed from registers: chunk c+2 is in flight from
-// memory into registers, chunk c+1 is being written into the idle LDS buffer, chunk c feeds the
-// matrix cores; operand fragments of k-step s+1 are read from LDS while the 16 MFMAs of k-step s
-// run.  (Direct-to-LDS loads were measured slower here: their LDS writes arrive 64 bytes per clock
-// and, together with the fragment reads, saturate the LDS port.)
+// 4 x 4 MFMA tiles (256 accumulator registers).  The contraction runs in chunks of 128 trace rows
+// (four 32-byte MFMA k-steps) through a two-deep LDS ring: thread t owns entry t of both panels; the
+// 16-byte bit words of chunk c+2 and c+3 are in flight from memory, the words of chunk c+1 are
+// being expanded and written into the idle LDS buffer, chunk c feeds the matrix cores; operand
+// fragments of k-step s+1 are read from LDS while the 16 MFMAs of k-step s run.
 // Workgroups are numbered so that the eight L2 slices (one per XCD, workgroups are dealt to them
 // round-robin) each walk a contiguous run of the tile schedule.
 template <int MODE, bool VEC>
-__global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __restrict__ At, int N, int Npad, int64_t Tpad,
-                                                            int32_t* __restrict__ C, uint32_t decay_q16, int nt,
+__global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nchunks,
+                                                            int32_t* __restrict__ C, uint32_t decay_q16,
                                                             int tiles_per_head, int total_tiles, int per_xcd,
                                                             const int32_t* __restrict__ tile_order) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
@@ -89,34 +116,31 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wy = wave >> 1, wx = wave & 1;
 
-    // memory -> registers -> LDS: thread t moves 16-byte chunk t%8 of rows t/8 + 32*i, i = 0..7, of both
-    // operand tiles (8 lanes cover one 128-byte line of a trace row).  The registers hold chunk c+2
-    // while chunk c+1 sits in the idle LDS buffer and chunk c feeds the matrix cores.
-    const int srow = tid >> 3, schunk = tid & 7;
-    const int8_t* a_src = At + ((size_t)h * Npad + (size_t)ti * TILE + srow) * Tpad + schunk * 16;
-    const int8_t* b_src = At + ((size_t)h * Npad + (size_t)tj * TILE + srow) * Tpad + schunk * 16;
-    const size_t row32 = (size_t)32 * Tpad;
-    const int nchunks = (int)(Tpad / KC);
-    const int st_base = lds_off(srow, schunk);              // rows srow + 32*i share the swizzle term: constant byte offsets
-    v4i sta[2][8], stb[2][8];                               // two register sets, indexed by chunk parity
-    // loads number l0 .. l1-1 of the 16 that make up one chunk (0..7: A rows, 8..15: B rows)
-    auto load_part = [&](int set, int chunk, int l0, int l1) {
-        const int64_t k0 = (int64_t)min(chunk, nchunks - 1) * KC;      // clamped: a redundant reload past the end is harmless
-#pragma unroll
-        for (int l = l0; l < l1; ++l) {
-            if (l < 8) sta[set][l] = *reinterpret_cast<const v4i*>(a_src + l * row32 + k0);
-            else stb[set][l - 8] = *reinterpret_cast<const v4i*>(b_src + (l - 8) * row32 + k0);
-        }
+    // memory -> registers: one 16-byte word per thread, panel and chunk.  Four register sets, indexed
+    // by chunk number mod 4.
+    const v4i* a_src = bits + (size_t)h * nchunks * Npad + (size_t)ti * TILE + tid;
+    const v4i* b_src = bits + (size_t)h * nchunks * Npad + (size_t)tj * TILE + tid;
+    v4i ba[4], bb[4];
+    const size_t last_off = (size_t)(nchunks - 1) * Npad;
+    auto load_a = [&](int set, int chunk) __attribute__((always_inline)) {            // clamped: a redundant reload past the end is harmless
+        ba[set] = a_src[chunk < nchunks ? (size_t)chunk * Npad : last_off];
     };
-    auto store_a = [&](int set, int buf) {
-        int8_t* la = lds + buf * 2 * STAGE_BYTES + st_base;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *reinterpret_cast<v4i*>(la + i * 32 * KC) = sta[set][i];
+    auto load_b = [&](int set, int chunk) __attribute__((always_inline)) {
+        bb[set] = b_src[chunk < nchunks ? (size_t)chunk * Npad : last_off];
     };
-    auto store_b = [&](int set, int buf) {
-        int8_t* lb = lds + buf * 2 * STAGE_BYTES + STAGE_BYTES + st_base;
+    // registers -> LDS: piece p (0..7) of a panel row is 16 contraction bytes; pieces 8..15 are the B
+    // panel's.  A piece is expanded one dword (4 trace rows) at a time and stored when complete.
+    int st_off[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *reinterpret_cast<v4i*>(lb + i * 32 * KC) = stb[set][i];
+    for (int p = 0; p < 8; ++p) st_off[p] = lds_off(tid, p);
+    v4i ex;
+    auto expand_quarter = [&](int set, int piece, int q) __attribute__((always_inline)) {
+        const int p = piece & 7;
+        const uint32_t w = (uint32_t)(piece < 8 ? ba[set][p >> 1] : bb[set][p >> 1]);
+        ex[q] = (int)(__umul24(__builtin_amdgcn_ubfe(w, 16 * (p & 1) + 4 * q, 4), 0x00204081u) & 0x01010101u);
+    };
+    auto store_piece = [&](int buf, int piece) __attribute__((always_inline)) {
+        *reinterpret_cast<v4i*>(lds + buf * 2 * STAGE_BYTES + (piece < 8 ? 0 : STAGE_BYTES) + st_off[piece & 7]) = ex;
     };
 
     v16i acc[4][4];
@@ -137,88 +161,67 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
         fb_base[ks] = STAGE_BYTES + lds_off(wx * 128 + frow, 2 * ks + fhalf);
     }
     v4i fa[2][4], fb[2][4];
-    auto read_frags = [&](int buf, int ks, int set) {
+    // fragment number f of a k-step, in the order the MFMAs need them (MFMA m uses A tile m/4, B tile m%4)
+    auto read_frag = [&](int buf, int ks, int set, int f) __attribute__((always_inline)) {
         const int8_t* base = lds + buf * 2 * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            fa[set][i] = *reinterpret_cast<const v4i*>(base + fa_base[ks] + i * 32 * KC);
-            fb[set][i] = *reinterpret_cast<const v4i*>(base + fb_base[ks] + i * 32 * KC);
-        }
+        if (f == 0) fa[set][0] = *reinterpret_cast<const v4i*>(base + fa_base[ks]);
+        else if (f < 5) fb[set][f - 1] = *reinterpret_cast<const v4i*>(base + fb_base[ks] + (f - 1) * 32 * KC);
+        else fa[set][f - 4] = *reinterpret_cast<const v4i*>(base + fa_base[ks] + (f - 4) * 32 * KC);
     };
-    auto mfma16 = [&](int set) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
-    };
-    auto mfma_half = [&](int set, int half_idx) {
-#pragma unroll
-        for (int i = 2 * half_idx; i < 2 * half_idx + 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
-    };
-    // Scheduling hint for one k-step of 16 MFMAs: after MFMA i comes one fragment read (i < 8), one LDS
-    // store (i >= 8, when the step carries stores) and one global load after every fourth MFMA, so
-    // that no unit sees a burst.
-    auto interleave16 = [&](bool with_stores) {
-        _Pragma("unroll") for (int i = 0; i < 16; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            else if (with_stores) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-            if ((i & 3) == 3) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
+    auto mfma = [&](int set, int m) __attribute__((always_inline)) {
+        acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][m >> 2], fb[set][m & 3], acc[m >> 2][m & 3], 0, 0, 0);
     };
 
-    load_part(0, 0, 0, 16);
-    load_part(1, 1, 0, 16);
-    store_a(0, 0);
-    store_b(0, 0);
-    load_part(0, 2, 0, 4);
+    load_a(0, 0); load_b(0, 0);
+    load_a(1, 1); load_b(1, 1);
+    load_a(2, 2); load_b(2, 2);
+#pragma unroll
+    for (int piece = 0; piece < 16; ++piece) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) expand_quarter(0, piece, q);
+        store_piece(0, piece);
+    }
     __syncthreads();
-    read_frags(0, 0, 0);
+#pragma unroll
+    for (int f = 0; f < 8; ++f) read_frag(0, 0, 0, f);
 
-    // Chunk c computes out of LDS buffer c%2.  Register set (c+1)%2 holds chunk c+1: it is written to the
-    // other LDS buffer during the second and third k-step and starts refilling with chunk c+3 in the
-    // fourth.  Register set c%2 keeps refilling with chunk c+2 during the first three k-steps.  The 16
-    // loads of a chunk are thus spread one per four MFMAs over a whole chunk time, and land at least a
-    // chunk time before they are needed.  The hand-over barrier sits 8 MFMAs before the end of the
-    // chunk; those last 8 MFMAs cover the LDS latency of the next chunk's first fragments.
-    auto chunk_body = [&](int c, int buf) {                 // buf = c % 2, passed as a literal
-        const int nset = buf ^ 1;
-        read_frags(buf, 1, 1);
-        load_part(buf, c + 2, 4, 8);
-        mfma16(0);
-        interleave16(false);
-
-        read_frags(buf, 2, 0);
-        store_a(nset, nset);                   // the other buffer was last read before the previous barrier
-        load_part(buf, c + 2, 8, 12);
-        mfma16(1);
-        interleave16(true);
-
-        read_frags(buf, 3, 1);
-        store_b(nset, nset);
-        load_part(buf, c + 2, 12, 16);
-        mfma16(0);
-        interleave16(true);
-
-        load_part(nset, c + 3, 0, 4);
-        mfma_half(1, 0);
-        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    // Chunk c computes out of LDS buffer c%2; its own bit words (register set c%4) are spent.  Set
+    // (c+1)%4 is expanded into the other LDS buffer, which no wave reads after the hand-over barrier
+    // of chunk c-1; set (c+3)%4 is refilled at the start.  The work is laid out as 64 slots, one per
+    // MFMA, fenced against reordering: slot m of a k-step issues the MFMA, then a fragment read for the
+    // next k-step (m < 8), then its share of the expansion (64 dwords of 3 operations and 16 LDS
+    // stores per chunk, spread over the first 56 slots) so that no unit sees a burst.  The hand-over
+    // barrier sits 8 MFMAs before the end of the chunk; those last 8 MFMAs cover the LDS latency of
+    // the next chunk's first fragments.
+    auto chunk_body = [&](int c, int buf, int set) __attribute__((always_inline)) {   // buf = c % 2, set = c % 4, passed as literals
+        const int nbuf = buf ^ 1, nset = (set + 1) & 3, lset = (set + 3) & 3;
+#pragma unroll
+        for (int slot = 0; slot < 56; ++slot) {
+            const int ks = slot >> 4, m = slot & 15;
+            mfma(ks & 1, m);
+            if (ks < 3 && m < 8) read_frag(buf, ks + 1, (ks + 1) & 1, m);
+            if (slot == 0) load_a(lset, c + 3);
+            if (slot == 1) load_b(lset, c + 3);
+            // quarters [slot*64/56, (slot+1)*64/56) of the 64
+#pragma unroll
+            for (int u = slot * 8 / 7; u < (slot + 1) * 8 / 7; ++u) {
+                expand_quarter(nset, u >> 2, u & 3);
+                if ((u & 3) == 3) store_piece(nbuf, u >> 2);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        read_frags(nset, 0, 0);                // after the last chunk this reads stale but valid LDS and is never used
+#pragma unroll
+        for (int f = 0; f < 8; ++f) read_frag(nbuf, 0, 0, f);          // after the last chunk this reads stale but valid LDS and is never used
         __builtin_amdgcn_sched_barrier(0);
-        mfma_half(1, 1);
+#pragma unroll
+        for (int m = 8; m < 16; ++m) mfma(1, m);
     };
-    for (int c = 0; c < nchunks; c += 2) {                  // nchunks is even
-        chunk_body(c, 0);
-        chunk_body(c + 1, 1);
+    for (int c = 0; c < nchunks; c += 4) {                  // nchunks is a multiple of 4
+        chunk_body(c, 0, 0);
+        chunk_body(c + 1, 1, 1);
+        chunk_body(c + 2, 0, 2);
+        chunk_body(c + 3, 1, 3);
     }
 
     // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4.  One
@@ -229,91 +232,129 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const int8_t* __rest
     // LDS and leaves in 16-byte stores that cover whole lines.  Streaming stores when C is not read.
     int32_t* Ch = C + (size_t)h * N * N;
     const int col_in = lane & 31, half = lane >> 5, row_in = half * 4;
-    auto rmw1 = [&](int32_t* p, int32_t v) {
-        if (MODE == 0) __builtin_nontemporal_store(v, p);
-        else if (MODE == 1) *p += v;
-        else *p = decayed(*p, decay_q16) + v;
-    };
-    auto rmw4 = [&](int32_t* p, v4i v) {
-        if (MODE == 0) {
-            __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(p));
-        } else {
-            const v4i o = *reinterpret_cast<const v4i*>(p);
-            if (MODE == 1) v += o;
-            else {
-                v.x += decayed(o.x, decay_q16); v.y += decayed(o.y, decay_q16);
-                v.z += decayed(o.z, decay_q16); v.w += decayed(o.w, decay_q16);
-            }
-            *reinterpret_cast<v4i*>(p) = v;
-        }
-    };
-    constexpr int TROW = 512 + 16;                                       // padded: 16-byte accesses of 16 lanes hit 16 bank groups
+    constexpr int TROW = 512 + 16;                                       // padded: the 16-byte slots of 8 consecutive lanes differ
     int8_t* tbuf = lds + wave * (32 * TROW);
     const int gi_base = ti * TILE + wy * 128;
+    // Addresses are a wave-uniform row pointer (scalar arithmetic) plus one per-lane element offset
+    // that is the same for every store of a tile.
+    const uint32_t lane_direct = (uint32_t)row_in * (uint32_t)N + col_in;
+    const uint32_t lane_mirror = (uint32_t)half * (uint32_t)N + col_in * 4;
+    auto combine = [&](int32_t old, int32_t v) __attribute__((always_inline)) {
+        return MODE == 1 ? old + v : decayed(old, decay_q16) + v;
+    };
+    // GUARD: the tile reaches past N (only tiles of the last tile row / column when N is not a multiple of 256)
+    auto emit = [&](auto guard_tag) __attribute__((always_inline)) {
+        constexpr bool GUARD = decltype(guard_tag)::value;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int gj_base = tj * TILE + wx * 128 + j * 32;
-        // park the 128 x 32 block as [column][row] for the mirrored tile; the LDS executes one wave's
-        // accesses in order, so the block of the previous j has been read by then
-        if (VEC && !diag) {
+        for (int j = 0; j < 4; ++j) {
+            const int gj_base = tj * TILE + wx * 128 + j * 32;
+            // park the 128 x 32 block as [column][row] for the mirrored tile; the LDS executes one wave's
+            // accesses in order, so the block of the previous j has been read by then
+            if (VEC && !diag) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    const v4i v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
-                    *reinterpret_cast<v4i*>(tbuf + col_in * TROW + (i * 32 + rq * 8 + row_in) * 4) = v;
-                }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        }
-        // direct tile: rows gi_base + 0..127, columns gj_base + 0..31
-        const int gjc = gj_base + col_in;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int gi = gi_base + i * 32 + (r >> 2) * 8 + row_in + (r & 3);
-                if (gi < N && gjc < N) {
-                    rmw1(Ch + (size_t)gi * N + gjc, acc[i][j][r]);
-                    if (!VEC && !diag) rmw1(Ch + (size_t)gjc * N + gi, acc[i][j][r]);    // rows of C not 16-byte aligned: element-wise mirror
-                }
+                    for (int rq = 0; rq < 4; ++rq) {
+                        const v4i v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
+                        *reinterpret_cast<v4i*>(tbuf + col_in * TROW + (i * 32 + rq * 8 + row_in) * 4) = v;
+                    }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             }
-            if (MODE != 0) asm volatile("" ::: "memory");
-        }
-        // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..127
-        if (VEC && !diag) {
+            // direct tile: rows gi_base + 0..127, columns gj_base + 0..31
+            int32_t* Cj = Ch + (size_t)gi_base * N + gj_base;                         // wave-uniform
+            const bool col_ok = !GUARD || gj_base + col_in < N;
 #pragma unroll
-            for (int sidx = 0; sidx < 16; ++sidx) {
-                const int r = 2 * sidx + half;
-                const v4i v = *reinterpret_cast<const v4i*>(tbuf + r * TROW + col_in * 16);
-                const int gj = gj_base + r, gi = gi_base + col_in * 4;
-                if (gj < N && gi < N) rmw4(Ch + (size_t)gj * N + gi, v);
-                if ((sidx & 7) == 7) asm volatile("" ::: "memory");
+            for (int ip = 0; ip < 4; ip += 2) {                                       // 32 rows x 2 in flight when C is read back
+                int32_t old[2][16];
+                if (MODE != 0) {
+#pragma unroll
+                    for (int i = ip; i < ip + 2; ++i)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int urow = i * 32 + (r >> 2) * 8 + (r & 3);
+                            if (col_ok && (!GUARD || gi_base + urow + row_in < N)) old[i - ip][r] = (Cj + (size_t)urow * N)[lane_direct];
+                        }
+                }
+#pragma unroll
+                for (int i = ip; i < ip + 2; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int urow = i * 32 + (r >> 2) * 8 + (r & 3);
+                        int32_t* p = Cj + (size_t)urow * N;
+                        if (col_ok && (!GUARD || gi_base + urow + row_in < N)) {
+                            if (MODE == 0) __builtin_nontemporal_store(acc[i][j][r], p + lane_direct);
+                            else p[lane_direct] = combine(old[i - ip][r], acc[i][j][r]);
+                            if (!VEC && !diag) {                                      // rows of C not 16-byte aligned: element-wise mirror
+                                int32_t* q = Ch + (size_t)(gj_base + col_in) * N + gi_base + urow + row_in;
+                                if (MODE == 0) *q = acc[i][j][r];
+                                else *q = combine(*q, acc[i][j][r]);
+                            }
+                        }
+                    }
+                if (MODE != 0) asm volatile("" ::: "memory");
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..127
+            if (VEC && !diag) {
+                int32_t* Cm = Ch + (size_t)gj_base * N + gi_base;                     // wave-uniform
+                const bool mcol_ok = !GUARD || gi_base + col_in * 4 < N;              // N is a multiple of 4 here
+#pragma unroll
+                for (int sp = 0; sp < 16; sp += 8) {
+                    v4i v[8], o[8];
+#pragma unroll
+                    for (int sidx = sp; sidx < sp + 8; ++sidx) {
+                        v[sidx - sp] = *reinterpret_cast<const v4i*>(tbuf + (2 * sidx + half) * TROW + col_in * 16);
+                        if (MODE != 0 && mcol_ok && (!GUARD || gj_base + 2 * sidx + half < N))
+                            o[sidx - sp] = *reinterpret_cast<const v4i*>(Cm + (size_t)(2 * sidx) * N + lane_mirror);
+                    }
+#pragma unroll
+                    for (int sidx = sp; sidx < sp + 8; ++sidx) {
+                        if (mcol_ok && (!GUARD || gj_base + 2 * sidx + half < N)) {
+                            v4i* p = reinterpret_cast<v4i*>(Cm + (size_t)(2 * sidx) * N + lane_mirror);
+                            if (MODE == 0) __builtin_nontemporal_store(v[sidx - sp], p);
+                            else {
+                                v4i w = v[sidx - sp];
+                                const v4i q = o[sidx - sp];
+                                w.x = combine(q.x, w.x); w.y = combine(q.y, w.y); w.z = combine(q.z, w.z); w.w = combine(q.w, w.w);
+                                *p = w;
+                            }
+                        }
+                    }
+                    if (MODE != 0) asm volatile("" ::: "memory");
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            }
         }
-    }
+    };
+    if (MODE == 0 && (ti + 1) * TILE <= N && (tj + 1) * TILE <= N) emit(std::false_type{});   // whole tile inside C: no per-store checks
+    else emit(std::true_type{});
 }
 
 }  // namespace
 
-swarm_status launch_trace_scatter(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
-                                  int64_t Tpad, uint32_t flags) {
-    const size_t n16 = (size_t)H * Npad * Tpad / 16;
-    const unsigned fill_blocks = (unsigned)((n16 + 255) / 256 < 16384 ? (n16 + 255) / 256 : 16384);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(fill_blocks), dim3(256), 0, ctx->stream,
-                       reinterpret_cast<uint4*>(ctx->trace), n16);
-    swarm_status st = swarm_check_launch(ctx, "fill_zero_kernel");
-    if (st != SWARM_OK) return st;
+swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
+                                int nchunks, uint32_t flags) {
     if (flags & SWARM_CHECK_IDX) {
         hipLaunchKernelGGL(check_distinct_kernel, dim3((unsigned)(rows * H)), dim3(256), 0, ctx->stream, idx, k,
                            ctx->dev_flags);
-        st = swarm_check_launch(ctx, "check_distinct_kernel");
+        const swarm_status st = swarm_check_launch(ctx, "check_distinct_kernel");
         if (st != SWARM_OK) return st;
     }
-    const int64_t total = rows * H * k;
-    hipLaunchKernelGGL(trace_scatter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, ctx->stream, idx, total,
-                       H, k, N, Npad, Tpad, ctx->trace, ctx->dev_flags);
-    return swarm_check_launch(ctx, "trace_scatter_kernel");
+    const int span = Npad < TRACE_SPAN ? Npad : TRACE_SPAN;
+    const size_t lds_bytes = (size_t)span * 16;
+    static bool lds_opt_in = false;
+    if (!lds_opt_in) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trace_build_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, TRACE_SPAN * 16);
+        if (e != hipSuccess) {
+            snprintf(ctx->err, sizeof(ctx->err), "coact: cannot opt in to %d bytes of LDS: %s", TRACE_SPAN * 16, hipGetErrorString(e));
+            return SWARM_EHIP;
+        }
+        lds_opt_in = true;
+    }
+    const dim3 grid((unsigned)nchunks, (unsigned)H, (unsigned)((Npad + TRACE_SPAN - 1) / TRACE_SPAN));
+    hipLaunchKernelGGL(trace_build_kernel, grid, dim3(1024), lds_bytes, ctx->stream, idx, rows, H, k, N, Npad, nchunks,
+                       reinterpret_cast<uint4*>(ctx->trace), ctx->dev_flags);
+    return swarm_check_launch(ctx, "trace_build_kernel");
 }
 
 // Order in which the upper-triangle tiles are handed out: super-blocks of 4 x 8 tiles, so that the
@@ -351,7 +392,7 @@ static swarm_status ensure_tile_order(swarm_ctx* ctx, int nt) {
     return st;
 }
 
-swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int64_t Tpad, int32_t* C, uint32_t decay_q16) {
+swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nchunks, int32_t* C, uint32_t decay_q16) {
     const int nt = Npad / TILE;
     const int64_t tiles_per_head = (int64_t)nt * (nt + 1) / 2;
     const int64_t total = tiles_per_head * H;
@@ -364,7 +405,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int64_t T
     const int per_xcd = (int)((total + 7) / 8);
     const int mode = decay_q16 == 0u ? 0 : decay_q16 == 65536u ? 1 : 2;
     const bool vec = (N & 3) == 0;
-    using kernel_t = void (*)(const int8_t*, int, int, int64_t, int32_t*, uint32_t, int, int, int, int, const int32_t*);
+    using kernel_t = void (*)(const v4i*, int, int, int, int32_t*, uint32_t, int, int, int, const int32_t*);
     static const kernel_t kernels[3][2] = {{coact_syrk_kernel<0, false>, coact_syrk_kernel<0, true>},
                                            {coact_syrk_kernel<1, false>, coact_syrk_kernel<1, true>},
                                            {coact_syrk_kernel<2, false>, coact_syrk_kernel<2, true>}};
@@ -384,7 +425,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int64_t T
     dim3 grid((unsigned)(per_xcd * 8)), block(256);
     const int tph = (int)tiles_per_head, tot = (int)total;
     hipLaunchKernelGGL(kernels[mode][vec ? 1 : 0], grid, block, SYRK_LDS_BYTES, ctx->stream,
-                       static_cast<const int8_t*>(ctx->trace), N, Npad, Tpad, C, decay_q16, nt, tph, tot, per_xcd,
+                       reinterpret_cast<const v4i*>(ctx->trace), N, Npad, nchunks, C, decay_q16, tph, tot, per_xcd,
                        static_cast<const int32_t*>(ctx->tile_order));
     return swarm_check_launch(ctx, "coact_syrk_kernel");
 }
