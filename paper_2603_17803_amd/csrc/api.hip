@@ -154,13 +154,13 @@ swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t 
     if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "coact_accumulate: C must be 16-byte aligned");
     if (flags & ~SWARM_CHECK_IDX) SWARM_REJECT(ctx, "coact_accumulate: unknown flags 0x%x", flags);
 
-    const int nchunks = (int)((rows + 511) / 512 * 4);   // contraction in chunks of 128 trace rows, zero-padded to a multiple of 4 chunks
+    const int nruns = (int)((rows + 511) / 512 * 4);      // contraction in runs of 128 trace rows, zero-padded to a multiple of 4 runs
     const int Npad = (N + 255) / 256 * 256;               // entries, zero-padded to the C tile
-    swarm_status st = swarm_grow(ctx, &ctx->trace, &ctx->trace_bytes, (size_t)H * nchunks * Npad * 16);
+    swarm_status st = swarm_grow(ctx, &ctx->trace, &ctx->trace_bytes, (size_t)H * nruns * Npad * 16);
     if (st != SWARM_OK) return st;
-    st = launch_trace_build(ctx, idx, rows, H, k, N, Npad, nchunks, flags);
+    st = launch_trace_build(ctx, idx, rows, H, k, N, Npad, nruns, flags);
     if (st != SWARM_OK) return st;
-    return launch_coact_syrk(ctx, H, N, Npad, nchunks, C, decay_q16);
+    return launch_coact_syrk(ctx, H, N, Npad, nruns, C, decay_q16);
 }
 
 swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int32_t S, int32_t H, int32_t N,

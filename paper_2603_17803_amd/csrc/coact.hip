@@ -2,9 +2,9 @@
 // rows in which entries i and j are both activated, i.e. C = A^T A for the binary trace A.
 //
 // The trace is binary, so it is kept in memory as bits: for every head and every run of 128 trace
-// rows ("chunk") one 16-byte word per entry, bits[h][chunk][entry], bit s = "entry activated in trace
-// row 128*chunk + s".  Both operands of the product are entry panels of this one array.  On the way
-// to the matrix cores a workgroup expands the bits of its two 256-entry panels to int8 0/1 rows in
+// rows one 16-byte word per entry, bits[h][run][entry], bit s = "entry activated in trace row
+// 128*run + s".  Both operands of the product are entry panels of this one array.  On the way
+// to the matrix cores a workgroup expands the bits of its two entry panels to int8 0/1 rows in
 // LDS (contraction index contiguous), and the product runs on v_mfma_i32_32x32x32_i8 with exact
 // int32 accumulation.  Feeding int8 from memory instead would make every workgroup pull
 // 512 bytes per contraction byte-step through the L2, which at this tile size is within 15% of
@@ -24,20 +24,20 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int TRACE_SPAN = 8192;   // entries one trace-building workgroup covers (128 KiB of LDS)
 
-// One workgroup per (chunk, head, span of entries): the 128 selections of the chunk are merged into
-// an LDS image of the chunk's bit words, which then leaves as one contiguous, fully written block
+// One workgroup per (run of 128 trace rows, head, span of entries): the 128 selections are merged
+// into an LDS image of the run's bit words, which then leaves as one contiguous, fully written block
 // (no separate clearing pass, no global atomics).
 __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __restrict__ idx, int64_t rows, int H, int k, int N,
-                                                           int Npad, int nchunks, uint4* __restrict__ bits,
+                                                           int Npad, int nruns, uint4* __restrict__ bits,
                                                            uint32_t* __restrict__ dev_flags) {
     extern __shared__ __attribute__((aligned(16))) uint32_t words[];          // [span][4]
-    const int chunk = blockIdx.x, h = blockIdx.y;
+    const int run = blockIdx.x, h = blockIdx.y;
     const int e0 = blockIdx.z * TRACE_SPAN;
     const int span = min(TRACE_SPAN, Npad - e0);
     for (int i = threadIdx.x; i < span * 4; i += blockDim.x) words[i] = 0u;
     __syncthreads();
-    const int64_t row0 = (int64_t)chunk * 128;
-    const int nrows = (int)min((int64_t)128, rows - row0);                       // <= 0 for a chunk of pure padding
+    const int64_t row0 = (int64_t)run * 128;
+    const int nrows = (int)min((int64_t)128, rows - row0);                       // <= 0 for a run of pure padding
     bool bad = false;
     for (int s = 0; s < nrows; ++s) {
         const int32_t* sel = idx + ((row0 + s) * H + h) * (int64_t)k;
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __rest
     }
     if (bad && blockIdx.z == 0) atomicOr(dev_flags, SWARM_DEV_BAD_ENTRY);
     __syncthreads();
-    uint4* out = bits + ((size_t)h * nchunks + chunk) * Npad + e0;
+    uint4* out = bits + ((size_t)h * nruns + run) * Npad + e0;
     const uint4* src = reinterpret_cast<const uint4*>(words);
     for (int i = threadIdx.x; i < span; i += blockDim.x) out[i] = src[i];
 }
@@ -71,157 +71,174 @@ __device__ __forceinline__ int32_t decayed(int32_t old, uint32_t decay_q16) {
     return (int32_t)(((int64_t)old * (int64_t)decay_q16 + 32768) >> 16);
 }
 
-// MODE 0: C = acc.  MODE 1: C += acc.  MODE 2: C = decayed(C) + acc.
-constexpr int TILE = 256;          // C tile edge per workgroup
-constexpr int KC = 128;            // contraction bytes staged per iteration (one cache line per trace row)
-constexpr int STAGE_BYTES = TILE * KC;                 // one operand tile in LDS
-constexpr int SYRK_LDS_BYTES = 2 * 2 * STAGE_BYTES;    // double buffer x (A, B) = 128 KiB
+constexpr int TM = 256;                        // C tile rows per workgroup
+constexpr int TN = 128;                        // C tile columns per workgroup
+constexpr int KC = 64;                         // trace rows (= contraction bytes) per chunk: two 32-byte MFMA k-steps
+constexpr int A_BYTES = TM * KC;               // operand panels of one chunk in LDS
+constexpr int B_BYTES = TN * KC;
+constexpr int BUF_BYTES = A_BYTES + B_BYTES;   // 24 KiB; two of them form the ring
+constexpr int TROW = 512 + 16;                 // epilogue staging row, padded: the 16-byte slots of 8 consecutive lanes differ
+constexpr int SYRK_LDS_BYTES = 4 * 32 * TROW;  // 66 KiB: the epilogue's staging (one 32-column block per wave) is the larger user
+static_assert(SYRK_LDS_BYTES >= 2 * BUF_BYTES, "operand ring must fit");
 
-// Operand rows in LDS are 128 bytes; 16-byte piece c of row r lives at slot c ^ swz(r).  Measured on
+// Operand rows in LDS are 64 bytes; 16-byte piece c of row r lives at slot c ^ swz(r).  Measured on
 // gfx950: a 16-byte LDS read is served 16 consecutive lanes at a time across 64 four-byte banks, a
-// 16-byte write 8 consecutive lanes at a time with only the slot (address bits 4..6) telling lanes
-// apart.  Fragment reads take one piece of 16 consecutive rows, expansion writes one piece of 8
-// consecutive rows (thread = row): swz must differ on rows of equal parity within 16 rows (reads:
-// parity picks the bank half) and on all rows within 8 (writes).  swz(r) = bits 1..2 of r, with bit 2
-// = bit 3 of r xor bit 0 of r, does both.
-__device__ __forceinline__ int lds_swz(int row) { return ((row >> 1) & 3) | ((((row >> 3) ^ row) & 1) << 2); }
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * KC + ((chunk ^ lds_swz(row)) << 4); }
+// 16-byte write 8 consecutive lanes at a time with only address bits 4..6 telling lanes apart.
+// Fragment reads take one piece of 16 consecutive rows, so rows that agree in bits 0..1 need
+// different swz; the expansion writes of 8 consecutive lanes cover 8 rows (A panel: thread = row)
+// or 4 rows x 2 halves (B panel), so rows that agree in bit 0 within 8 need different swz, and bit 0
+// of swz must follow bit 1 of the row.  swz = (bit1 ^ bit3) | bit2 << 1 does all of it.
+__device__ __forceinline__ int lds_swz(int row) { return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1); }
+__device__ __forceinline__ int lds_off(int row, int piece) { return row * KC + ((piece ^ lds_swz(row)) << 4); }
 
 // Expansion of trace bits to bytes of 0/1, four at a time: a nibble times (1 + 2^7 + 2^14 + 2^21) puts
 // bit b at bit 8b (the four shifted copies do not overlap, so nothing carries); a mask drops the rest.
 
-// C tile of 256 x 256 per workgroup; 4 waves in a 2 x 2 arrangement, each owning 128 x 128 =
-// 4 x 4 MFMA tiles (256 accumulator registers).  The contraction runs in chunks of 128 trace rows
-// (four 32-byte MFMA k-steps) through a two-deep LDS ring: thread t owns entry t of both panels; the
-// 16-byte bit words of chunk c+2 and c+3 are in flight from memory, the words of chunk c+1 are
-// being expanded and written into the idle LDS buffer, chunk c feeds the matrix cores; operand
-// fragments of k-step s+1 are read from LDS while the 16 MFMAs of k-step s run.
+// C tile of 256 x 128 per workgroup of 4 waves (2 x 2, each 128 x 64 = 4 x 2 MFMA tiles, 128
+// accumulator registers), two workgroups per compute unit: while one waits at its hand-over barrier,
+// writes its tile or starts up, the other keeps the matrix cores busy.  The contraction runs in
+// chunks of 64 trace rows through a two-deep LDS ring: thread t owns row t of the A panel and half
+// of row t/2 of the B panel; the bit words of the next runs of 128 trace rows are in flight from
+// memory (three runs ahead), those of chunk c+1 are being expanded and written into the idle LDS buffer, chunk c feeds the matrix
+// cores; operand fragments of k-step s+1 are read from LDS while the MFMAs of k-step s run.
+// Because the operands travel as bits, the smaller tile costs next to nothing in memory traffic.
 // Workgroups are numbered so that the eight L2 slices (one per XCD, workgroups are dealt to them
 // round-robin) each walk a contiguous run of the tile schedule.
 template <int MODE, bool VEC>
-__global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nchunks,
+__global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns,
                                                             int32_t* __restrict__ C, uint32_t decay_q16,
                                                             int tiles_per_head, int total_tiles, int per_xcd,
                                                             const int32_t* __restrict__ tile_order) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int t = xcd * per_xcd + slot;
-    if (slot >= per_xcd || t >= total_tiles) return;
+    const int xcd = blockIdx.x & 7, slot_id = blockIdx.x >> 3;
+    const int t = xcd * per_xcd + slot_id;
+    if (slot_id >= per_xcd || t >= total_tiles) return;
     const int h = t / tiles_per_head;
     const int32_t packed = tile_order[t - h * tiles_per_head];
-    const int ti = packed >> 16, tj = packed & 0xffff;
-    const bool diag = ti == tj;
+    const int ti = packed >> 16, tj = packed & 0xffff;       // 256-row tile, 128-column tile
+    const bool diag = (tj >> 1) == ti;                       // inside a diagonal 256 x 256 block: its two tiles cover it, no mirror
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wy = wave >> 1, wx = wave & 1;
 
-    // memory -> registers: one 16-byte word per thread, panel and chunk.  Four register sets, indexed
-    // by chunk number mod 4.
-    const v4i* a_src = bits + (size_t)h * nchunks * Npad + (size_t)ti * TILE + tid;
-    const v4i* b_src = bits + (size_t)h * nchunks * Npad + (size_t)tj * TILE + tid;
+    // memory -> registers, one 16-byte word (a run of 128 trace rows = two chunks) per panel row at a
+    // time: thread t takes row t of the A panel and row t/2 of the B panel, of which it expands the
+    // half t%2 of either chunk.  Four register sets, indexed by run number mod 4.
+    const v4i* panel = bits + (size_t)h * nruns * Npad;
+    const v4i* a_src = panel + (size_t)ti * TM + tid;
+    const v4i* b_src = panel + (size_t)tj * TN + (tid >> 1);
+    const bool odd = tid & 1;
     v4i ba[4], bb[4];
-    const size_t last_off = (size_t)(nchunks - 1) * Npad;
-    auto load_a = [&](int set, int chunk) __attribute__((always_inline)) {            // clamped: a redundant reload past the end is harmless
-        ba[set] = a_src[chunk < nchunks ? (size_t)chunk * Npad : last_off];
+    const size_t last_off = (size_t)(nruns - 1) * Npad;
+    auto load_bits = [&](int set, int run) __attribute__((always_inline)) {           // clamped: a redundant reload past the end is harmless
+        const size_t off = run < nruns ? (size_t)run * Npad : last_off;
+        ba[set] = a_src[off];
+        bb[set] = b_src[off];
     };
-    auto load_b = [&](int set, int chunk) __attribute__((always_inline)) {
-        bb[set] = b_src[chunk < nchunks ? (size_t)chunk * Npad : last_off];
-    };
-    // registers -> LDS: piece p (0..7) of a panel row is 16 contraction bytes; pieces 8..15 are the B
-    // panel's.  A piece is expanded one dword (4 trace rows) at a time and stored when complete.
-    int st_off[8];
+    // registers -> LDS, in pieces of 16 contraction bytes: pieces 0..3 are the A row's, 4..5 the two of
+    // the B half row.  A piece is expanded one dword (4 trace rows) at a time and stored when complete.
+    int st_off[6];
 #pragma unroll
-    for (int p = 0; p < 8; ++p) st_off[p] = lds_off(tid, p);
+    for (int p = 0; p < 4; ++p) st_off[p] = lds_off(tid, p);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) st_off[4 + q] = A_BYTES + lds_off(tid >> 1, 2 * (tid & 1) + q);
     v4i ex;
-    auto expand_quarter = [&](int set, int piece, int q) __attribute__((always_inline)) {
-        const int p = piece & 7;
-        const uint32_t w = (uint32_t)(piece < 8 ? ba[set][p >> 1] : bb[set][p >> 1]);
-        ex[q] = (int)(__umul24(__builtin_amdgcn_ubfe(w, 16 * (p & 1) + 4 * q, 4), 0x00204081u) & 0x01010101u);
+    uint32_t bw;                                   // the thread's half of the B row's word for the chunk being expanded
+    auto pick_b = [&](int set, int half) __attribute__((always_inline)) {
+        bw = (uint32_t)(odd ? bb[set][2 * half + 1] : bb[set][2 * half]);
+    };
+    auto expand_quarter = [&](int set, int half, int piece, int q) __attribute__((always_inline)) {
+        const uint32_t w = piece < 4 ? (uint32_t)ba[set][2 * half + (piece >> 1)] : bw;
+        ex[q] = (int)(__umul24(__builtin_amdgcn_ubfe(w, 16 * (piece & 1) + 4 * q, 4), 0x00204081u) & 0x01010101u);
     };
     auto store_piece = [&](int buf, int piece) __attribute__((always_inline)) {
-        *reinterpret_cast<v4i*>(lds + buf * 2 * STAGE_BYTES + (piece < 8 ? 0 : STAGE_BYTES) + st_off[piece & 7]) = ex;
+        *reinterpret_cast<v4i*>(lds + buf * BUF_BYTES + st_off[piece]) = ex;
     };
 
-    v16i acc[4][4];
+    v16i acc[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
     // fragment addressing: lane l reads row l%32 of an MFMA tile, bytes [16*(l/32), +16) of the 32-byte
-    // k-step.  The swizzle term only depends on the k-step; the tile index is a constant byte offset.
+    // k-step.  The swizzle term is the same for rows 32 apart; the tile index is a constant byte offset.
     const int frow = lane & 31, fhalf = lane >> 5;
-    int fa_base[4], fb_base[4];
+    int fa_base[2], fb_base[2];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < 2; ++ks) {
         fa_base[ks] = lds_off(wy * 128 + frow, 2 * ks + fhalf);
-        fb_base[ks] = STAGE_BYTES + lds_off(wx * 128 + frow, 2 * ks + fhalf);
+        fb_base[ks] = A_BYTES + lds_off(wx * 64 + frow, 2 * ks + fhalf);
     }
-    v4i fa[2][4], fb[2][4];
-    // fragment number f of a k-step, in the order the MFMAs need them (MFMA m uses A tile m/4, B tile m%4)
+    v4i fa[2][4], fb[2][2];
+    // fragment number f of a k-step, in the order the MFMAs need them (MFMA m uses A tile m/2, B tile m%2)
     auto read_frag = [&](int buf, int ks, int set, int f) __attribute__((always_inline)) {
-        const int8_t* base = lds + buf * 2 * STAGE_BYTES;
+        const int8_t* base = lds + buf * BUF_BYTES;
         if (f == 0) fa[set][0] = *reinterpret_cast<const v4i*>(base + fa_base[ks]);
-        else if (f < 5) fb[set][f - 1] = *reinterpret_cast<const v4i*>(base + fb_base[ks] + (f - 1) * 32 * KC);
-        else fa[set][f - 4] = *reinterpret_cast<const v4i*>(base + fa_base[ks] + (f - 4) * 32 * KC);
+        else if (f < 3) fb[set][f - 1] = *reinterpret_cast<const v4i*>(base + fb_base[ks] + (f - 1) * 32 * KC);
+        else fa[set][f - 2] = *reinterpret_cast<const v4i*>(base + fa_base[ks] + (f - 2) * 32 * KC);
     };
     auto mfma = [&](int set, int m) __attribute__((always_inline)) {
-        acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][m >> 2], fb[set][m & 3], acc[m >> 2][m & 3], 0, 0, 0);
+        acc[m >> 1][m & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][m >> 1], fb[set][m & 1], acc[m >> 1][m & 1], 0, 0, 0);
     };
 
-    load_a(0, 0); load_b(0, 0);
-    load_a(1, 1); load_b(1, 1);
-    load_a(2, 2); load_b(2, 2);
+    load_bits(0, 0);
+    load_bits(1, 1);
+    load_bits(2, 2);
+    pick_b(0, 0);
 #pragma unroll
-    for (int piece = 0; piece < 16; ++piece) {
+    for (int piece = 0; piece < 6; ++piece) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) expand_quarter(0, piece, q);
+        for (int q = 0; q < 4; ++q) expand_quarter(0, 0, piece, q);
         store_piece(0, piece);
     }
     __syncthreads();
 #pragma unroll
-    for (int f = 0; f < 8; ++f) read_frag(0, 0, 0, f);
+    for (int f = 0; f < 6; ++f) read_frag(0, 0, 0, f);
 
-    // Chunk c computes out of LDS buffer c%2; its own bit words (register set c%4) are spent.  Set
-    // (c+1)%4 is expanded into the other LDS buffer, which no wave reads after the hand-over barrier
-    // of chunk c-1; set (c+3)%4 is refilled at the start.  The work is laid out as 64 slots, one per
-    // MFMA, fenced against reordering: slot m of a k-step issues the MFMA, then a fragment read for the
-    // next k-step (m < 8), then its share of the expansion (64 dwords of 3 operations and 16 LDS
-    // stores per chunk, spread over the first 56 slots) so that no unit sees a burst.  The hand-over
-    // barrier sits 8 MFMAs before the end of the chunk; those last 8 MFMAs cover the LDS latency of
-    // the next chunk's first fragments.
-    auto chunk_body = [&](int c, int buf, int set) __attribute__((always_inline)) {   // buf = c % 2, set = c % 4, passed as literals
-        const int nbuf = buf ^ 1, nset = (set + 1) & 3, lset = (set + 3) & 3;
+    // Chunk `half` of run d computes out of LDS buffer `half`; its own bits are spent.  The next chunk
+    // (the run's second half, or the first half of run d+1 in register set (d+1)%4) is expanded into
+    // the other LDS buffer, which no wave reads after the hand-over barrier of the previous chunk; set
+    // (d+3)%4 is refilled at the start of the run, three runs (6 chunks) ahead of its use.  The work is
+    // laid out as 16 slots, one per MFMA: slot m issues the MFMA, then a
+    // fragment read for the second k-step (first six slots), then its share of the expansion (24 dwords
+    // of 3 operations and 6 LDS stores per chunk, spread over the first 12 slots).  The hand-over
+    // barrier sits 4 MFMAs before the end of the chunk; those and the other workgroup on the compute
+    // unit cover the LDS latency of the next chunk's first fragments.
+    auto chunk_body = [&](int d, int half, int set) __attribute__((always_inline)) {   // set = d % 4; half and set passed as literals
+        const int buf = half, nbuf = half ^ 1;
+        const int nset = half ? (set + 1) & 3 : set, nhalf = half ^ 1, lset = (set + 3) & 3;
+        pick_b(nset, nhalf);
 #pragma unroll
-        for (int slot = 0; slot < 56; ++slot) {
-            const int ks = slot >> 4, m = slot & 15;
-            mfma(ks & 1, m);
-            if (ks < 3 && m < 8) read_frag(buf, ks + 1, (ks + 1) & 1, m);
-            if (slot == 0) load_a(lset, c + 3);
-            if (slot == 1) load_b(lset, c + 3);
-            // quarters [slot*64/56, (slot+1)*64/56) of the 64
+        for (int s = 0; s < 12; ++s) {
+            mfma(s >> 3, s & 7);
+            if (s < 6) read_frag(buf, 1, 1, s);
+            if (half == 0 && s == 0) load_bits(lset, d + 3);
 #pragma unroll
-            for (int u = slot * 8 / 7; u < (slot + 1) * 8 / 7; ++u) {
-                expand_quarter(nset, u >> 2, u & 3);
+            for (int u = 2 * s; u < 2 * s + 2; ++u) {
+                expand_quarter(nset, nhalf, u >> 2, u & 3);
                 if ((u & 3) == 3) store_piece(nbuf, u >> 2);
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
 #pragma unroll
-        for (int f = 0; f < 8; ++f) read_frag(nbuf, 0, 0, f);          // after the last chunk this reads stale but valid LDS and is never used
+        for (int f = 0; f < 6; ++f) read_frag(nbuf, 0, 0, f);          // after the last chunk this reads stale but valid LDS and is never used
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int m = 8; m < 16; ++m) mfma(1, m);
+        for (int m = 4; m < 8; ++m) mfma(1, m);
     };
-    for (int c = 0; c < nchunks; c += 4) {                  // nchunks is a multiple of 4
-        chunk_body(c, 0, 0);
-        chunk_body(c + 1, 1, 1);
-        chunk_body(c + 2, 0, 2);
-        chunk_body(c + 3, 1, 3);
+    for (int d = 0; d < nruns; d += 4) {                    // nruns is a multiple of 4
+        chunk_body(d, 0, 0);
+        chunk_body(d, 1, 0);
+        chunk_body(d + 1, 0, 1);
+        chunk_body(d + 1, 1, 1);
+        chunk_body(d + 2, 0, 2);
+        chunk_body(d + 2, 1, 2);
+        chunk_body(d + 3, 0, 3);
+        chunk_body(d + 3, 1, 3);
     }
 
     // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4.  One
@@ -232,9 +249,8 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const v4i* __restric
     // LDS and leaves in 16-byte stores that cover whole lines.  Streaming stores when C is not read.
     int32_t* Ch = C + (size_t)h * N * N;
     const int col_in = lane & 31, half = lane >> 5, row_in = half * 4;
-    constexpr int TROW = 512 + 16;                                       // padded: the 16-byte slots of 8 consecutive lanes differ
     int8_t* tbuf = lds + wave * (32 * TROW);
-    const int gi_base = ti * TILE + wy * 128;
+    const int gi_base = ti * TM + wy * 128;
     // Addresses are a wave-uniform row pointer (scalar arithmetic) plus one per-lane element offset
     // that is the same for every store of a tile.
     const uint32_t lane_direct = (uint32_t)row_in * (uint32_t)N + col_in;
@@ -246,8 +262,8 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const v4i* __restric
     auto emit = [&](auto guard_tag) __attribute__((always_inline)) {
         constexpr bool GUARD = decltype(guard_tag)::value;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int gj_base = tj * TILE + wx * 128 + j * 32;
+        for (int j = 0; j < 2; ++j) {
+            const int gj_base = tj * TN + wx * 64 + j * 32;
             // park the 128 x 32 block as [column][row] for the mirrored tile; the LDS executes one wave's
             // accesses in order, so the block of the previous j has been read by then
             if (VEC && !diag) {
@@ -325,14 +341,14 @@ __global__ __launch_bounds__(256, 1) void coact_syrk_kernel(const v4i* __restric
             }
         }
     };
-    if (MODE == 0 && (ti + 1) * TILE <= N && (tj + 1) * TILE <= N) emit(std::false_type{});   // whole tile inside C: no per-store checks
+    if (MODE == 0 && (ti + 1) * TM <= N && (tj + 1) * TN <= N) emit(std::false_type{});   // whole tile inside C: no per-store checks
     else emit(std::true_type{});
 }
 
 }  // namespace
 
 swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
-                                int nchunks, uint32_t flags) {
+                                int nruns, uint32_t flags) {
     if (flags & SWARM_CHECK_IDX) {
         hipLaunchKernelGGL(check_distinct_kernel, dim3((unsigned)(rows * H)), dim3(256), 0, ctx->stream, idx, k,
                            ctx->dev_flags);
@@ -351,31 +367,34 @@ swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows
         }
         lds_opt_in = true;
     }
-    const dim3 grid((unsigned)nchunks, (unsigned)H, (unsigned)((Npad + TRACE_SPAN - 1) / TRACE_SPAN));
-    hipLaunchKernelGGL(trace_build_kernel, grid, dim3(1024), lds_bytes, ctx->stream, idx, rows, H, k, N, Npad, nchunks,
+    const dim3 grid((unsigned)nruns, (unsigned)H, (unsigned)((Npad + TRACE_SPAN - 1) / TRACE_SPAN));
+    hipLaunchKernelGGL(trace_build_kernel, grid, dim3(1024), lds_bytes, ctx->stream, idx, rows, H, k, N, Npad, nruns,
                        reinterpret_cast<uint4*>(ctx->trace), ctx->dev_flags);
     return swarm_check_launch(ctx, "trace_build_kernel");
 }
 
-// Order in which the upper-triangle tiles are handed out: super-blocks of 4 x 8 tiles, so that the
-// ~32 workgroups resident on one XCD share 4 A panels and 8 B panels in its L2.
-static swarm_status ensure_tile_order(swarm_ctx* ctx, int nt) {
-    if (ctx->tile_order && ctx->tile_order_nt == nt) return SWARM_OK;
-    const size_t count = (size_t)nt * (nt + 1) / 2;
+// Order in which the tiles on or above the diagonal are handed out: super-blocks of 4 x 16 tiles
+// (1024 x 2048 entries), so that the workgroups resident on one XCD share few panels in its L2.
+// Tile (ti, tj) covers rows [256 ti, +256) and columns [128 tj, +128); the tiles of a row start at
+// tj = 2 ti, the left half of the diagonal block.
+static swarm_status ensure_tile_order(swarm_ctx* ctx, int ntm) {
+    if (ctx->tile_order && ctx->tile_order_nt == ntm) return SWARM_OK;
+    const int ntn = 2 * ntm;
+    const size_t count = (size_t)ntm * (ntm + 1);
     int32_t* host = static_cast<int32_t*>(malloc(count * sizeof(int32_t)));
     if (!host) return SWARM_ENOMEM;
     size_t n = 0;
-    for (int bi = 0; bi < nt; bi += 4)
-        for (int bj = bi / 8 * 8; bj < nt; bj += 8)
-            for (int ti = bi; ti < bi + 4 && ti < nt; ++ti)
-                for (int tj = (bj > ti ? bj : ti); tj < bj + 8 && tj < nt; ++tj) host[n++] = (ti << 16) | tj;
+    for (int bi = 0; bi < ntm; bi += 4)
+        for (int bj = 2 * bi / 16 * 16; bj < ntn; bj += 16)
+            for (int ti = bi; ti < bi + 4 && ti < ntm; ++ti)
+                for (int tj = (bj > 2 * ti ? bj : 2 * ti); tj < bj + 16 && tj < ntn; ++tj) host[n++] = (ti << 16) | tj;
     swarm_status st = SWARM_OK;
     if (n != count) {
         snprintf(ctx->err, sizeof(ctx->err), "coact: tile order covers %zu of %zu tiles", n, count);
         st = SWARM_EINVAL;
     }
     if (st == SWARM_OK) {
-        size_t have = ctx->tile_order ? (size_t)ctx->tile_order_nt * (ctx->tile_order_nt + 1) / 2 * 4 : 0;
+        size_t have = ctx->tile_order ? (size_t)ctx->tile_order_nt * (ctx->tile_order_nt + 1) * 4 : 0;
         st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->tile_order), &have, count * 4);
     }
     if (st == SWARM_OK) {
@@ -385,22 +404,22 @@ static swarm_status ensure_tile_order(swarm_ctx* ctx, int nt) {
             snprintf(ctx->err, sizeof(ctx->err), "coact: tile order upload failed: %s", hipGetErrorString(e));
             st = SWARM_EHIP;
         } else {
-            ctx->tile_order_nt = nt;
+            ctx->tile_order_nt = ntm;
         }
     }
     free(host);
     return st;
 }
 
-swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nchunks, int32_t* C, uint32_t decay_q16) {
-    const int nt = Npad / TILE;
-    const int64_t tiles_per_head = (int64_t)nt * (nt + 1) / 2;
+swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16) {
+    const int ntm = Npad / TM;
+    const int64_t tiles_per_head = (int64_t)ntm * (ntm + 1);
     const int64_t total = tiles_per_head * H;
-    if (total > (int64_t)1 << 30 || nt > 32767) {
+    if (total > (int64_t)1 << 30 || 2 * ntm > 65535) {
         snprintf(ctx->err, sizeof(ctx->err), "coact: N=%d, H=%d give too many tiles for one launch", N, H);
         return SWARM_EINVAL;
     }
-    swarm_status st = ensure_tile_order(ctx, nt);
+    swarm_status st = ensure_tile_order(ctx, ntm);
     if (st != SWARM_OK) return st;
     const int per_xcd = (int)((total + 7) / 8);
     const int mode = decay_q16 == 0u ? 0 : decay_q16 == 65536u ? 1 : 2;
@@ -425,7 +444,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nchun
     dim3 grid((unsigned)(per_xcd * 8)), block(256);
     const int tph = (int)tiles_per_head, tot = (int)total;
     hipLaunchKernelGGL(kernels[mode][vec ? 1 : 0], grid, block, SYRK_LDS_BYTES, ctx->stream,
-                       reinterpret_cast<const v4i*>(ctx->trace), N, Npad, nchunks, C, decay_q16, tph, tot, per_xcd,
+                       reinterpret_cast<const v4i*>(ctx->trace), N, Npad, nruns, C, decay_q16, tph, tot, per_xcd,
                        static_cast<const int32_t*>(ctx->tile_order));
     return swarm_check_launch(ctx, "coact_syrk_kernel");
 }

@@ -22,7 +22,7 @@ struct swarm_ctx {
     size_t scores_bytes = 0;
     uint16_t* weights = nullptr;   // folded query weights of the batched scorer: bf16 hi then lo, each [B][H][L]
     size_t weights_bytes = 0;
-    void* trace = nullptr;         // binary trace as bits: uint4 [H][chunks of 128 rows][Npad]
+    void* trace = nullptr;         // binary trace as bits: uint4 [H][runs of 128 rows][Npad]
     size_t trace_bytes = 0;
     uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
     int32_t* tile_order = nullptr; // co-activation tile schedule for tile_order_nt tiles per edge
@@ -54,8 +54,8 @@ constexpr int SWARM_BATCHED_MIN_STREAMS = 8;   // from this many streams on, sco
 swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores);
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx);
 swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
-                                int nchunks, uint32_t flags);
-swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nchunks, int32_t* C, uint32_t decay_q16);
+                                int nruns, uint32_t flags);
+swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16);
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                         const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap);
