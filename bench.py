@@ -100,11 +100,13 @@ def main():
     def coact():
         sw.coact_accumulate(idx_all, N, Cm, decay_q16=0)
 
-    def whole_pass():
+    def decode_steps():
         for t in range(T):
-            sw.score_select(cfg.unit, layers[t % len(layers)], q_d[t], k, G=cfg.G, out_idx=idx_all[t:t + 1])
-            sw.map_requests(idx_all[t], H, N, e2c_d, cfg.Nc, rep_d, cfg.D, w_d, cap=cap,
-                            out=(q_off[t], q_clu[t], q_load[t]))
+            sw.step(cfg.unit, layers[t % len(layers)], q_d[t, 0], k, e2c_d, cfg.Nc, rep_d, cfg.D, G=cfg.G, weight=w_d,
+                    cap=cap, out_idx=idx_all[t], out=(q_off[t], q_clu[t], q_load[t]))
+
+    def whole_pass():
+        decode_steps()
         coact()
 
     def make_runner(fn):
@@ -146,6 +148,9 @@ def main():
     run_sc = make_runner(score_steps)
     _, ev_sc = timed(run_sc, max(2, args.steps // 2), 1)
     score_us = ev_sc / (max(2, args.steps // 2) * T) * 1e6
+    run_dec = make_runner(decode_steps)
+    _, ev_dec = timed(run_dec, max(2, args.steps // 2), 1)
+    step_us = ev_dec / (max(2, args.steps // 2) * T) * 1e6
     run_map = make_runner(map_steps)
     _, ev_map = timed(run_map, max(2, args.steps // 2), 1)
     map_us = ev_map / (max(2, args.steps // 2) * T) * 1e6
@@ -179,7 +184,8 @@ def main():
                            "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(coact_tops / INT8_MFMA_PEAK_TOPS, 4),
                            "issued_ops": issued_ops, "dense_equivalent_tops": round(dense_ops / (coact_ms * 1e-3) / 1e12, 1),
                            "ms_per_build_incl_trace": round(coact_ms, 3)},
-        "stages": {"score_us_per_step": round(score_us, 3), "score_select_us_per_step": round(sel_us, 3), "map_us_per_step": round(map_us, 3),
+        "stages": {"step_us": round(step_us, 3), "score_us_per_step": round(score_us, 3),
+                   "score_select_us_per_step": round(sel_us, 3), "map_us_per_step": round(map_us, 3),
                    "coact_ms_per_pass": round(coact_ms, 3),
                    "score_select_steps_per_s": round(1e6 / sel_us, 1), "event_s_per_pass": round(ev / args.steps, 5)},
         "paper_context": "paper reports 2.41x lower I/O time and 2.72x higher bandwidth utilisation (Xeon 6530, 8x H20, "

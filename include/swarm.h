@@ -114,8 +114,8 @@ swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, 
  * i and j are activated together; the diagonal is an entry's own activation count).
  *
  * The `rows` selections are scattered into a binary trace A (rows x N per head, kept entry-major
- * as int8 in the context's scratch) and C[h] is updated with A^T A computed exactly in int32 by
- * int8 matrix-core instructions:
+ * as bits in the context's scratch, expanded to int8 0/1 on the way to the matrix cores) and C[h] is
+ * updated with A^T A computed exactly in int32 by int8 matrix-core instructions:
  *     decay_q16 == 65536 : C += A^T A
  *     decay_q16 == 0     : C  = A^T A            (C is not read)
  *     otherwise          : C  = floor((C * decay_q16 + 2^15) / 2^16) + A^T A   (int64 intermediate)
@@ -129,8 +129,8 @@ swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, 
  * C      device, int32 [H][N][N] row-major, in/out, 16-byte aligned.
  * flags  SWARM_CHECK_IDX additionally flags repeated entries (SWARM_DEV_DUP_ENTRY); a repeated
  *        entry counts once either way, because the trace is binary.
- * Errors: SWARM_EINVAL as above or decay_q16 > 65536; SWARM_ENOMEM if the trace (H*N*rows bytes,
- * rows rounded up to 256, N to 256) cannot be allocated.
+ * Errors: SWARM_EINVAL as above or decay_q16 > 65536; SWARM_ENOMEM if the trace (H*N*rows/8 bytes,
+ * rows rounded up to 512, N to 256) cannot be allocated.
  */
 swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int32_t H, int32_t k,
                                     int32_t N, int32_t* C, uint32_t decay_q16, uint32_t flags);
@@ -167,6 +167,22 @@ swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t grou
                                 const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
                                 const int32_t* weight, const uint32_t* resident,
                                 int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap);
+
+/*
+ * One decode step of a single stream: swarm_score_select with B = 1 followed by swarm_map_requests on
+ * that selection (groups = H, one per KV head; S = k), with identical results (Sections 2.3 and 6.1:
+ * the entries activated at a step are what the step requests from the SSDs).  The step's three
+ * stages depend on each other, so their cost is latency, not throughput; here selection and mapping
+ * run in one kernel where the shapes allow it (the mapping's lookup tables load while the selection
+ * runs), and otherwise as the two calls would.
+ * Arguments as in swarm_score_select (q: bf16 [H*G][d]; out_idx: int32 [H][k]; out_scores fp32 [H][N]
+ * or NULL) and swarm_map_requests (N = keys->N; q_off [H][D+1], q_cluster [H][cap], q_load [H][D]).
+ * Errors: those of the two calls.
+ */
+swarm_status swarm_step(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t k, int32_t* out_idx,
+                        float* out_scores, const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
+                        const int32_t* weight, const uint32_t* resident, int32_t* q_off, int32_t* q_cluster,
+                        int32_t* q_load, int32_t cap);
 
 /*
  * Replay of a recorded call sequence.  The per-step work of the path is a handful of short kernels,

@@ -19,7 +19,7 @@ SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
 
 EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score", "swarm_score_select",
-           "swarm_coact_accumulate", "swarm_map_requests", "swarm_capture_begin", "swarm_capture_end",
+           "swarm_coact_accumulate", "swarm_map_requests", "swarm_step", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
 
 
@@ -55,6 +55,7 @@ def load() -> C.CDLL:
     L.swarm_score.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, vp]
     L.swarm_coact_accumulate.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, u32]
     L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
+    L.swarm_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_capture_begin.argtypes = [vp]
     L.swarm_capture_end.argtypes = [vp, C.POINTER(vp)]
     L.swarm_graph_launch.argtypes = [vp, vp]
@@ -100,6 +101,15 @@ def swarm_score_select(ctx: int, kind: int, data: int, H: int, N: int, d: int, G
 def swarm_score(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q: int, B: int, out_scores: int) -> int:
     ks = swarm_keys(kind, data, H, N, d, G)
     return load().swarm_score(C.c_void_p(ctx), C.byref(ks), C.c_void_p(q), B, C.c_void_p(out_scores))
+
+
+def swarm_step(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q: int, k: int, out_idx: int,
+               out_scores: Optional[int], e2c: int, Nc: int, replicas: int, R: int, D: int, weight: Optional[int],
+               resident: Optional[int], q_off: int, q_cluster: int, q_load: int, cap: int) -> int:
+    ks = swarm_keys(kind, data, H, N, d, G)
+    return load().swarm_step(C.c_void_p(ctx), C.byref(ks), C.c_void_p(q), k, C.c_void_p(out_idx), C.c_void_p(out_scores),
+                             C.c_void_p(e2c), Nc, C.c_void_p(replicas), R, D, C.c_void_p(weight), C.c_void_p(resident),
+                             C.c_void_p(q_off), C.c_void_p(q_cluster), C.c_void_p(q_load), cap)
 
 
 def swarm_coact_accumulate(ctx: int, idx: int, rows: int, H: int, k: int, N: int, Cptr: int, decay_q16: int,
@@ -249,6 +259,47 @@ class Swarm:
                                 self._dev(q_load, torch.int32, "q_load"), cap)
         self._check("swarm_map_requests", rc)
         return q_off, q_cluster, q_load
+
+    def step(self, kind: str, keys, q, k: int, e2c, Nc: int, replicas, D: int, G: int = 1, weight=None, resident=None,
+             cap: Optional[int] = None, out_idx=None, out_scores=None, want_scores: bool = False, out=None):
+        """One decode step of one stream: q [H*G][d] -> (idx int32 [H][k], scores or None, (q_off, q_cluster, q_load))."""
+        torch = self.torch
+        b16 = (torch.bfloat16, torch.int16, torch.uint16)
+        H, N, d = keys.shape[0], keys.shape[1], keys.shape[-1]
+        R = replicas.shape[1]
+        if tuple(q.shape) != (H * G, d):
+            raise ValueError(f"q has shape {tuple(q.shape)}, expected {(H * G, d)}")
+        want = (H, N, d) if kind == "token" else (H, N, 2, d)
+        if tuple(keys.shape) != want:
+            raise ValueError(f"keys has shape {tuple(keys.shape)}, expected {want}")
+        if tuple(e2c.shape) != (H, N) or tuple(replicas.shape) != (H * Nc, R):
+            raise ValueError("e2c must be [H][N] and replicas [H*Nc][R]")
+        if weight is not None and tuple(weight.shape) != (H * Nc,):
+            raise ValueError("weight must be [H*Nc]")
+        if resident is not None and resident.numel() < (H * Nc + 31) // 32:
+            raise ValueError("resident bitmap too short")
+        if cap is None:
+            cap = min(k, Nc)
+        if out_idx is None:
+            out_idx = torch.empty((H, k), dtype=torch.int32, device=self.device)
+        if out_scores is None and want_scores:
+            out_scores = torch.empty((H, N), dtype=torch.float32, device=self.device)
+        if out is None:
+            out = (torch.empty((H, D + 1), dtype=torch.int32, device=self.device),
+                   torch.empty((H, cap), dtype=torch.int32, device=self.device),
+                   torch.empty((H, D), dtype=torch.int32, device=self.device))
+        q_off, q_cluster, q_load = out
+        rc = swarm_step(self.ctx, SWARM_KEYS_TOKEN if kind == "token" else SWARM_KEYS_PAGE_MINMAX,
+                        self._dev(keys, b16, "keys"), H, N, d, G, self._dev(q, b16, "q"), k,
+                        self._dev(out_idx, torch.int32, "out_idx"),
+                        None if out_scores is None else self._dev(out_scores, torch.float32, "out_scores"),
+                        self._dev(e2c, torch.int32, "e2c"), Nc, self._dev(replicas, torch.int32, "replicas"), R, D,
+                        None if weight is None else self._dev(weight, torch.int32, "weight"),
+                        None if resident is None else self._dev(resident, (torch.int32, torch.uint32), "resident"),
+                        self._dev(q_off, torch.int32, "q_off"), self._dev(q_cluster, torch.int32, "q_cluster"),
+                        self._dev(q_load, torch.int32, "q_load"), cap)
+        self._check("swarm_step", rc)
+        return out_idx, out_scores, out
 
     def capture_begin(self):
         self._check("swarm_capture_begin", swarm_capture_begin(self.ctx))

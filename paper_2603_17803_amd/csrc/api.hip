@@ -163,23 +163,64 @@ swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t 
     return launch_coact_syrk(ctx, H, N, Npad, nruns, C, decay_q16);
 }
 
+static swarm_status check_map_args(swarm_ctx* ctx, const char* fn, int64_t groups, int32_t S, int32_t H, int32_t N,
+                                   const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
+                                   const int32_t* q_off, const int32_t* q_cluster, const int32_t* q_load, int32_t cap) {
+    if (!e2c || !replicas || !q_off || !q_cluster || !q_load) SWARM_REJECT(ctx, "%s: NULL required pointer", fn);
+    if (groups < 1 || groups > ((int64_t)1 << 30) || S < 1 || H < 1 || N < 1 || Nc < 1 || cap < 1)
+        SWARM_REJECT(ctx, "%s: groups=%lld S=%d H=%d N=%d Nc=%d cap=%d must all be >= 1", fn, (long long)groups, S, H, N,
+                     Nc, cap);
+    if (R < 1 || R > D || D > 64) SWARM_REJECT(ctx, "%s: need 1 <= R=%d <= D=%d <= 64", fn, R, D);
+    if (Nc > (1 << 20)) SWARM_REJECT(ctx, "%s: Nc=%d above 2^20", fn, Nc);
+    const size_t lds = ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + 64) * 4;
+    if (lds > 64u * 1024u)
+        SWARM_REJECT(ctx, "%s: cap=%d and Nc=%d need %zu bytes of on-chip staging (limit 64 KiB)", fn, cap, Nc, lds);
+    return SWARM_OK;
+}
+
 swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int32_t S, int32_t H, int32_t N,
                                 const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
                                 const int32_t* weight, const uint32_t* resident,
                                 int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap) {
     if (!ctx) return SWARM_EINVAL;
-    if (!sel || !e2c || !replicas || !q_off || !q_cluster || !q_load)
-        SWARM_REJECT(ctx, "map_requests: NULL required pointer");
-    if (groups < 1 || groups > ((int64_t)1 << 30) || S < 1 || H < 1 || N < 1 || Nc < 1 || cap < 1)
-        SWARM_REJECT(ctx, "map_requests: groups=%lld S=%d H=%d N=%d Nc=%d cap=%d must all be >= 1", (long long)groups,
-                     S, H, N, Nc, cap);
-    if (R < 1 || R > D || D > 64) SWARM_REJECT(ctx, "map_requests: need 1 <= R=%d <= D=%d <= 64", R, D);
-    if (Nc > (1 << 20)) SWARM_REJECT(ctx, "map_requests: Nc=%d above 2^20", Nc);
-    const size_t lds = ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + 64) * 4;
-    if (lds > 64u * 1024u)
-        SWARM_REJECT(ctx, "map_requests: cap=%d and Nc=%d need %zu bytes of on-chip staging (limit 64 KiB)", cap, Nc, lds);
+    if (!sel) SWARM_REJECT(ctx, "map_requests: NULL sel");
+    const swarm_status st = check_map_args(ctx, "map_requests", groups, S, H, N, e2c, Nc, replicas, R, D, q_off, q_cluster,
+                                           q_load, cap);
+    if (st != SWARM_OK) return st;
     return launch_map(ctx, sel, groups, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load,
                       cap);
+}
+
+swarm_status swarm_step(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t k, int32_t* out_idx,
+                        float* out_scores, const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
+                        const int32_t* weight, const uint32_t* resident, int32_t* q_off, int32_t* q_cluster,
+                        int32_t* q_load, int32_t cap) {
+    if (!ctx) return SWARM_EINVAL;
+    swarm_status st = check_score_args(ctx, "step", keys, q, 1);
+    if (st != SWARM_OK) return st;
+    if (!out_idx) SWARM_REJECT(ctx, "step: NULL out_idx");
+    if (k < 1 || k > keys->N) SWARM_REJECT(ctx, "step: k=%d outside [1,N=%d]", k, keys->N);
+    if (out_scores && (reinterpret_cast<uintptr_t>(out_scores) & 3)) SWARM_REJECT(ctx, "step: out_scores misaligned");
+    st = check_map_args(ctx, "step", keys->H, k, keys->H, keys->N, e2c, Nc, replicas, R, D, q_off, q_cluster, q_load, cap);
+    if (st != SWARM_OK) return st;
+
+    float* scores = out_scores;
+    if (!scores) {
+        st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->scores), &ctx->scores_bytes,
+                        sizeof(float) * (size_t)keys->H * keys->N);
+        if (st != SWARM_OK) return st;
+        scores = ctx->scores;
+    }
+    st = launch_score(ctx, keys, q, 1, scores);
+    if (st != SWARM_OK) return st;
+    bool fused = false;
+    st = launch_select_map(ctx, scores, keys->H, keys->N, k, out_idx, e2c, Nc, replicas, R, D, weight, resident, q_off,
+                           q_cluster, q_load, cap, &fused);
+    if (st != SWARM_OK || fused) return st;
+    st = launch_select(ctx, scores, keys->H, keys->N, k, out_idx);
+    if (st != SWARM_OK) return st;
+    return launch_map(ctx, out_idx, keys->H, k, keys->H, keys->N, e2c, Nc, replicas, R, D, weight, resident, q_off,
+                      q_cluster, q_load, cap);
 }
 
 swarm_status swarm_capture_begin(swarm_ctx* ctx) {

@@ -59,6 +59,10 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                         const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap);
+swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N, int k, int32_t* out_idx,
+                               const int32_t* e2c, int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
+                               const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap,
+                               bool* launched);
 
 static inline swarm_status swarm_check_launch(swarm_ctx* ctx, const char* what) {
     hipError_t e = hipGetLastError();

@@ -11,6 +11,7 @@
 // replica with ties to the lower SSD id, and only the compare-and-add of the winner stays on the
 // dependent path.  Bucket positions are computed afterwards, in parallel, from the winners.
 #include "common.h"
+#include "select_core.h"
 #include "wave_ops.h"
 
 namespace {
@@ -113,91 +114,111 @@ constexpr int MAP_THREADS = 256;
 // Copies n words from global memory to LDS with batches of independent loads (all loads of a batch
 // are in flight together, so a small table costs one memory round trip).  16-byte loads when the
 // source allows it.
+template <int NT>
 __device__ __forceinline__ void stage_words(int32_t* __restrict__ dst, const int32_t* __restrict__ src, int n, int tid) {
     constexpr int BATCH = 8;
     if (((reinterpret_cast<uintptr_t>(src) & 15) == 0) && (n & 3) == 0) {
         const int n4 = n >> 2;
         const int4* s4 = reinterpret_cast<const int4*>(src);
         int4* d4 = reinterpret_cast<int4*>(dst);
-        for (int base = 0; base < n4; base += BATCH * MAP_THREADS) {
+        for (int base = 0; base < n4; base += BATCH * NT) {
             int4 v[BATCH];
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
-                const int i = base + u * MAP_THREADS + tid;
+                const int i = base + u * NT + tid;
                 v[u] = (i < n4) ? s4[i] : make_int4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
-                const int i = base + u * MAP_THREADS + tid;
+                const int i = base + u * NT + tid;
                 if (i < n4) d4[i] = v[u];
             }
         }
     } else {
-        for (int base = 0; base < n; base += BATCH * MAP_THREADS) {
+        for (int base = 0; base < n; base += BATCH * NT) {
             int32_t v[BATCH];
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
-                const int i = base + u * MAP_THREADS + tid;
+                const int i = base + u * NT + tid;
                 v[u] = (i < n) ? src[i] : 0;
             }
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
-                const int i = base + u * MAP_THREADS + tid;
+                const int i = base + u * NT + tid;
                 if (i < n) dst[i] = v[u];
             }
         }
     }
 }
 
-// Block of 4 waves.  All waves cooperate on staging and on the merge; wave 0 alone runs the
-// compaction, the chain and the emission (the chain is a single-wave algorithm).  When the head's
-// lookup tables are small they are staged in LDS by one burst of independent loads issued at kernel
-// start, so that the whole kernel pays one memory round trip instead of three dependent ones
-// (selection -> cluster of entry -> replica row).
-__global__ __launch_bounds__(MAP_THREADS) void map_requests_kernel(MapArgs a, int stage_e2c, int stage_tab) {
-    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
-    const int nwords = (a.Nc + 31) / 32;
-    uint32_t* bitmap = smem;
-    uint32_t* list = bitmap + nwords;
-    uint32_t* mask_lo = list + a.cap;
-    uint32_t* mask_hi = mask_lo + a.cap;
-    uint32_t* wgt = mask_hi + a.cap;
-    uint32_t* order = wgt + a.cap;
-    uint32_t* assign = order + a.cap;
-    uint32_t* off = assign + a.cap;                 // 64 words
-    int32_t* s_e2c = reinterpret_cast<int32_t*>(smem + ((off + 64 - smem + 3) & ~3));   // N words when staged (16-byte aligned)
-    int32_t* s_rep = s_e2c + (stage_e2c ? ((a.N + 3) & ~3) : 0);                // Nc*R words when staged
-    int32_t* s_wgt = s_rep + (stage_tab ? ((a.Nc * a.R + 3) & ~3) : 0);         // Nc words when staged
+// LDS layout shared by the stand-alone and the fused kernel.
+struct MapLds {
+    uint32_t *bitmap, *list, *mask_lo, *mask_hi, *wgt, *order, *assign, *off;
+    int32_t *s_e2c, *s_rep, *s_wgt;
+    int nwords;
+    __device__ __forceinline__ MapLds(uint32_t* smem, const MapArgs& a, int stage_e2c, int stage_tab) {
+        nwords = (a.Nc + 31) / 32;
+        bitmap = smem;
+        list = bitmap + nwords;
+        mask_lo = list + a.cap;
+        mask_hi = mask_lo + a.cap;
+        wgt = mask_hi + a.cap;
+        order = wgt + a.cap;
+        assign = order + a.cap;
+        off = assign + a.cap;                 // 64 words
+        s_e2c = reinterpret_cast<int32_t*>(smem + ((off + 64 - smem + 3) & ~3));   // N words when staged (16-byte aligned)
+        s_rep = s_e2c + (stage_e2c ? ((a.N + 3) & ~3) : 0);                // Nc*R words when staged
+        s_wgt = s_rep + (stage_tab ? ((a.Nc * a.R + 3) & ~3) : 0);         // Nc words when staged
+    }
+};
+
+// One group on a block of NT threads.  All waves cooperate on staging and on the merge; wave 0
+// alone runs the compaction, the chain and the emission (the chain is a single-wave algorithm).
+// When the head's lookup tables are small they are staged in LDS by one burst of independent loads,
+// so that the kernel pays one memory round trip instead of three dependent ones (selection ->
+// cluster of entry -> replica row).  PRESTAGED: the caller has already filled the staged tables,
+// cleared the bitmap and synchronised, and `sel` points into LDS.
+template <int NT, bool PRESTAGED>
+__device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int32_t* __restrict__ sel, uint32_t* smem,
+                                          int stage_e2c, int stage_tab) {
+    const MapLds L(smem, a, stage_e2c, stage_tab);
+    const int nwords = L.nwords;
+    uint32_t *bitmap = L.bitmap, *list = L.list, *mask_lo = L.mask_lo, *mask_hi = L.mask_hi, *wgt = L.wgt, *order = L.order,
+             *assign = L.assign, *off = L.off;
+    int32_t *s_e2c = L.s_e2c, *s_rep = L.s_rep, *s_wgt = L.s_wgt;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t g = blockIdx.x;
+
     const int h = (int)(g % a.H);
     const int64_t cbase = (int64_t)h * a.Nc;
     uint32_t flags = 0;
 
-    // burst of independent loads: the selection into registers, the tables into LDS
-    const int32_t* sel = a.sel + g * a.S;
     const int32_t* e2c = a.e2c + (size_t)h * a.N;
     constexpr int SEL_REGS = 4;
     int32_t my_sel[SEL_REGS];
+    if (!PRESTAGED) {
+        // burst of independent loads: the selection into registers, the tables into LDS
 #pragma unroll
-    for (int r = 0; r < SEL_REGS; ++r) {
-        const int s0 = tid + r * MAP_THREADS;
-        my_sel[r] = (s0 < a.S) ? sel[s0] : -1;
+        for (int r = 0; r < SEL_REGS; ++r) {
+            const int s0 = tid + r * NT;
+            my_sel[r] = (s0 < a.S) ? sel[s0] : -1;
+        }
+        if (stage_tab) {
+            stage_words<NT>(s_rep, a.replicas + cbase * a.R, a.Nc * a.R, tid);
+            if (a.weight) stage_words<NT>(s_wgt, a.weight + cbase, a.Nc, tid);
+            else for (int i = tid; i < a.Nc; i += NT) s_wgt[i] = 1;
+        }
+        if (stage_e2c) stage_words<NT>(s_e2c, e2c, a.N, tid);
+        for (int w = tid; w < nwords; w += NT) bitmap[w] = 0;
+        __syncthreads();
     }
-    if (stage_tab) {
-        stage_words(s_rep, a.replicas + cbase * a.R, a.Nc * a.R, tid);
-        if (a.weight) stage_words(s_wgt, a.weight + cbase, a.Nc, tid);
-        else for (int i = tid; i < a.Nc; i += MAP_THREADS) s_wgt[i] = 1;
-    }
-    if (stage_e2c) stage_words(s_e2c, e2c, a.N, tid);
-    for (int w = tid; w < nwords; w += MAP_THREADS) bitmap[w] = 0;
-    __syncthreads();
 
     // merge: one bit per activated, non-resident cluster
-    for (int s0 = tid, r = 0; s0 < a.S; s0 += MAP_THREADS, ++r) {
+    for (int s0 = tid, r = 0; s0 < a.S; s0 += NT, ++r) {
         int32_t e;
-        if (r < SEL_REGS) {
+        if (PRESTAGED) {
+            e = sel[s0];
+        } else if (r < SEL_REGS) {
             e = my_sel[0];
 #pragma unroll
             for (int rr = 1; rr < SEL_REGS; ++rr) e = (r == rr) ? my_sel[rr] : e;
@@ -331,6 +352,64 @@ __global__ __launch_bounds__(MAP_THREADS) void map_requests_kernel(MapArgs a, in
     if (flags) atomicOr(a.dev_flags, flags);
 }
 
+__global__ __launch_bounds__(MAP_THREADS) void map_requests_kernel(MapArgs a, int stage_e2c, int stage_tab) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+    const int64_t g = blockIdx.x;
+    map_group<MAP_THREADS, false>(a, g, a.sel + g * a.S, smem, stage_e2c, stage_tab);
+}
+
+// Selection and request mapping of one decode step of a single stream in one kernel: block h selects
+// the k entries of head h (selcore::block_select, into LDS), writes them out, and maps them.  The
+// lookup tables of the mapping do not depend on the selection: their loads are issued first and are
+// in flight while the selection runs.  Per thread: up to 2 x 16 bytes of the entry->cluster table,
+// 16 bytes of the replica table and 16 bytes of the weights (the host stages a table only if it fits
+// that and is 16-byte aligned).
+template <int IPT>
+__global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __restrict__ scores, int N, int k,
+                                                                 int32_t* __restrict__ out_idx, MapArgs a, int stage_e2c,
+                                                                 int stage_tab, int sel_off) {
+    __shared__ selcore::Smem sm;
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+    constexpr int NT = selcore::NT;
+    const int tid = threadIdx.x;
+    const int h = blockIdx.x;                                 // one stream: group = head
+    const int64_t cbase = (int64_t)h * a.Nc;
+    const MapLds L(smem, a, stage_e2c, stage_tab);
+
+    int4 r_e2c[2] = {make_int4(0, 0, 0, 0), make_int4(0, 0, 0, 0)}, r_rep = make_int4(0, 0, 0, 0), r_wgt = make_int4(0, 0, 0, 0);
+    const int n4_e2c = a.N >> 2, n4_rep = (a.Nc * a.R) >> 2, n4_wgt = a.Nc >> 2;
+    if (stage_e2c) {
+        const int4* src = reinterpret_cast<const int4*>(a.e2c + (size_t)h * a.N);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            if (tid + u * NT < n4_e2c) r_e2c[u] = src[tid + u * NT];
+    }
+    if (stage_tab) {
+        if (tid < n4_rep) r_rep = reinterpret_cast<const int4*>(a.replicas + cbase * a.R)[tid];
+        if (a.weight && tid < n4_wgt) r_wgt = reinterpret_cast<const int4*>(a.weight + cbase)[tid];
+    }
+    for (int w = tid; w < L.nwords; w += NT) L.bitmap[w] = 0;
+
+    int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + sel_off);
+    uint32_t key[IPT];
+    selcore::load_keys<IPT>(scores + (size_t)h * N, N, key);
+    selcore::block_select<IPT>(key, N, k, sel_lds, sm);
+
+    if (stage_e2c) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            if (tid + u * NT < n4_e2c) reinterpret_cast<int4*>(L.s_e2c)[tid + u * NT] = r_e2c[u];
+    }
+    if (stage_tab) {
+        if (tid < n4_rep) reinterpret_cast<int4*>(L.s_rep)[tid] = r_rep;
+        if (a.weight) { if (tid < n4_wgt) reinterpret_cast<int4*>(L.s_wgt)[tid] = r_wgt; }
+        else for (int i = tid; i < a.Nc; i += NT) L.s_wgt[i] = 1;
+    }
+    __syncthreads();
+    for (int i = tid; i < k; i += NT) out_idx[(size_t)h * k + i] = sel_lds[i];
+    map_group<NT, true>(a, h, sel_lds, smem, stage_e2c, stage_tab);
+}
+
 }  // namespace
 
 size_t map_lds_base_bytes(int Nc, int cap) { return ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + 64) * 4; }
@@ -349,4 +428,41 @@ swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int 
     hipLaunchKernelGGL(map_requests_kernel, dim3((unsigned)groups), dim3(MAP_THREADS), lds, ctx->stream, a, stage_e2c,
                        stage_tab);
     return swarm_check_launch(ctx, "map_requests_kernel");
+}
+
+// Fused selection + mapping for one stream (groups = H, S = k).  Returns SWARM_OK after launching, or
+// SWARM_EINVAL *without touching ctx->err* when the shapes do not fit the fused kernel (the caller
+// then launches the two kernels separately).
+swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N, int k, int32_t* out_idx,
+                               const int32_t* e2c, int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
+                               const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap,
+                               bool* launched) {
+    *launched = false;
+    if (N > 64 * selcore::NT) return SWARM_OK;
+    constexpr int NT = selcore::NT;
+    MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags};
+    size_t lds = map_lds_base_bytes(Nc, cap);
+    const size_t budget = 64u * 1024u;
+    lds = (lds + 15) / 16 * 16;
+    int stage_tab = 0, stage_e2c = 0;
+    const size_t tab_bytes = ((size_t)Nc * R + 3) / 4 * 16 + ((size_t)Nc + 3) / 4 * 16, e2c_bytes = ((size_t)N + 3) / 4 * 16;
+    const bool tab_regs = (Nc * R) % 4 == 0 && Nc % 4 == 0 && Nc * R <= 4 * NT && Nc <= 4 * NT &&
+                          (reinterpret_cast<uintptr_t>(replicas) & 15) == 0 && (!weight || (reinterpret_cast<uintptr_t>(weight) & 15) == 0);
+    const bool e2c_regs = N % 4 == 0 && N <= 8 * NT && (reinterpret_cast<uintptr_t>(e2c) & 15) == 0;
+    if (tab_regs && lds + tab_bytes <= budget) { stage_tab = 1; lds += tab_bytes; }
+    if (e2c_regs && lds + e2c_bytes <= budget) { stage_e2c = 1; lds += e2c_bytes; }
+    const int sel_off = (int)(lds / 4);
+    lds += (size_t)k * 4;
+    if (lds > budget) return SWARM_OK;
+    const dim3 grid((unsigned)H), block(NT);
+    hipStream_t st = ctx->stream;
+#define SWARM_SELMAP(IPT) hipLaunchKernelGGL(select_map_kernel<IPT>, grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off)
+    if (N <= 4 * NT) SWARM_SELMAP(4);
+    else if (N <= 8 * NT) SWARM_SELMAP(8);
+    else if (N <= 16 * NT) SWARM_SELMAP(16);
+    else if (N <= 32 * NT) SWARM_SELMAP(32);
+    else SWARM_SELMAP(64);
+#undef SWARM_SELMAP
+    *launched = true;
+    return swarm_check_launch(ctx, "select_map_kernel");
 }

@@ -359,6 +359,56 @@ def test_whole_path_batched_grouped_scaled(sw):
     whole_path(sw, W.CONFIGS["drift_batch"].scaled(N=512, B=4, T=6, k=32), 6)
 
 
+# --------------------------------------------------------------------------- one-call decode step
+
+STEP_CASES = [
+    # (config, resident bitmap?, weights?)  -- shapes chosen to hit the fused kernel with both tables staged,
+    # with the entry->cluster table left in memory (N > 8192 or N not a multiple of 4), with the replica
+    # table left in memory (Nc*R not a multiple of 4) and the two-kernel route (k too large for staging)
+    (W.CONFIGS["long_128k"].scaled(T=3), False, True),
+    (W.CONFIGS["llama8b_32k"].scaled(T=3), True, True),
+    (W.CONFIGS["tiny"].scaled(T=3), False, False),
+    (W.CONFIGS["tiny"].scaled(N=1027, k=33, T=2, Nc=37, M=37, R=3, D=5), True, True),
+    (W.CONFIGS["token_stress"].scaled(N=12288, k=512, T=2), False, True),
+    (W.CONFIGS["token_stress"].scaled(N=65536, k=15000, T=1, Nc=2048), False, True),
+]
+
+
+@pytest.mark.parametrize("cfg,use_res,use_w", STEP_CASES,
+                         ids=lambda v: f"{v.name}-N{v.N}-k{v.k}-Nc{v.Nc}" if hasattr(v, "name") else str(v))
+def test_step_equals_score_select_then_map(sw, cfg, use_res, use_w):
+    """swarm_step against the two calls it stands for (bit-exact), and against the oracle stage by stage."""
+    K = W.keys(cfg)
+    Kd = dev(K)
+    e2c, weight, rep = W.cluster_tables(cfg)
+    e2c_d, rep_d = dev(e2c), dev(rep)
+    w_d = dev(weight) if use_w else None
+    res = None
+    if use_res:
+        rng = np.random.default_rng(cfg.seed + 5)
+        res = rng.integers(0, 2 ** 32, (cfg.H * cfg.Nc + 31) // 32, dtype=np.uint32) & rng.integers(0, 2 ** 32, (cfg.H * cfg.Nc + 31) // 32, dtype=np.uint32)
+    res_d = dev(res) if use_res else None
+    cap = min(cfg.k, cfg.Nc)
+    qs = W.queries(cfg, 0, cfg.T)
+    for t in range(cfg.T):
+        q_d = dev(qs[t])                                       # [1][H*G][d]
+        idx, sc, queues = sw.step(cfg.unit, Kd, q_d[0], cfg.k, e2c_d, cfg.Nc, rep_d, cfg.D, G=cfg.G, weight=w_d,
+                                  resident=res_d, cap=cap, want_scores=True)
+        idx2, sc2 = sw.score_select(cfg.unit, Kd, q_d, cfg.k, G=cfg.G, want_scores=True)
+        queues2 = sw.map_requests(idx2[0], cfg.H, cfg.N, e2c_d, cfg.Nc, rep_d, cfg.D, w_d, res_d, cap=cap)
+        assert torch.equal(sc, sc2[0]) and torch.equal(idx, idx2[0])
+        for a_, b_ in zip(queues, queues2):
+            assert torch.equal(a_, b_)
+        sc_h, idx_h = sc.cpu().numpy(), idx.cpu().numpy()
+        check_scores(cfg.unit, K, qs[t], cfg.G, sc_h[None])
+        assert np.array_equal(idx_h[None], oracle.select(sc_h[None], cfg.k, nthreads=8))
+        ref = oracle.map_requests(idx_h, cfg.H, cfg.N, e2c, cfg.Nc, rep, cfg.D, weight if use_w else None,
+                                  resident=res, cap=cap, nthreads=8)
+        for g_, r_ in zip(queues, ref):
+            assert np.array_equal(g_.cpu().numpy(), r_)
+    assert sw.device_status() == 0
+
+
 def test_host_side_argument_errors(sw):
     from paper_2603_17803_amd import binding
     cfg = W.CONFIGS["tiny"].scaled(N=64, k=8, T=1)
