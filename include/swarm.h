@@ -26,6 +26,7 @@
 #ifndef SWARM_H_
 #define SWARM_H_
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -199,6 +200,20 @@ swarm_status swarm_capture_begin(swarm_ctx* ctx);
 swarm_status swarm_capture_end(swarm_ctx* ctx, swarm_graph** out);
 swarm_status swarm_graph_launch(swarm_ctx* ctx, swarm_graph* graph);
 swarm_status swarm_graph_destroy(swarm_graph* graph);
+
+/*
+ * Measurement aid (no part of the path): the rate this device reaches with a minimal kernel, to be
+ * quoted next to the nominal peak a roofline is priced against.  Runs `reps` launches on the
+ * context's stream, waits for them and returns the average rate in *out (host).
+ *   SWARM_CAL_HBM_READ   streams `bytes` from buf with 16-byte loads           -> GB/s
+ *   SWARM_CAL_HBM_WRITE  overwrites `bytes` of buf with 16-byte stores         -> GB/s
+ *   SWARM_CAL_MFMA_I8    register-resident loop of v_mfma_i32_32x32x32_i8, 16
+ *                        independent accumulators per wave; buf >= 4 bytes     -> TOP/s
+ * buf: device, 16-byte aligned.  Choose bytes well above the 256 MB last-level cache to measure
+ * memory, not cache.  Errors: SWARM_EINVAL for bad arguments or while recording a graph.
+ */
+typedef enum { SWARM_CAL_HBM_READ = 0, SWARM_CAL_HBM_WRITE = 1, SWARM_CAL_MFMA_I8 = 2 } swarm_calibration;
+swarm_status swarm_calibrate(swarm_ctx* ctx, int32_t what, void* buf, size_t bytes, int32_t reps, double* out);
 
 #ifdef __cplusplus
 }

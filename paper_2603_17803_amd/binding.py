@@ -19,7 +19,7 @@ SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
 
 EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score", "swarm_score_select",
-           "swarm_coact_accumulate", "swarm_map_requests", "swarm_step", "swarm_capture_begin", "swarm_capture_end",
+           "swarm_coact_accumulate", "swarm_map_requests", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
 
 
@@ -56,6 +56,7 @@ def load() -> C.CDLL:
     L.swarm_coact_accumulate.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, u32]
     L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
+    L.swarm_calibrate.argtypes = [vp, i32, vp, C.c_size_t, i32, C.POINTER(C.c_double)]
     L.swarm_capture_begin.argtypes = [vp]
     L.swarm_capture_end.argtypes = [vp, C.POINTER(vp)]
     L.swarm_graph_launch.argtypes = [vp, vp]
@@ -110,6 +111,15 @@ def swarm_step(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q
     return load().swarm_step(C.c_void_p(ctx), C.byref(ks), C.c_void_p(q), k, C.c_void_p(out_idx), C.c_void_p(out_scores),
                              C.c_void_p(e2c), Nc, C.c_void_p(replicas), R, D, C.c_void_p(weight), C.c_void_p(resident),
                              C.c_void_p(q_off), C.c_void_p(q_cluster), C.c_void_p(q_load), cap)
+
+
+SWARM_CAL_HBM_READ, SWARM_CAL_HBM_WRITE, SWARM_CAL_MFMA_I8 = 0, 1, 2
+
+
+def swarm_calibrate(ctx: int, what: int, buf: int, nbytes: int, reps: int):
+    out = C.c_double(0.0)
+    rc = load().swarm_calibrate(C.c_void_p(ctx), what, C.c_void_p(buf), nbytes, reps, C.byref(out))
+    return rc, out.value
 
 
 def swarm_coact_accumulate(ctx: int, idx: int, rows: int, H: int, k: int, N: int, Cptr: int, decay_q16: int,
@@ -300,6 +310,12 @@ class Swarm:
                         self._dev(q_load, torch.int32, "q_load"), cap)
         self._check("swarm_step", rc)
         return out_idx, out_scores, out
+
+    def calibrate(self, what: int, buf, reps: int = 5) -> float:
+        """Measured rate of a minimal kernel (GB/s for the memory measurements over `buf`, TOP/s for the MFMA loop)."""
+        rc, value = swarm_calibrate(self.ctx, what, self._dev(buf, None, "buf"), buf.numel() * buf.element_size(), reps)
+        self._check("swarm_calibrate", rc)
+        return value
 
     def capture_begin(self):
         self._check("swarm_capture_begin", swarm_capture_begin(self.ctx))

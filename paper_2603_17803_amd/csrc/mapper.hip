@@ -376,6 +376,10 @@ __global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __
     const int64_t cbase = (int64_t)h * a.Nc;
     const MapLds L(smem, a, stage_e2c, stage_tab);
 
+    // the scores first (the selection waits for them), then the tables (needed only after it)
+    int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + sel_off);
+    uint32_t key[IPT];
+    selcore::load_keys<IPT>(scores + (size_t)h * N, N, key);
     int4 r_e2c[2] = {make_int4(0, 0, 0, 0), make_int4(0, 0, 0, 0)}, r_rep = make_int4(0, 0, 0, 0), r_wgt = make_int4(0, 0, 0, 0);
     const int n4_e2c = a.N >> 2, n4_rep = (a.Nc * a.R) >> 2, n4_wgt = a.Nc >> 2;
     if (stage_e2c) {
@@ -390,9 +394,6 @@ __global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __
     }
     for (int w = tid; w < L.nwords; w += NT) L.bitmap[w] = 0;
 
-    int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + sel_off);
-    uint32_t key[IPT];
-    selcore::load_keys<IPT>(scores + (size_t)h * N, N, key);
     selcore::block_select<IPT>(key, N, k, sel_lds, sm);
 
     if (stage_e2c) {
