@@ -28,6 +28,7 @@ def lib():
         L.oracle_coact_dense.restype = C.c_int
         L.oracle_coact_update.restype = C.c_int
         L.oracle_map.restype = C.c_int
+        L.oracle_density.restype = C.c_int
         L.oracle_hardware_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -118,6 +119,26 @@ def coact_update(idx: np.ndarray, N: int, Cm: np.ndarray | None = None, decay_q1
     if rc:
         raise OracleError("oracle_coact_update", rc)
     return Cm
+
+
+def density(Cm: np.ndarray, tau: float, flags: int = 0, totals: np.ndarray | None = None, nthreads: int = 1):
+    """C int32 [H][N][N] -> (rho int32 [H][N], queue int32 [H][N], totals int64 [H]).
+    flags bit 0: leave out j = i; bit 1: strict "<"."""
+    Cm = _c(Cm, np.int32)
+    H, N, N2 = Cm.shape
+    assert N == N2
+    rho = np.empty((H, N), np.int32)
+    queue = np.empty((H, N), np.int32)
+    tot = np.empty(H, np.int64)
+    tin = None
+    if totals is not None:
+        tin = _c(totals, np.int64)
+        assert tin.shape == (H,)
+    rc = lib().oracle_density(_p(Cm), H, N, _p(tin) if tin is not None else None, C.c_double(tau), C.c_uint32(flags),
+                              _p(rho), _p(queue), _p(tot), nthreads)
+    if rc:
+        raise OracleError("oracle_density", rc)
+    return rho, queue, tot
 
 
 def map_requests(sel: np.ndarray, H: int, N: int, e2c: np.ndarray, Nc: int, replicas: np.ndarray, D: int,

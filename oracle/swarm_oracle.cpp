@@ -1,4 +1,5 @@
-// CPU oracle for the score -> select -> trace -> co-activation -> request-mapping path.
+// CPU oracle for the score -> select -> trace -> co-activation -> request-mapping path and the
+// density pass over the co-activation counts.
 //
 // TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what each step of the
 // path computes, written from the paper's definitions.  It shares no code with the HIP path
@@ -281,5 +282,50 @@ int oracle_map(const int32_t* sel, int64_t groups, int S, int H, int N, const in
 }
 
 int oracle_hardware_threads(void) { return (int)std::thread::hardware_concurrency(); }
+
+// ---------------------------------------------------------------------------------------
+// Co-activation density and medoid queue (Section 5.1: the probability equation of Step 1, the
+// distance of Step 2, and the density loop and the descending sort of Algorithm 1's Step 3).
+//
+//   total   = sum over all (k, l) of C[k][l]                       (the denominator of P)
+//   P(i,j)  = C[i][j] / total ;  d(i,j) = 1 - P(i,j)               (fp64, each operation rounded once)
+//   rho[i]  = number of j with d(i,j) <= tau                       (Algorithm 1: every j, "<=")
+//             flags bit 0: leave out j = i, bit 1: "<" instead of "<="  (the density equation's form)
+//   queue   = entries in descending rho, equal rho in ascending entry id (the paper does not order ties)
+// total = 0 leaves P undefined; no pair is then counted.  totals_in (nullable) replaces the computed
+// denominator, e.g. to rescale.  C int32 [H][N][N]; rho int32 [H][N]; queue int32 [H][N];
+// totals_out int64 [H].
+// ---------------------------------------------------------------------------------------
+int oracle_density(const int32_t* C, int H, int N, const int64_t* totals_in, double tau, uint32_t flags, int32_t* rho,
+                   int32_t* queue, int64_t* totals_out, int nthreads) {
+    if (!C || !rho || !queue || !totals_out || H < 1 || N < 1) return 1;
+    const bool skip_self = flags & 1u, strict = flags & 2u;
+    for (int h = 0; h < H; ++h) {
+        const int32_t* Ch = C + (size_t)h * N * N;
+        int64_t total = 0;
+        for (size_t e = 0; e < (size_t)N * N; ++e) total += Ch[e];
+        if (totals_in) total = totals_in[h];
+        totals_out[h] = total;
+        int32_t* rh = rho + (size_t)h * N;
+        parallel_for(N, nthreads, [&](int64_t lo, int64_t hi) {
+            for (int64_t i = lo; i < hi; ++i) {
+                int32_t count = 0;
+                for (int j = 0; j < N; ++j) {
+                    if (skip_self && j == i) continue;
+                    if (total == 0) continue;
+                    const double P = static_cast<double>(Ch[(size_t)i * N + j]) / static_cast<double>(total);
+                    const double d = 1.0 - P;
+                    if (strict ? (d < tau) : (d <= tau)) ++count;
+                }
+                rh[i] = count;
+            }
+        });
+        std::vector<int32_t> ids(N);
+        for (int i = 0; i < N; ++i) ids[i] = i;
+        std::stable_sort(ids.begin(), ids.end(), [&](int32_t a, int32_t b) { return rh[a] > rh[b]; });
+        std::memcpy(queue + (size_t)h * N, ids.data(), sizeof(int32_t) * N);
+    }
+    return 0;
+}
 
 }  // extern "C"
