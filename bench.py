@@ -163,6 +163,12 @@ def main():
     step_us, step_us_min = stage(decode_steps, reps, T)
     map_us, map_us_min = stage(map_steps, reps, T)
     coact_us, coact_us_min = stage(coact, reps, 1)
+    tau = 1.0 - 0.25 * float(Cm.max()) / (float(T) * k * k)
+
+    def density():
+        sw.coact_density(Cm, tau)
+
+    dens_us, dens_us_min = stage(density, reps, 1)
     coact_ms = coact_us * 1e-3
     # the same sweep out of one buffer: served by the 256 MB last-level cache, not by HBM
     layers_all, layers[:] = list(layers), [layers[0]]
@@ -208,6 +214,9 @@ def main():
                            "ms_per_build_incl_trace": round(coact_ms, 3), "ms_min": round(coact_us_min * 1e-3, 3),
                            "frac_of_measured_mfma_peak": round(coact_tops / peaks["mfma_i8_TOPs"], 4),
                            "pair_increments_per_s": round(increments / (coact_ms * 1e-3), 0)},
+        "density_pass": {"what": "grand total, rho and medoid queue from C (two sweeps of C plus an N^2 ranking)",
+                         "ms": round(dens_us * 1e-3, 3), "ms_min": round(dens_us_min * 1e-3, 3), "bound": "hbm",
+                         "bytes": 2 * H * N * N * 4, "achieved_GBs": round(2 * H * N * N * 4 / (dens_us * 1e-6) / 1e9, 1)},
         "measured_peaks": peaks,
         "stages": {"timing": f"median (min) over {reps} graph replays, HIP events on the launch stream",
                    "step_us": round(step_us, 3), "step_us_min": round(step_us_min, 3),

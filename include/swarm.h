@@ -137,6 +137,30 @@ swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t 
                                     int32_t N, int32_t* C, uint32_t decay_q16, uint32_t flags);
 
 /*
+ * Co-activation density and medoid queue (Section 5.1: the co-activation probability of Step 1, the
+ * distance of Step 2, the density and the descending medoid queue of Algorithm 1's Step 3) -- the
+ * streaming front half of the clustering, whose sequential expansion step stays on the host.
+ *
+ *   total[h] = sum over all (k, l) of C[h][k][l]     (or totals_in[h] when given, e.g. to rescale)
+ *   P(i,j)   = C[h][i][j] / total[h] ;  d(i,j) = 1 - P(i,j)          (fp64, each operation rounded once)
+ *   rho[h][i] = number of j with d(i,j) <= tau                       (Algorithm 1: every j, "<=")
+ *   queue[h]  = entry ids in descending rho, equal rho in ascending id
+ * SWARM_RHO_EXCLUDE_SELF leaves j = i out and SWARM_RHO_STRICT tests d < tau (the form of the paper's
+ * density equation).  total = 0 leaves P undefined: no pair is counted.  Counts must be >= 0.
+ *
+ * C          device, int32 [H][N][N], 16-byte aligned (as produced by swarm_coact_accumulate).
+ * totals_in  device, int64 [H], or NULL to sum C (one more pass over C).
+ * rho        device out, int32 [H][N].
+ * queue      device out, int32 [H][N], or NULL to skip the queue.
+ * totals_out device out, int64 [H], or NULL.
+ * Errors: SWARM_EINVAL for NULL C or rho, H/N < 1, misaligned pointers, unknown flags.
+ */
+#define SWARM_RHO_EXCLUDE_SELF 1u
+#define SWARM_RHO_STRICT 2u
+swarm_status swarm_coact_density(swarm_ctx* ctx, const int32_t* C, int32_t H, int32_t N, const int64_t* totals_in,
+                                 double tau, uint32_t flags, int32_t* rho, int32_t* queue, int64_t* totals_out);
+
+/*
  * Request mapping (Section 6.1: merge the activated clusters, drop what is already resident in
  * DRAM, then fill one bucket per SSD -- items in ascending order of replication factor, an item
  * with a single copy to its SSD, an item with several copies to the SSD whose bucket is currently

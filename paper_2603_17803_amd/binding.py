@@ -19,7 +19,7 @@ SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
 
 EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score", "swarm_score_select",
-           "swarm_coact_accumulate", "swarm_map_requests", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
+           "swarm_coact_accumulate", "swarm_map_requests", "swarm_coact_density", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
 
 
@@ -56,6 +56,7 @@ def load() -> C.CDLL:
     L.swarm_coact_accumulate.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, u32]
     L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
+    L.swarm_coact_density.argtypes = [vp, vp, i32, i32, vp, C.c_double, C.c_uint32, vp, vp, vp]
     L.swarm_calibrate.argtypes = [vp, i32, vp, C.c_size_t, i32, C.POINTER(C.c_double)]
     L.swarm_capture_begin.argtypes = [vp]
     L.swarm_capture_end.argtypes = [vp, C.POINTER(vp)]
@@ -114,6 +115,13 @@ def swarm_step(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q
 
 
 SWARM_CAL_HBM_READ, SWARM_CAL_HBM_WRITE, SWARM_CAL_MFMA_I8 = 0, 1, 2
+SWARM_RHO_EXCLUDE_SELF, SWARM_RHO_STRICT = 1, 2
+
+
+def swarm_coact_density(ctx: int, Cptr: int, H: int, N: int, totals_in: Optional[int], tau: float, flags: int, rho: int,
+                        queue: Optional[int], totals_out: Optional[int]) -> int:
+    return load().swarm_coact_density(C.c_void_p(ctx), C.c_void_p(Cptr), H, N, C.c_void_p(totals_in), tau, flags,
+                                      C.c_void_p(rho), C.c_void_p(queue), C.c_void_p(totals_out))
 
 
 def swarm_calibrate(ctx: int, what: int, buf: int, nbytes: int, reps: int):
@@ -240,6 +248,23 @@ class Swarm:
                                     self._dev(Cm, torch.int32, "C"), decay_q16, flags)
         self._check("swarm_coact_accumulate", rc)
         return Cm
+
+    def coact_density(self, Cm, tau: float, flags: int = 0, totals_in=None, want_queue: bool = True):
+        """Cm int32 [H][N][N] -> (rho int32 [H][N], queue int32 [H][N] or None, totals int64 [H])."""
+        torch = self.torch
+        H, N, N2 = Cm.shape
+        if N != N2:
+            raise ValueError("C must be [H][N][N]")
+        rho = torch.empty((H, N), dtype=torch.int32, device=self.device)
+        queue = torch.empty((H, N), dtype=torch.int32, device=self.device) if want_queue else None
+        totals = torch.empty((H,), dtype=torch.int64, device=self.device)
+        rc = swarm_coact_density(self.ctx, self._dev(Cm, torch.int32, "C"), H, N,
+                                 None if totals_in is None else self._dev(totals_in, torch.int64, "totals_in"), float(tau),
+                                 flags, self._dev(rho, torch.int32, "rho"),
+                                 None if queue is None else self._dev(queue, torch.int32, "queue"),
+                                 self._dev(totals, torch.int64, "totals"))
+        self._check("swarm_coact_density", rc)
+        return rho, queue, totals
 
     def map_requests(self, sel, H: int, N: int, e2c, Nc: int, replicas, D: int, weight=None, resident=None,
                      cap: Optional[int] = None, out=None):

@@ -74,6 +74,7 @@ swarm_status swarm_destroy(swarm_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->scores) (void)hipFree(ctx->scores);
     if (ctx->trace) (void)hipFree(ctx->trace);
+    if (ctx->totals) (void)hipFree(ctx->totals);
     if (ctx->weights) (void)hipFree(ctx->weights);
     if (ctx->tile_order) (void)hipFree(ctx->tile_order);
     if (ctx->dev_flags) (void)hipFree(ctx->dev_flags);
@@ -161,6 +162,24 @@ swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t 
     st = launch_trace_build(ctx, idx, rows, H, k, N, Npad, nruns, flags);
     if (st != SWARM_OK) return st;
     return launch_coact_syrk(ctx, H, N, Npad, nruns, C, decay_q16);
+}
+
+swarm_status swarm_coact_density(swarm_ctx* ctx, const int32_t* C, int32_t H, int32_t N, const int64_t* totals_in,
+                                 double tau, uint32_t flags, int32_t* rho, int32_t* queue, int64_t* totals_out) {
+    if (!ctx) return SWARM_EINVAL;
+    if (!C || !rho) SWARM_REJECT(ctx, "coact_density: NULL C or rho");
+    if (H < 1 || N < 1) SWARM_REJECT(ctx, "coact_density: H=%d N=%d must be >= 1", H, N);
+    if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "coact_density: C must be 16-byte aligned");
+    if (flags & ~(SWARM_RHO_EXCLUDE_SELF | SWARM_RHO_STRICT)) SWARM_REJECT(ctx, "coact_density: unknown flags 0x%x", flags);
+    if ((totals_in && (reinterpret_cast<uintptr_t>(totals_in) & 7)) || (totals_out && (reinterpret_cast<uintptr_t>(totals_out) & 7)))
+        SWARM_REJECT(ctx, "coact_density: totals must be 8-byte aligned");
+    int64_t* totals = totals_out;
+    if (!totals) {
+        const swarm_status st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->totals), &ctx->totals_bytes, sizeof(int64_t) * (size_t)H);
+        if (st != SWARM_OK) return st;
+        totals = ctx->totals;
+    }
+    return launch_density(ctx, C, H, N, totals_in, tau, flags, rho, queue, totals);
 }
 
 static swarm_status check_map_args(swarm_ctx* ctx, const char* fn, int64_t groups, int32_t S, int32_t H, int32_t N,

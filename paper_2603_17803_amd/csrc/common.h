@@ -24,6 +24,8 @@ struct swarm_ctx {
     size_t weights_bytes = 0;
     void* trace = nullptr;         // binary trace as bits: uint4 [H][runs of 128 rows][Npad]
     size_t trace_bytes = 0;
+    int64_t* totals = nullptr;     // per-head grand totals of C when the caller keeps none
+    size_t totals_bytes = 0;
     uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
     int32_t* tile_order = nullptr; // co-activation tile schedule for tile_order_nt tiles per edge
     int tile_order_nt = 0;
@@ -59,6 +61,8 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                         const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap);
+swarm_status launch_density(swarm_ctx* ctx, const int32_t* C, int H, int N, const int64_t* totals_in, double tau,
+                            uint32_t flags, int32_t* rho, int32_t* queue, int64_t* totals);
 swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N, int k, int32_t* out_idx,
                                const int32_t* e2c, int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                                const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap,

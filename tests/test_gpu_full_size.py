@@ -99,6 +99,16 @@ def run_full(sw, cfg, sample_steps, rng):
         got = c[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()].cpu().numpy()
         want = np.array([int((member[int(a)] & member[int(b)]).sum()) for a, b in zip(ii, jj)])
         assert np.array_equal(got, want)
+    if N <= 8192:
+        # density pass over the C just built, against the oracle on the same matrix (Section 5.1, Steps 1-3)
+        C_host = Cm.cpu().numpy()
+        tau = 1.0 - 0.25 * float(C_host.max()) / (float(T) * k * k)
+        rho, queue, tot = sw.coact_density(Cm, tau)
+        r_rho, r_queue, r_tot = oracle.density(C_host, tau, nthreads=16)
+        assert (r_tot == T * k * k).all() and np.array_equal(tot.cpu().numpy(), r_tot)
+        assert np.array_equal(rho.cpu().numpy(), r_rho) and np.array_equal(queue.cpu().numpy(), r_queue)
+        assert 0 < int(r_rho.max()) < N
+        del C_host
     del Cm
     torch.cuda.empty_cache()
 

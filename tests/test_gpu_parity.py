@@ -359,6 +359,43 @@ def test_whole_path_batched_grouped_scaled(sw):
     whole_path(sw, W.CONFIGS["drift_batch"].scaled(N=512, B=4, T=6, k=32), 6)
 
 
+# --------------------------------------------------------------------------- density pass over C
+
+DENSITY_CASES = [(1, 64), (3, 307), (2, 1024), (1, 2500)]
+
+
+@pytest.mark.parametrize("H,N", DENSITY_CASES)
+def test_density_and_medoid_queue_bit_exact(sw, H, N):
+    from paper_2603_17803_amd import binding
+    rng = np.random.default_rng(100 + N)
+    k = max(2, N // 16)
+    idx = W.random_selections(96, H, k, N, seed=N, topic_like=True)
+    Cm = oracle.coact_update(idx, N, nthreads=8)
+    Cd = dev(Cm)
+    total = 96 * k * k
+    # radii around the interesting range: P is at most diag/total, so tau sits just below 1
+    pmax = Cm.max() / total
+    taus = [1.0, 1.0 - 0.5 * pmax, 1.0 - 0.1 * pmax, 1.0 - 1.0 / total, 1.0 - 3.0 / total, 0.5, float(rng.random()), -1.0]
+    for tau in taus:
+        for flags in (0, binding.SWARM_RHO_EXCLUDE_SELF, binding.SWARM_RHO_STRICT, 3):
+            rho, queue, tot = sw.coact_density(Cd, tau, flags)
+            r_rho, r_queue, r_tot = oracle.density(Cm, tau, flags, nthreads=8)
+            assert np.array_equal(tot.cpu().numpy(), r_tot) and (r_tot == total).all()
+            assert np.array_equal(rho.cpu().numpy(), r_rho), (tau, flags)
+            assert np.array_equal(queue.cpu().numpy(), r_queue), (tau, flags)
+    # caller-supplied denominators, no queue
+    tin = np.arange(1, H + 1, dtype=np.int64) * 1000
+    rho, queue, tot = sw.coact_density(Cd, 0.97, 0, totals_in=dev(tin), want_queue=False)
+    r_rho, _, r_tot = oracle.density(Cm, 0.97, 0, totals=tin, nthreads=8)
+    assert queue is None and np.array_equal(rho.cpu().numpy(), r_rho) and np.array_equal(tot.cpu().numpy(), r_tot)
+    # all-zero counts: nothing is counted, the queue is the identity
+    Z = torch.zeros((H, N, N), dtype=torch.int32, device="cuda")
+    rho, queue, tot = sw.coact_density(Z, 1.0)
+    assert int(rho.abs().sum()) == 0 and int(tot.abs().sum()) == 0
+    assert np.array_equal(queue.cpu().numpy(), np.tile(np.arange(N, dtype=np.int32), (H, 1)))
+    assert sw.device_status() == 0
+
+
 # --------------------------------------------------------------------------- one-call decode step
 
 STEP_CASES = [
