@@ -29,6 +29,7 @@ def lib():
         L.oracle_coact_update.restype = C.c_int
         L.oracle_map.restype = C.c_int
         L.oracle_density.restype = C.c_int
+        L.oracle_window_assign.restype = C.c_int
         L.oracle_hardware_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -139,6 +140,30 @@ def density(Cm: np.ndarray, tau: float, flags: int = 0, totals: np.ndarray | Non
     if rc:
         raise OracleError("oracle_density", rc)
     return rho, queue, tot
+
+
+def window_assign(sel: np.ndarray, N: int, new_ids: np.ndarray, medoids: np.ndarray, tau: float,
+                  primary: np.ndarray | None = None, size: np.ndarray | None = None, D: int = 0):
+    """sel int32 [W][H][k]; new_ids int32 [H][n_new]; medoids int32 [H][Nc]; primary/size int32 [H][Nc] or None.
+    Returns (f int32 [H][n_new][Nc], member uint8 [H][n_new][Nc], disk int32 [H][n_new][Nc] or None)."""
+    sel = _c(sel, np.int32)
+    W, H, k = sel.shape
+    new_ids = _c(new_ids, np.int32)
+    medoids = _c(medoids, np.int32)
+    n_new, Nc = new_ids.shape[1], medoids.shape[1]
+    assert new_ids.shape == (H, n_new) and medoids.shape == (H, Nc)
+    f = np.empty((H, n_new, Nc), np.int32)
+    member = np.empty((H, n_new, Nc), np.uint8)
+    disk = None
+    if primary is not None:
+        primary, size = _c(primary, np.int32), _c(size, np.int32)
+        assert primary.shape == (H, Nc) and size.shape == (H, Nc) and D >= 1
+        disk = np.empty((H, n_new, Nc), np.int32)
+    rc = lib().oracle_window_assign(_p(sel), W, H, k, N, _p(new_ids), n_new, _p(medoids), Nc, C.c_double(tau),
+                                    _p(primary), _p(size), D, _p(f), _p(member), _p(disk))
+    if rc:
+        raise OracleError("oracle_window_assign", rc)
+    return f, member, disk
 
 
 def map_requests(sel: np.ndarray, H: int, N: int, e2c: np.ndarray, Nc: int, replicas: np.ndarray, D: int,

@@ -328,4 +328,56 @@ int oracle_density(const int32_t* C, int H, int N, const int64_t* totals_in, dou
     return 0;
 }
 
+// ---------------------------------------------------------------------------------------
+// Cluster maintenance over the local window (Section 6.2, the distance between a newly generated
+// entry and a cluster): for every new entry e and every cluster i with medoid m_i,
+//   f(e, m_i) = number of the window's W steps in which e and m_i are both activated,
+//   d(e, C_i) = 1 - f(e, m_i) / W                                          (fp64)
+// and e joins every cluster with d < tau.  A joining entry is placed on the cluster's next SSD:
+// disk = (id_i + |C_i| + 1) mod D, where |C_i| grows by one with every entry that joins (new entries
+// are taken in the order given: a reading, the paper places one entry at a time).
+// sel int32 [W][H][k]; new_ids int32 [H][n_new]; medoids int32 [H][Nc]; primary, size int32 [H][Nc]
+// (nullable together: no placement); f_out int32 [H][n_new][Nc]; member uint8 [H][n_new][Nc];
+// disk int32 [H][n_new][Nc] (-1 where not joined; nullable).
+// ---------------------------------------------------------------------------------------
+int oracle_window_assign(const int32_t* sel, int W, int H, int k, int N, const int32_t* new_ids, int n_new,
+                         const int32_t* medoids, int Nc, double tau, const int32_t* primary, const int32_t* size, int D,
+                         int32_t* f_out, uint8_t* member, int32_t* disk) {
+    if (!sel || !new_ids || !medoids || !f_out || !member || W < 1 || H < 1 || k < 1 || n_new < 1 || Nc < 1) return 1;
+    if ((primary == nullptr) != (size == nullptr) || (disk && (!primary || D < 1))) return 1;
+    std::vector<uint8_t> act((size_t)W * N);
+    for (int h = 0; h < H; ++h) {
+        std::fill(act.begin(), act.end(), 0);
+        for (int t = 0; t < W; ++t)
+            for (int j = 0; j < k; ++j) {
+                const int32_t e = sel[((size_t)t * H + h) * k + j];
+                if (e >= 0 && e < N) act[(size_t)t * N + e] = 1;
+            }
+        std::vector<int32_t> grown(Nc, 0);
+        for (int a = 0; a < n_new; ++a) {
+            const int32_t e = new_ids[(size_t)h * n_new + a];
+            for (int c = 0; c < Nc; ++c) {
+                const int32_t m = medoids[(size_t)h * Nc + c];
+                int32_t f = 0;
+                if (e >= 0 && e < N && m >= 0 && m < N)
+                    for (int t = 0; t < W; ++t) f += act[(size_t)t * N + e] & act[(size_t)t * N + m];
+                const double d = 1.0 - static_cast<double>(f) / static_cast<double>(W);
+                const bool join = d < tau;
+                const size_t o = ((size_t)h * n_new + a) * Nc + c;
+                f_out[o] = f;
+                member[o] = join;
+                if (disk) {
+                    disk[o] = -1;
+                    if (join) {
+                        const int64_t sz = (int64_t)size[(size_t)h * Nc + c] + grown[c];
+                        disk[o] = (int32_t)(((int64_t)primary[(size_t)h * Nc + c] + sz + 1) % D);
+                        ++grown[c];
+                    }
+                }
+            }
+        }
+    }
+    return 0;
+}
+
 }  // extern "C"
