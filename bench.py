@@ -169,6 +169,17 @@ def main():
         sw.coact_density(Cm, tau)
 
     dens_us, dens_us_min = stage(density, reps, 1)
+    # cluster maintenance over the last 256 steps: 256 new entries against one medoid per cluster
+    g = np.random.default_rng(cfg.seed + 17)
+    new_d = dev(np.stack([g.choice(N, 256, replace=False) for _ in range(H)]).astype(np.int32))
+    med_d = dev(np.stack([g.choice(N, cfg.Nc, replace=False) for _ in range(H)]).astype(np.int32))
+    win_sel = idx_all[T - 256:]
+    win_member = torch.empty((H, 256, cfg.Nc), dtype=torch.uint8, device="cuda")
+
+    def window():
+        sw.window_assign(win_sel, N, new_d, med_d, 1.0 - 8.0 / 256, want_counts=False)
+
+    win_us, win_us_min = stage(window, reps, 1)
     coact_ms = coact_us * 1e-3
     # the same sweep out of one buffer: served by the 256 MB last-level cache, not by HBM
     layers_all, layers[:] = list(layers), [layers[0]]
@@ -217,6 +228,8 @@ def main():
         "density_pass": {"what": "grand total, rho and medoid queue from C (two sweeps of C plus an N^2 ranking)",
                          "ms": round(dens_us * 1e-3, 3), "ms_min": round(dens_us_min * 1e-3, 3), "bound": "hbm",
                          "bytes": 2 * H * N * N * 4, "achieved_GBs": round(2 * H * N * N * 4 / (dens_us * 1e-6) / 1e9, 1)},
+        "window_maintenance": {"what": "last 256 steps, 256 new entries x %d medoids per head: trace bits + counts + membership" % cfg.Nc,
+                               "us": round(win_us, 1), "us_min": round(win_us_min, 1)},
         "measured_peaks": peaks,
         "stages": {"timing": f"median (min) over {reps} graph replays, HIP events on the launch stream",
                    "step_us": round(step_us, 3), "step_us_min": round(step_us_min, 3),

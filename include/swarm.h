@@ -161,6 +161,33 @@ swarm_status swarm_coact_density(swarm_ctx* ctx, const int32_t* C, int32_t H, in
                                  double tau, uint32_t flags, int32_t* rho, int32_t* queue, int64_t* totals_out);
 
 /*
+ * Cluster maintenance over the local window (Section 6.2: the distance between a newly generated entry
+ * and a cluster is 1 - f(e_new, m_i) / W, with f the number of the window's W steps in which the entry
+ * and the cluster's medoid m_i are activated together; the entry joins every cluster whose distance is
+ * below the radius, and is placed on that cluster's next SSD).
+ *
+ *   f[h][a][c]      = number of t < W with new_ids[h][a] and medoids[h][c] both in sel[t][h][0..k)
+ *   member[h][a][c] = 1 - f / W < tau            (fp64; strict, as the text says "smaller than")
+ *   disk[h][a][c]   = (primary[h][c] + size[h][c] + j + 1) mod D for the j-th entry (in the order of
+ *                     new_ids, j from 0) that joins cluster c, -1 where the entry does not join
+ *                     (the cluster grows by one with every joining entry: a reading, the paper places
+ *                     one entry at a time)
+ * sel      device, int32 [W][H][k], the window's selections (1 <= W <= 2048).
+ * new_ids  device, int32 [H][n_new];  medoids device, int32 [H][Nc]: entry ids in [0,N); an id outside
+ *          the range counts as never activated and is flagged (SWARM_DEV_BAD_ENTRY).
+ * primary, size  device, int32 [H][Nc] (first SSD and current entry count of each cluster), or both
+ *          NULL when disk is NULL.
+ * f_out    device out, int32 [H][n_new][Nc], or NULL.   member  device out, uint8 [H][n_new][Nc].
+ * disk     device out, int32 [H][n_new][Nc], or NULL.
+ * The window's trace is rebuilt in the context's scratch (it replaces the trace of the last
+ * swarm_coact_accumulate).  Errors: SWARM_EINVAL for NULL required pointers or sizes out of range.
+ */
+swarm_status swarm_window_assign(swarm_ctx* ctx, const int32_t* sel, int32_t W, int32_t H, int32_t k, int32_t N,
+                                 const int32_t* new_ids, int32_t n_new, const int32_t* medoids, int32_t Nc, double tau,
+                                 const int32_t* primary, const int32_t* size, int32_t D, int32_t* f_out, uint8_t* member,
+                                 int32_t* disk);
+
+/*
  * Request mapping (Section 6.1: merge the activated clusters, drop what is already resident in
  * DRAM, then fill one bucket per SSD -- items in ascending order of replication factor, an item
  * with a single copy to its SSD, an item with several copies to the SSD whose bucket is currently

@@ -19,7 +19,7 @@ SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
 
 EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score", "swarm_score_select",
-           "swarm_coact_accumulate", "swarm_map_requests", "swarm_coact_density", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
+           "swarm_coact_accumulate", "swarm_map_requests", "swarm_coact_density", "swarm_window_assign", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
 
 
@@ -57,6 +57,7 @@ def load() -> C.CDLL:
     L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_coact_density.argtypes = [vp, vp, i32, i32, vp, C.c_double, C.c_uint32, vp, vp, vp]
+    L.swarm_window_assign.argtypes = [vp, vp, i32, i32, i32, i32, vp, i32, vp, i32, C.c_double, vp, vp, i32, vp, vp, vp]
     L.swarm_calibrate.argtypes = [vp, i32, vp, C.c_size_t, i32, C.POINTER(C.c_double)]
     L.swarm_capture_begin.argtypes = [vp]
     L.swarm_capture_end.argtypes = [vp, C.POINTER(vp)]
@@ -116,6 +117,14 @@ def swarm_step(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q
 
 SWARM_CAL_HBM_READ, SWARM_CAL_HBM_WRITE, SWARM_CAL_MFMA_I8 = 0, 1, 2
 SWARM_RHO_EXCLUDE_SELF, SWARM_RHO_STRICT = 1, 2
+
+
+def swarm_window_assign(ctx: int, sel: int, W: int, H: int, k: int, N: int, new_ids: int, n_new: int, medoids: int, Nc: int,
+                        tau: float, primary: Optional[int], size: Optional[int], D: int, f_out: Optional[int], member: int,
+                        disk: Optional[int]) -> int:
+    return load().swarm_window_assign(C.c_void_p(ctx), C.c_void_p(sel), W, H, k, N, C.c_void_p(new_ids), n_new,
+                                      C.c_void_p(medoids), Nc, tau, C.c_void_p(primary), C.c_void_p(size), D,
+                                      C.c_void_p(f_out), C.c_void_p(member), C.c_void_p(disk))
 
 
 def swarm_coact_density(ctx: int, Cptr: int, H: int, N: int, totals_in: Optional[int], tau: float, flags: int, rho: int,
@@ -265,6 +274,32 @@ class Swarm:
                                  self._dev(totals, torch.int64, "totals"))
         self._check("swarm_coact_density", rc)
         return rho, queue, totals
+
+    def window_assign(self, sel, N: int, new_ids, medoids, tau: float, primary=None, size=None, D: int = 0,
+                      want_counts: bool = True):
+        """sel int32 [W][H][k]; new_ids int32 [H][n_new]; medoids int32 [H][Nc] ->
+        (f int32 [H][n_new][Nc] or None, member uint8 [H][n_new][Nc], disk int32 [H][n_new][Nc] or None)."""
+        torch = self.torch
+        W, H, k = sel.shape
+        n_new, Nc = new_ids.shape[1], medoids.shape[1]
+        if tuple(new_ids.shape) != (H, n_new) or tuple(medoids.shape) != (H, Nc):
+            raise ValueError("new_ids must be [H][n_new] and medoids [H][Nc]")
+        f = torch.empty((H, n_new, Nc), dtype=torch.int32, device=self.device) if want_counts else None
+        member = torch.empty((H, n_new, Nc), dtype=torch.uint8, device=self.device)
+        disk = None
+        if primary is not None:
+            if tuple(primary.shape) != (H, Nc) or tuple(size.shape) != (H, Nc):
+                raise ValueError("primary and size must be [H][Nc]")
+            disk = torch.empty((H, n_new, Nc), dtype=torch.int32, device=self.device)
+        rc = swarm_window_assign(self.ctx, self._dev(sel, torch.int32, "sel"), W, H, k, N,
+                                 self._dev(new_ids, torch.int32, "new_ids"), n_new, self._dev(medoids, torch.int32, "medoids"),
+                                 Nc, float(tau), None if primary is None else self._dev(primary, torch.int32, "primary"),
+                                 None if size is None else self._dev(size, torch.int32, "size"), D,
+                                 None if f is None else self._dev(f, torch.int32, "f"),
+                                 self._dev(member, torch.uint8, "member"),
+                                 None if disk is None else self._dev(disk, torch.int32, "disk"))
+        self._check("swarm_window_assign", rc)
+        return f, member, disk
 
     def map_requests(self, sel, H: int, N: int, e2c, Nc: int, replicas, D: int, weight=None, resident=None,
                      cap: Optional[int] = None, out=None):

@@ -182,6 +182,26 @@ swarm_status swarm_coact_density(swarm_ctx* ctx, const int32_t* C, int32_t H, in
     return launch_density(ctx, C, H, N, totals_in, tau, flags, rho, queue, totals);
 }
 
+swarm_status swarm_window_assign(swarm_ctx* ctx, const int32_t* sel, int32_t W, int32_t H, int32_t k, int32_t N,
+                                 const int32_t* new_ids, int32_t n_new, const int32_t* medoids, int32_t Nc, double tau,
+                                 const int32_t* primary, const int32_t* size, int32_t D, int32_t* f_out, uint8_t* member,
+                                 int32_t* disk) {
+    if (!ctx) return SWARM_EINVAL;
+    if (!sel || !new_ids || !medoids || !member) SWARM_REJECT(ctx, "window_assign: NULL required pointer");
+    if (W < 1 || W > 2048) SWARM_REJECT(ctx, "window_assign: W=%d outside [1,2048]", W);
+    if (H < 1 || N < 1 || k < 1 || k > N || n_new < 1 || Nc < 1)
+        SWARM_REJECT(ctx, "window_assign: H=%d N=%d k=%d n_new=%d Nc=%d invalid", H, N, k, n_new, Nc);
+    if ((primary == nullptr) != (size == nullptr)) SWARM_REJECT(ctx, "window_assign: primary and size go together");
+    if (disk && (!primary || D < 1)) SWARM_REJECT(ctx, "window_assign: disk needs primary, size and D >= 1");
+    const int nruns = (W + 127) / 128;
+    const int Npad = (N + 255) / 256 * 256;
+    swarm_status st = swarm_grow(ctx, &ctx->trace, &ctx->trace_bytes, (size_t)H * nruns * Npad * 16);
+    if (st != SWARM_OK) return st;
+    st = launch_trace_build(ctx, sel, W, H, k, N, Npad, nruns, 0u);
+    if (st != SWARM_OK) return st;
+    return launch_window(ctx, nruns, Npad, N, W, H, new_ids, n_new, medoids, Nc, tau, primary, size, D, f_out, member, disk);
+}
+
 static swarm_status check_map_args(swarm_ctx* ctx, const char* fn, int64_t groups, int32_t S, int32_t H, int32_t N,
                                    const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
                                    const int32_t* q_off, const int32_t* q_cluster, const int32_t* q_load, int32_t cap) {

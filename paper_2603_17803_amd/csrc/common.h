@@ -63,6 +63,9 @@ swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int 
                         const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap);
 swarm_status launch_density(swarm_ctx* ctx, const int32_t* C, int H, int N, const int64_t* totals_in, double tau,
                             uint32_t flags, int32_t* rho, int32_t* queue, int64_t* totals);
+swarm_status launch_window(swarm_ctx* ctx, int nruns, int Npad, int N, int W, int H, const int32_t* new_ids, int n_new,
+                           const int32_t* medoids, int Nc, double tau, const int32_t* primary, const int32_t* size, int D,
+                           int32_t* f_out, uint8_t* member, int32_t* disk);
 swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N, int k, int32_t* out_idx,
                                const int32_t* e2c, int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                                const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap,

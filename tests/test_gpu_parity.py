@@ -396,6 +396,39 @@ def test_density_and_medoid_queue_bit_exact(sw, H, N):
     assert sw.device_status() == 0
 
 
+# --------------------------------------------------------------------------- local-window cluster maintenance
+
+WINDOW_CASES = [(4, 1, 3, 8, 3, 2), (256, 8, 64, 2048, 96, 200), (300, 2, 17, 1027, 33, 61), (2048, 1, 40, 700, 5, 700)]
+
+
+@pytest.mark.parametrize("Wn,H,k,N,n_new,Nc", WINDOW_CASES)
+def test_window_assign_bit_exact(sw, Wn, H, k, N, n_new, Nc):
+    sel = W.random_selections(Wn, H, k, N, seed=Wn + N, topic_like=N >= 2 * k)
+    rng = np.random.default_rng(Wn)
+    new_ids = np.stack([rng.choice(N, n_new, replace=False) for _ in range(H)]).astype(np.int32)
+    med = np.stack([rng.choice(N, Nc, replace=False) for _ in range(H)]).astype(np.int32)
+    D = 7
+    primary = rng.integers(0, D, (H, Nc)).astype(np.int32)
+    size = rng.integers(1, 500, (H, Nc)).astype(np.int32)
+    sel_d, new_d, med_d = dev(sel), dev(new_ids), dev(med)
+    for tau in (1.0, 1.0 - 1.0 / Wn, 1.0 - 2.5 / Wn, 0.5, 1.5, 0.0):
+        f, member, disk = sw.window_assign(sel_d, N, new_d, med_d, tau, dev(primary), dev(size), D)
+        r_f, r_member, r_disk = oracle.window_assign(sel, N, new_ids, med, tau, primary, size, D)
+        assert np.array_equal(f.cpu().numpy(), r_f)
+        assert np.array_equal(member.cpu().numpy(), r_member), tau
+        assert np.array_equal(disk.cpu().numpy(), r_disk), tau
+    f, member, disk = sw.window_assign(sel_d, N, new_d, med_d, 0.9, want_counts=False)
+    assert f is None and disk is None
+    assert np.array_equal(member.cpu().numpy(), oracle.window_assign(sel, N, new_ids, med, 0.9)[1])
+    assert sw.device_status() == 0
+    # an id outside [0, N) counts as never activated and raises the flag
+    from paper_2603_17803_amd import binding
+    bad = new_ids.copy()
+    bad[0, 0] = N
+    f, member, _ = sw.window_assign(sel_d, N, dev(bad), med_d, 1.0)
+    assert int(f[0, 0].abs().sum()) == 0 and sw.device_status() == binding.SWARM_DEV_BAD_ENTRY
+
+
 # --------------------------------------------------------------------------- one-call decode step
 
 STEP_CASES = [
