@@ -29,6 +29,9 @@ def lib():
         L.oracle_coact_update.restype = C.c_int
         L.oracle_map.restype = C.c_int
         L.oracle_density.restype = C.c_int
+        L.oracle_score_rows.restype = C.c_int
+        L.oracle_expand_clusters.restype = C.c_int
+        L.oracle_submission_order.restype = C.c_int
         L.oracle_window_assign.restype = C.c_int
         L.oracle_hardware_threads.restype = C.c_int
         _lib = L
@@ -164,6 +167,55 @@ def window_assign(sel: np.ndarray, N: int, new_ids: np.ndarray, medoids: np.ndar
     if rc:
         raise OracleError("oracle_window_assign", rc)
     return f, member, disk
+
+
+def score_rows(kind: str, keys: np.ndarray, row_ids: np.ndarray, q: np.ndarray, G: int = 1):
+    """Scores of the listed entries only: row_ids int32 [H][M] -> (f32, f64, abs) each [B][H][M]."""
+    keys = _c(keys, np.uint16)
+    q = _c(q, np.uint16)
+    row_ids = _c(row_ids, np.int32)
+    H, N, d = keys.shape[0], keys.shape[1], keys.shape[-1]
+    M = row_ids.shape[1]
+    B = q.shape[0]
+    assert row_ids.shape == (H, M) and q.shape == (B, H * G, d)
+    f32 = np.empty((B, H, M), np.float32)
+    f64 = np.empty((B, H, M), np.float64)
+    ab = np.empty((B, H, M), np.float64)
+    rc = lib().oracle_score_rows(0 if kind == "token" else 1, _p(keys), _p(row_ids), M, _p(q), B, H, G, N, d, _p(f32), _p(f64), _p(ab))
+    if rc:
+        raise OracleError("oracle_score_rows", rc)
+    return f32, f64, ab
+
+
+def expand_clusters(clusters: np.ndarray, H: int, Nc: int, cl_off: np.ndarray, cl_entries: np.ndarray, cap_e: int):
+    """clusters int32 [groups][Sc] (-1 padding); cl_off int32 [H][Nc+1]; cl_entries int32 [H][E] ->
+    (entries int32 [groups][cap_e] (-1 padded), count int32 [groups])."""
+    clusters = _c(clusters, np.int32)
+    cl_off, cl_entries = _c(cl_off, np.int32), _c(cl_entries, np.int32)
+    groups, Sc = clusters.shape
+    E = cl_entries.shape[1]
+    assert cl_off.shape == (H, Nc + 1) and cl_entries.shape == (H, E)
+    entries = np.empty((groups, cap_e), np.int32)
+    count = np.empty(groups, np.int32)
+    rc = lib().oracle_expand_clusters(_p(clusters), C.c_int64(groups), Sc, H, Nc, _p(cl_off), _p(cl_entries), E, _p(entries),
+                                      _p(count), cap_e)
+    if rc:
+        raise OracleError("oracle_expand_clusters", rc)
+    return entries, count
+
+
+def submission_order(q_off: np.ndarray, q_cluster: np.ndarray):
+    """q_off int32 [groups][D+1], q_cluster int32 [groups][cap] -> (order [groups][cap], batch_off [groups][cap+1], nb [groups])."""
+    q_off, q_cluster = _c(q_off, np.int32), _c(q_cluster, np.int32)
+    groups, D1 = q_off.shape
+    cap = q_cluster.shape[1]
+    order = np.empty((groups, cap), np.int32)
+    batch_off = np.empty((groups, cap + 1), np.int32)
+    nb = np.empty(groups, np.int32)
+    rc = lib().oracle_submission_order(_p(q_off), _p(q_cluster), C.c_int64(groups), D1 - 1, cap, _p(order), _p(batch_off), _p(nb))
+    if rc:
+        raise OracleError("oracle_submission_order", rc)
+    return order, batch_off, nb
 
 
 def map_requests(sel: np.ndarray, H: int, N: int, e2c: np.ndarray, Nc: int, replicas: np.ndarray, D: int,

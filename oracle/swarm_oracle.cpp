@@ -65,6 +65,30 @@ extern "C" {
 // out_f64 (nullable) the double result; out_abs (nullable) = sum of |terms| (the magnitude the
 // floating-point tolerance is scaled by).
 // ---------------------------------------------------------------------------------------
+// One entry's score against the G query heads of one KV head: s (fp64 sum, channels ascending, query
+// heads in turn) and a (sum of the terms' magnitudes).
+static void score_row(int kind, const uint16_t* row, const uint16_t* qhead, int G, int d, double* s_out, double* a_out) {
+    double s = 0.0, a = 0.0;
+    for (int g = 0; g < G; ++g) {
+        const uint16_t* qv = qhead + (int64_t)g * d;
+        for (int c = 0; c < d; ++c) {
+            const double qc = bf16_to_double(qv[c]);
+            double term;
+            if (kind == 0) {
+                term = qc * bf16_to_double(row[c]);
+            } else {
+                const double lo_t = qc * bf16_to_double(row[c]);       // q * min
+                const double hi_t = qc * bf16_to_double(row[d + c]);   // q * max
+                term = std::max(lo_t, hi_t);
+            }
+            s += term;
+            a += std::fabs(term);
+        }
+    }
+    *s_out = s;
+    *a_out = a;
+}
+
 int oracle_score(int kind, const uint16_t* keys, const uint16_t* q, int B, int H, int G, int N, int d,
                  float* out_f32, double* out_f64, double* out_abs, int nthreads) {
     if (!keys || !q || B < 1 || H < 1 || G < 1 || N < 1 || d < 1 || (kind != 0 && kind != 1)) return -1;
@@ -73,24 +97,8 @@ int oracle_score(int kind, const uint16_t* keys, const uint16_t* q, int B, int H
         for (int64_t bh = lo; bh < hi; ++bh) {
             const int b = (int)(bh / H), h = (int)(bh % H);
             for (int n = 0; n < N; ++n) {
-                const uint16_t* row = keys + ((int64_t)h * N + n) * row_len;
-                double s = 0.0, a = 0.0;
-                for (int g = 0; g < G; ++g) {
-                    const uint16_t* qv = q + ((int64_t)b * H * G + (int64_t)h * G + g) * d;
-                    for (int c = 0; c < d; ++c) {
-                        const double qc = bf16_to_double(qv[c]);
-                        double term;
-                        if (kind == 0) {
-                            term = qc * bf16_to_double(row[c]);
-                        } else {
-                            const double lo_t = qc * bf16_to_double(row[c]);       // q * min
-                            const double hi_t = qc * bf16_to_double(row[d + c]);   // q * max
-                            term = std::max(lo_t, hi_t);
-                        }
-                        s += term;
-                        a += std::fabs(term);
-                    }
-                }
+                double s, a;
+                score_row(kind, keys + ((int64_t)h * N + n) * row_len, q + ((int64_t)b * H * G + (int64_t)h * G) * d, G, d, &s, &a);
                 const int64_t o = ((int64_t)b * H + h) * N + n;
                 if (out_f32) out_f32[o] = static_cast<float>(s);
                 if (out_f64) out_f64[o] = s;
@@ -98,6 +106,27 @@ int oracle_score(int kind, const uint16_t* keys, const uint16_t* q, int B, int H
             }
         }
     });
+    return 0;
+}
+
+// The same scores for the listed entries only (medoid index, Section 5.2 Tier 1):
+// out[b][h][m] = score of entry row_ids[h][m].  Returns -2 on an id outside [0,N).
+int oracle_score_rows(int kind, const uint16_t* keys, const int32_t* row_ids, int M, const uint16_t* q, int B, int H, int G,
+                      int N, int d, float* out_f32, double* out_f64, double* out_abs) {
+    if (!keys || !row_ids || !q || B < 1 || H < 1 || G < 1 || N < 1 || M < 1 || d < 1 || (kind != 0 && kind != 1)) return -1;
+    const int64_t row_len = (kind == 0) ? d : 2 * (int64_t)d;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h)
+            for (int m = 0; m < M; ++m) {
+                const int32_t n = row_ids[(int64_t)h * M + m];
+                if (n < 0 || n >= N) return -2;
+                double s, a;
+                score_row(kind, keys + ((int64_t)h * N + n) * row_len, q + ((int64_t)b * H * G + (int64_t)h * G) * d, G, d, &s, &a);
+                const int64_t o = ((int64_t)b * H + h) * M + m;
+                if (out_f32) out_f32[o] = static_cast<float>(s);
+                if (out_f64) out_f64[o] = s;
+                if (out_abs) out_abs[o] = a;
+            }
     return 0;
 }
 
@@ -214,7 +243,8 @@ int oracle_coact_update(const int32_t* idx, int64_t rows, int H, int k, int N, i
 //      q_load[g][D].
 // The unit routed is a cluster (the paper's atomic retrieval unit); with Nc = N, identity e2c
 // and unit weights this is exactly the paper's per-entry rule.
-// Returns -2 on an out-of-range entry / cluster / SSD id, -4 if cap is too small.
+// An entry id of -1 is padding (ragged selections) and is skipped.
+// Returns -2 on any other out-of-range entry / cluster / SSD id, -4 if cap is too small.
 // ---------------------------------------------------------------------------------------
 int oracle_map(const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c, int Nc,
                const int32_t* replicas, int R, int D, const int32_t* weight, const uint32_t* resident,
@@ -228,6 +258,7 @@ int oracle_map(const int32_t* sel, int64_t groups, int S, int H, int N, const in
             std::vector<uint8_t> seen(Nc, 0);
             for (int s = 0; s < S; ++s) {
                 const int32_t e = sel[g * S + s];
+                if (e == -1) continue;                            // padding of a ragged selection
                 if (e < 0 || e >= N) { status[g] = -2; break; }
                 const int32_t c = e2c[(int64_t)h * N + e];
                 if (c < 0 || c >= Nc) { status[g] = -2; break; }
@@ -278,6 +309,77 @@ int oracle_map(const int32_t* sel, int64_t groups, int S, int H, int N, const in
     });
     for (int64_t g = 0; g < groups; ++g)
         if (status[g]) return status[g];
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------------
+// Medoid-indexed retrieval (Section 5.2, Tier 1: every cluster's medoid is its index entry, scored
+// against the query to decide whether the cluster is retrieved; Section 6.1: the activated clusters
+// are merged into the set of entries to transfer).
+//
+// oracle_score_rows: the score of oracle_score, for the listed entries only:
+//   out[b][h][m] = score of entry row_ids[h][m]   (fp32 and fp64; abs = sum of |terms|)
+// oracle_expand_clusters: per group g (head g % H), the distinct activated clusters in ascending id,
+// each replaced by its member entries in stored order: entries[g][0..count[g]) then -1 padding.
+// Entries shared by several clusters appear once per cluster; the merge into a set (and the removal
+// of DRAM-resident entries) is the mapping step's.  clusters int32 [groups][Sc] (-1 = padding);
+// cl_off int32 [H][Nc+1] offsets into cl_entries int32 [H][E].  Returns -4 if cap_e is too small.
+// ---------------------------------------------------------------------------------------
+int oracle_expand_clusters(const int32_t* clusters, int64_t groups, int Sc, int H, int Nc, const int32_t* cl_off,
+                           const int32_t* cl_entries, int E, int32_t* entries, int32_t* count, int cap_e) {
+    if (!clusters || !cl_off || !cl_entries || !entries || !count || groups < 0 || Sc < 1 || H < 1 || Nc < 1 || cap_e < 1) return -1;
+    for (int64_t g = 0; g < groups; ++g) {
+        const int h = (int)(g % H);
+        std::vector<uint8_t> seen(Nc, 0);
+        for (int s = 0; s < Sc; ++s) {
+            const int32_t c = clusters[g * Sc + s];
+            if (c == -1) continue;
+            if (c < 0 || c >= Nc) return -2;
+            seen[c] = 1;
+        }
+        int32_t n = 0;
+        for (int c = 0; c < Nc; ++c) {
+            if (!seen[c]) continue;
+            const int32_t lo = cl_off[(int64_t)h * (Nc + 1) + c], hi = cl_off[(int64_t)h * (Nc + 1) + c + 1];
+            if (lo < 0 || hi < lo || hi > E) return -2;
+            for (int32_t p = lo; p < hi; ++p) {
+                if (n >= cap_e) return -4;
+                entries[g * cap_e + n++] = cl_entries[(int64_t)h * E + p];
+            }
+        }
+        count[g] = n;
+        for (int32_t p = n; p < cap_e; ++p) entries[g * cap_e + p] = -1;
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------------
+// Submission order (Section 6.1, last paragraph: the head entry of every bucket is taken in turn and
+// the heads form one submission batch).  From the buckets of oracle_map: order[g] lists the routed
+// items batch by batch -- batch b holds the b-th item of every bucket that has one, in ascending SSD
+// id -- and batch_off[g][b] is where batch b starts (batch_off[g][nb[g]] = number of items).
+// order int32 [groups][cap] (-1 padded); batch_off int32 [groups][cap+1] (entries past nb[g] repeat
+// the total); nb int32 [groups].
+// ---------------------------------------------------------------------------------------
+int oracle_submission_order(const int32_t* q_off, const int32_t* q_cluster, int64_t groups, int D, int cap, int32_t* order,
+                            int32_t* batch_off, int32_t* nb) {
+    if (!q_off || !q_cluster || !order || !batch_off || !nb || groups < 0 || D < 1 || cap < 1) return -1;
+    for (int64_t g = 0; g < groups; ++g) {
+        const int32_t* off = q_off + g * (D + 1);
+        std::vector<int32_t> head(off, off + D);                   // next unread position of every bucket
+        int32_t n = 0, b = 0;
+        for (;;) {
+            bool any = false;
+            const int32_t start = n;
+            for (int d = 0; d < D; ++d)
+                if (head[d] < off[d + 1]) { order[g * cap + n++] = q_cluster[g * cap + head[d]++]; any = true; }
+            if (!any) break;
+            batch_off[g * (cap + 1) + b++] = start;
+        }
+        nb[g] = b;
+        for (int32_t p = b; p <= cap; ++p) batch_off[g * (cap + 1) + p] = n;
+        for (int32_t p = n; p < cap; ++p) order[g * cap + p] = -1;
+    }
     return 0;
 }
 
