@@ -180,6 +180,14 @@ def main():
         sw.window_assign(win_sel, N, new_d, med_d, 1.0 - 8.0 / 256, want_counts=False)
 
     win_us, win_us_min = stage(window, reps, 1)
+    # medoid index: score and select over one medoid per cluster instead of every page
+    kc = max(1, min(cfg.Nc, k // 8))
+
+    def medoid_steps():
+        for t in range(0, T, 8):
+            sw.score_select_indexed(cfg.unit, layers[t % len(layers)], med_d, q_d[t], kc, G=cfg.G)
+
+    med_us, med_us_min = stage(medoid_steps, reps, T // 8)
     coact_ms = coact_us * 1e-3
     # the same sweep out of one buffer: served by the 256 MB last-level cache, not by HBM
     layers_all, layers[:] = list(layers), [layers[0]]
@@ -230,6 +238,9 @@ def main():
                          "bytes": 2 * H * N * N * 4, "achieved_GBs": round(2 * H * N * N * 4 / (dens_us * 1e-6) / 1e9, 1)},
         "window_maintenance": {"what": "last 256 steps, 256 new entries x %d medoids per head: trace bits + counts + membership" % cfg.Nc,
                                "us": round(win_us, 1), "us_min": round(win_us_min, 1)},
+        "medoid_index": {"what": "score + select over %d medoids per head (top %d) instead of %d pages" % (cfg.Nc, kc, N),
+                         "us_per_step": round(med_us, 3), "us_min": round(med_us_min, 3),
+                         "speedup_vs_full_score_select": round(sel_us / med_us, 2)},
         "measured_peaks": peaks,
         "stages": {"timing": f"median (min) over {reps} graph replays, HIP events on the launch stream",
                    "step_us": round(step_us, 3), "step_us_min": round(step_us_min, 3),

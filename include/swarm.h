@@ -201,7 +201,8 @@ swarm_status swarm_window_assign(swarm_ctx* ctx, const int32_t* sel, int32_t W, 
  *      load += weight[head*Nc + c] (1 when weight is NULL);
  *   4. emit the buckets SSD-major, each in insertion order.
  *
- * sel        device, int32 [groups][S] entry ids (repeats allowed; all streams of a step merged).
+ * sel        device, int32 [groups][S] entry ids (repeats allowed; all streams of a step merged; -1 is
+ *            padding and is skipped).
  * e2c        device, int32 [H][N] cluster of each entry, in [0,Nc).
  * replicas   device, int32 [H*Nc][R]: distinct SSD ids in [0,D); a slot < 0 is unused.
  * weight     device, int32 [H*Nc] or NULL.
@@ -219,6 +220,39 @@ swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t grou
                                 const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
                                 const int32_t* weight, const uint32_t* resident,
                                 int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap);
+
+/*
+ * Medoid-indexed retrieval (Section 5.2, Tier 1: the medoid of each cluster is its index entry and is
+ * scored against the query to decide whether the cluster is retrieved; Section 6.1: the activated
+ * clusters are merged into the set of entries to transfer, which the mapping step routes entry by
+ * entry; the finished buckets are submitted head by head).  Three calls around swarm_map_requests:
+ *
+ * swarm_score_select_indexed: as swarm_score_select, over the listed entries only.
+ *   row_ids    device, int32 [H][M], entry ids in [0,N) (an id outside scores 0 and is flagged).
+ *   scores     s[b][h][m] = score of entry row_ids[h][m]; out_scores fp32 [B][H][M] or NULL.
+ *   out_idx    device, int32 [B][H][k]: positions m in the list (ascending), 1 <= k <= M.
+ *
+ * swarm_expand_clusters: per group g (head g % H) the distinct clusters of clusters[g][0..Sc) (-1 is
+ *   padding) in ascending id, each replaced by its members cl_entries[h][cl_off[h][c] .. cl_off[h][c+1]):
+ *   entries[g][0..count[g]), then -1 padding up to cap_e (too small a cap_e truncates and raises
+ *   SWARM_DEV_CAP).  An entry held by several activated clusters appears once per cluster; merging into
+ *   a set, and dropping DRAM-resident entries, is what swarm_map_requests then does (with Nc = N and the
+ *   identity entry->cluster table it routes entries, replication factor = number of SSD copies).
+ *   cl_off device int32 [H][Nc+1]; cl_entries device int32 [H][E]; Nc <= 2^18.
+ *
+ * swarm_submission_order: order[g] lists the items of swarm_map_requests' buckets batch by batch (batch
+ *   b = the b-th item of every bucket that has one, ascending SSD id), -1 padded to cap;
+ *   batch_off[g][b] is where batch b starts (entries from nb[g] on repeat the item count), int32
+ *   [groups][cap+1]; nb[g] = number of batches = longest bucket.
+ * In swarm_map_requests an entry id of -1 is padding and is skipped, so ragged entry lists can be mapped.
+ */
+swarm_status swarm_score_select_indexed(swarm_ctx* ctx, const swarm_keys* keys, const int32_t* row_ids, int32_t M, const void* q,
+                                        int32_t B, int32_t k, int32_t* out_idx, float* out_scores);
+swarm_status swarm_expand_clusters(swarm_ctx* ctx, const int32_t* clusters, int64_t groups, int32_t Sc, int32_t H, int32_t Nc,
+                                   const int32_t* cl_off, const int32_t* cl_entries, int32_t E, int32_t* entries, int32_t* count,
+                                   int32_t cap_e);
+swarm_status swarm_submission_order(swarm_ctx* ctx, const int32_t* q_off, const int32_t* q_cluster, int64_t groups, int32_t D,
+                                    int32_t cap, int32_t* order, int32_t* batch_off, int32_t* nb);
 
 /*
  * One decode step of a single stream: swarm_score_select with B = 1 followed by swarm_map_requests on

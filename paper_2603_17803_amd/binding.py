@@ -19,7 +19,8 @@ SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
 
 EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score", "swarm_score_select",
-           "swarm_coact_accumulate", "swarm_map_requests", "swarm_coact_density", "swarm_window_assign", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
+           "swarm_coact_accumulate", "swarm_map_requests", "swarm_coact_density", "swarm_window_assign", "swarm_score_select_indexed", "swarm_expand_clusters",
+           "swarm_submission_order", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
 
 
@@ -58,6 +59,9 @@ def load() -> C.CDLL:
     L.swarm_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_coact_density.argtypes = [vp, vp, i32, i32, vp, C.c_double, C.c_uint32, vp, vp, vp]
     L.swarm_window_assign.argtypes = [vp, vp, i32, i32, i32, i32, vp, i32, vp, i32, C.c_double, vp, vp, i32, vp, vp, vp]
+    L.swarm_score_select_indexed.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp]
+    L.swarm_expand_clusters.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, i32, vp, vp, i32]
+    L.swarm_submission_order.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp, vp]
     L.swarm_calibrate.argtypes = [vp, i32, vp, C.c_size_t, i32, C.POINTER(C.c_double)]
     L.swarm_capture_begin.argtypes = [vp]
     L.swarm_capture_end.argtypes = [vp, C.POINTER(vp)]
@@ -125,6 +129,25 @@ def swarm_window_assign(ctx: int, sel: int, W: int, H: int, k: int, N: int, new_
     return load().swarm_window_assign(C.c_void_p(ctx), C.c_void_p(sel), W, H, k, N, C.c_void_p(new_ids), n_new,
                                       C.c_void_p(medoids), Nc, tau, C.c_void_p(primary), C.c_void_p(size), D,
                                       C.c_void_p(f_out), C.c_void_p(member), C.c_void_p(disk))
+
+
+def swarm_score_select_indexed(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, row_ids: int, M: int, q: int, B: int,
+                               k: int, out_idx: int, out_scores: Optional[int]) -> int:
+    ks = swarm_keys(kind, data, H, N, d, G)
+    return load().swarm_score_select_indexed(C.c_void_p(ctx), C.byref(ks), C.c_void_p(row_ids), M, C.c_void_p(q), B, k,
+                                             C.c_void_p(out_idx), C.c_void_p(out_scores))
+
+
+def swarm_expand_clusters(ctx: int, clusters: int, groups: int, Sc: int, H: int, Nc: int, cl_off: int, cl_entries: int, E: int,
+                          entries: int, count: int, cap_e: int) -> int:
+    return load().swarm_expand_clusters(C.c_void_p(ctx), C.c_void_p(clusters), groups, Sc, H, Nc, C.c_void_p(cl_off),
+                                        C.c_void_p(cl_entries), E, C.c_void_p(entries), C.c_void_p(count), cap_e)
+
+
+def swarm_submission_order(ctx: int, q_off: int, q_cluster: int, groups: int, D: int, cap: int, order: int, batch_off: int,
+                           nb: int) -> int:
+    return load().swarm_submission_order(C.c_void_p(ctx), C.c_void_p(q_off), C.c_void_p(q_cluster), groups, D, cap,
+                                         C.c_void_p(order), C.c_void_p(batch_off), C.c_void_p(nb))
 
 
 def swarm_coact_density(ctx: int, Cptr: int, H: int, N: int, totals_in: Optional[int], tau: float, flags: int, rho: int,
@@ -300,6 +323,53 @@ class Swarm:
                                  None if disk is None else self._dev(disk, torch.int32, "disk"))
         self._check("swarm_window_assign", rc)
         return f, member, disk
+
+    def score_select_indexed(self, kind: str, keys, row_ids, q, k: int, G: int = 1, want_scores: bool = False):
+        """Scores and selects over the listed entries only: row_ids int32 [H][M]; returns (positions int32 [B][H][k],
+        scores fp32 [B][H][M] or None)."""
+        torch = self.torch
+        b16 = (torch.bfloat16, torch.int16, torch.uint16)
+        H, N, d = keys.shape[0], keys.shape[1], keys.shape[-1]
+        B, M = q.shape[0], row_ids.shape[1]
+        if tuple(q.shape) != (B, H * G, d) or tuple(row_ids.shape) != (H, M):
+            raise ValueError("q must be [B][H*G][d] and row_ids [H][M]")
+        out_idx = torch.empty((B, H, k), dtype=torch.int32, device=self.device)
+        out_scores = torch.empty((B, H, M), dtype=torch.float32, device=self.device) if want_scores else None
+        rc = swarm_score_select_indexed(self.ctx, SWARM_KEYS_TOKEN if kind == "token" else SWARM_KEYS_PAGE_MINMAX,
+                                        self._dev(keys, b16, "keys"), H, N, d, G, self._dev(row_ids, torch.int32, "row_ids"), M,
+                                        self._dev(q, b16, "q"), B, k, self._dev(out_idx, torch.int32, "out_idx"),
+                                        None if out_scores is None else self._dev(out_scores, torch.float32, "out_scores"))
+        self._check("swarm_score_select_indexed", rc)
+        return out_idx, out_scores
+
+    def expand_clusters(self, clusters, H: int, Nc: int, cl_off, cl_entries, cap_e: int):
+        """clusters int32 [groups][Sc] -> (entries int32 [groups][cap_e] (-1 padded), count int32 [groups])."""
+        torch = self.torch
+        groups, Sc = clusters.shape
+        E = cl_entries.shape[1]
+        if tuple(cl_off.shape) != (H, Nc + 1) or cl_entries.shape[0] != H:
+            raise ValueError("cl_off must be [H][Nc+1] and cl_entries [H][E]")
+        entries = torch.empty((groups, cap_e), dtype=torch.int32, device=self.device)
+        count = torch.empty((groups,), dtype=torch.int32, device=self.device)
+        rc = swarm_expand_clusters(self.ctx, self._dev(clusters, torch.int32, "clusters"), groups, Sc, H, Nc,
+                                   self._dev(cl_off, torch.int32, "cl_off"), self._dev(cl_entries, torch.int32, "cl_entries"), E,
+                                   self._dev(entries, torch.int32, "entries"), self._dev(count, torch.int32, "count"), cap_e)
+        self._check("swarm_expand_clusters", rc)
+        return entries, count
+
+    def submission_order(self, q_off, q_cluster):
+        """(q_off [groups][D+1], q_cluster [groups][cap]) -> (order [groups][cap], batch_off [groups][cap+1], nb [groups])."""
+        torch = self.torch
+        groups, D1 = q_off.shape
+        cap = q_cluster.shape[1]
+        order = torch.empty((groups, cap), dtype=torch.int32, device=self.device)
+        batch_off = torch.empty((groups, cap + 1), dtype=torch.int32, device=self.device)
+        nb = torch.empty((groups,), dtype=torch.int32, device=self.device)
+        rc = swarm_submission_order(self.ctx, self._dev(q_off, torch.int32, "q_off"), self._dev(q_cluster, torch.int32, "q_cluster"),
+                                    groups, D1 - 1, cap, self._dev(order, torch.int32, "order"),
+                                    self._dev(batch_off, torch.int32, "batch_off"), self._dev(nb, torch.int32, "nb"))
+        self._check("swarm_submission_order", rc)
+        return order, batch_off, nb
 
     def map_requests(self, sel, H: int, N: int, e2c, Nc: int, replicas, D: int, weight=None, resident=None,
                      cap: Optional[int] = None, out=None):

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswarm.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "coact.hip", "mapper.hip", "density.hip", "window.hip", "calib.hip"]
+SOURCES = ["api.hip", "score.hip", "select.hip", "coact.hip", "mapper.hip", "density.hip", "window.hip", "retrieval.hip", "calib.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # the fully unrolled epilogues of the co-activation kernel exceed the default budget of "#pragma unroll";

@@ -145,6 +145,47 @@ swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const vo
     return launch_select(ctx, scores, (int64_t)B * keys->H, keys->N, k, out_idx);
 }
 
+swarm_status swarm_score_select_indexed(swarm_ctx* ctx, const swarm_keys* keys, const int32_t* row_ids, int32_t M, const void* q,
+                                        int32_t B, int32_t k, int32_t* out_idx, float* out_scores) {
+    if (!ctx) return SWARM_EINVAL;
+    swarm_status st = check_score_args(ctx, "score_select_indexed", keys, q, B);
+    if (st != SWARM_OK) return st;
+    if (!row_ids || !out_idx) SWARM_REJECT(ctx, "score_select_indexed: NULL row_ids or out_idx");
+    if (M < 1) SWARM_REJECT(ctx, "score_select_indexed: M=%d must be >= 1", M);
+    if (k < 1 || k > M) SWARM_REJECT(ctx, "score_select_indexed: k=%d outside [1,M=%d]", k, M);
+    if (out_scores && (reinterpret_cast<uintptr_t>(out_scores) & 3)) SWARM_REJECT(ctx, "score_select_indexed: out_scores misaligned");
+    float* scores = out_scores;
+    if (!scores) {
+        st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->scores), &ctx->scores_bytes, sizeof(float) * (size_t)B * keys->H * M);
+        if (st != SWARM_OK) return st;
+        scores = ctx->scores;
+    }
+    st = launch_score(ctx, keys, q, B, scores, row_ids, M);
+    if (st != SWARM_OK) return st;
+    return launch_select(ctx, scores, (int64_t)B * keys->H, M, k, out_idx);
+}
+
+swarm_status swarm_expand_clusters(swarm_ctx* ctx, const int32_t* clusters, int64_t groups, int32_t Sc, int32_t H, int32_t Nc,
+                                   const int32_t* cl_off, const int32_t* cl_entries, int32_t E, int32_t* entries, int32_t* count,
+                                   int32_t cap_e) {
+    if (!ctx) return SWARM_EINVAL;
+    if (!clusters || !cl_off || !cl_entries || !entries || !count) SWARM_REJECT(ctx, "expand_clusters: NULL required pointer");
+    if (groups < 1 || groups > ((int64_t)1 << 30) || Sc < 1 || H < 1 || Nc < 1 || E < 1 || cap_e < 1)
+        SWARM_REJECT(ctx, "expand_clusters: groups=%lld Sc=%d H=%d Nc=%d E=%d cap_e=%d must all be >= 1", (long long)groups, Sc,
+                     H, Nc, E, cap_e);
+    if (Nc > (1 << 18)) SWARM_REJECT(ctx, "expand_clusters: Nc=%d above 2^18", Nc);
+    return launch_expand_clusters(ctx, clusters, groups, Sc, H, Nc, cl_off, cl_entries, E, entries, count, cap_e);
+}
+
+swarm_status swarm_submission_order(swarm_ctx* ctx, const int32_t* q_off, const int32_t* q_cluster, int64_t groups, int32_t D,
+                                    int32_t cap, int32_t* order, int32_t* batch_off, int32_t* nb) {
+    if (!ctx) return SWARM_EINVAL;
+    if (!q_off || !q_cluster || !order || !batch_off || !nb) SWARM_REJECT(ctx, "submission_order: NULL required pointer");
+    if (groups < 1 || groups > ((int64_t)1 << 30) || D < 1 || D > 64 || cap < 1)
+        SWARM_REJECT(ctx, "submission_order: groups=%lld D=%d cap=%d out of range", (long long)groups, D, cap);
+    return launch_submission_order(ctx, q_off, q_cluster, groups, D, cap, order, batch_off, nb);
+}
+
 swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int32_t H, int32_t k,
                                     int32_t N, int32_t* C, uint32_t decay_q16, uint32_t flags) {
     if (!ctx) return SWARM_EINVAL;

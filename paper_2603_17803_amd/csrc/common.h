@@ -53,7 +53,8 @@ swarm_status swarm_grow(swarm_ctx* ctx, void** buf, size_t* have, size_t bytes);
 
 // --- kernel launchers (each enqueues on ctx->stream and reports launch errors) ---------------
 constexpr int SWARM_BATCHED_MIN_STREAMS = 8;   // from this many streams on, scoring runs as a GEMM on the matrix cores
-swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores);
+swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores,
+                          const int32_t* row_ids = nullptr, int M = 0);
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx);
 swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
                                 int nruns, uint32_t flags);
@@ -66,6 +67,11 @@ swarm_status launch_density(swarm_ctx* ctx, const int32_t* C, int H, int N, cons
 swarm_status launch_window(swarm_ctx* ctx, int nruns, int Npad, int N, int W, int H, const int32_t* new_ids, int n_new,
                            const int32_t* medoids, int Nc, double tau, const int32_t* primary, const int32_t* size, int D,
                            int32_t* f_out, uint8_t* member, int32_t* disk);
+swarm_status launch_expand_clusters(swarm_ctx* ctx, const int32_t* clusters, int64_t groups, int Sc, int H, int Nc,
+                                    const int32_t* cl_off, const int32_t* cl_entries, int E, int32_t* entries, int32_t* count,
+                                    int cap_e);
+swarm_status launch_submission_order(swarm_ctx* ctx, const int32_t* q_off, const int32_t* q_cluster, int64_t groups, int D, int cap,
+                                     int32_t* order, int32_t* batch_off, int32_t* nb);
 swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N, int k, int32_t* out_idx,
                                const int32_t* e2c, int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                                const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap,

@@ -225,6 +225,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         } else {
             e = sel[s0];
         }
+        if (e == -1) continue;                       // padding of a ragged selection
         if (e < 0 || e >= a.N) { flags |= SWARM_DEV_BAD_ENTRY; continue; }
         const int32_t c = stage_e2c ? s_e2c[e] : e2c[e];
         if (c < 0 || c >= a.Nc) { flags |= SWARM_DEV_BAD_CLUSTER; continue; }

@@ -55,7 +55,8 @@ __device__ __forceinline__ void load_weights(const uint16_t* __restrict__ qbh, i
 // rows in flight per lane.  CH = 16-byte chunks per row.
 template <int LPR, int NCH, int UNROLL, bool PAGE>
 __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ rows, const uint16_t* __restrict__ q,
-                                                    float* __restrict__ out, int N, int H, int G, int d, int CH, int iters) {
+                                                    float* __restrict__ out, int N, int H, int G, int d, int CH, int iters,
+                                                    const int32_t* __restrict__ row_ids, int M, uint32_t* __restrict__ dev_flags) {
     constexpr int RPW = 64 / LPR;
     constexpr int RPB = 4 * UNROLL * RPW;
     const int h = blockIdx.y, b = blockIdx.z;
@@ -76,8 +77,12 @@ __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ ro
         }
     }
 
+    // With a row list (medoid index, Section 5.2 Tier 1) output row n is the score of entry row_ids[h][n];
+    // an id outside [0,N) scores 0 and is flagged.
     const u32x4* base = rows + (size_t)h * N * CH;
-    float* o = out + ((size_t)b * H + h) * N;
+    const int nout = row_ids ? M : N;
+    const int32_t* ids = row_ids ? row_ids + (size_t)h * M : nullptr;
+    float* o = out + ((size_t)b * H + h) * nout;
     // `iters` row groups per workgroup, a grid width apart: fewer, longer-lived workgroups measured
     // a few percent faster on long sweeps
 #pragma unroll 1
@@ -87,9 +92,15 @@ __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ ro
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int n = row0 + u * RPW;
+        int src = n;
+        bool ok = n < nout;
+        if (ids && ok) {
+            src = ids[n];
+            if (src < 0 || src >= N) { ok = false; atomicOr(dev_flags, SWARM_DEV_BAD_ENTRY); }
+        }
 #pragma unroll
         for (int m = 0; m < NCH; ++m) {
-            if (n < N && chunk_ok[m]) x[u][m] = __builtin_nontemporal_load(base + (size_t)n * CH + sub + m * LPR);
+            if (ok && chunk_ok[m]) x[u][m] = __builtin_nontemporal_load(base + (size_t)src * CH + sub + m * LPR);
             else x[u][m] = u32x4{0, 0, 0, 0};
         }
     }
@@ -112,13 +123,13 @@ __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ ro
 #pragma unroll
         for (int u = 1; u < UNROLL; ++u) v = (sub == u) ? p[u] : v;
         const int n = row0 + sub * RPW;
-        if (sub < UNROLL && n < N) o[n] = v;
+        if (sub < UNROLL && n < nout) o[n] = v;
     } else {
         if (sub == 0) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const int n = row0 + u * RPW;
-                if (n < N) o[n] = p[u];
+                if (n < nout) o[n] = p[u];
             }
         }
     }
@@ -127,27 +138,29 @@ __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ ro
 
 
 template <int LPR, int NCH, bool PAGE>
-void launch_one(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int CH) {
+void launch_one(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int CH, const int32_t* row_ids,
+                int M, uint32_t* dev_flags) {
     constexpr int UNROLL = (NCH == 2 || LPR >= 16) ? 4 : 8;
     constexpr int RPB = 4 * UNROLL * (64 / LPR);
-    const int groups = (keys->N + RPB - 1) / RPB;
+    const int groups = ((row_ids ? M : keys->N) + RPB - 1) / RPB;
     const int iters = ((long)groups * keys->H * B >= 2048) ? 2 : 1;
     dim3 grid((groups + iters - 1) / iters, keys->H, B);
     hipLaunchKernelGGL((score_kernel<LPR, NCH, UNROLL, PAGE>), grid, dim3(256), 0, st,
                        static_cast<const u32x4*>(keys->data), static_cast<const uint16_t*>(q), scores, keys->N, keys->H,
-                       keys->G, keys->d, CH, iters);
+                       keys->G, keys->d, CH, iters, row_ids, M, dev_flags);
 }
 
 template <bool PAGE>
-void dispatch(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int CH) {
-    if (CH > 64) return launch_one<64, 2, PAGE>(st, keys, q, B, scores, CH);
-    if (CH > 32) return launch_one<64, 1, PAGE>(st, keys, q, B, scores, CH);
-    if (CH > 16) return launch_one<32, 1, PAGE>(st, keys, q, B, scores, CH);
-    if (CH > 8) return launch_one<16, 1, PAGE>(st, keys, q, B, scores, CH);
-    if (CH > 4) return launch_one<8, 1, PAGE>(st, keys, q, B, scores, CH);
-    if (CH > 2) return launch_one<4, 1, PAGE>(st, keys, q, B, scores, CH);
-    if (CH > 1) return launch_one<2, 1, PAGE>(st, keys, q, B, scores, CH);
-    return launch_one<1, 1, PAGE>(st, keys, q, B, scores, CH);
+void dispatch(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int CH, const int32_t* row_ids, int M,
+              uint32_t* dev_flags) {
+    if (CH > 64) return launch_one<64, 2, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
+    if (CH > 32) return launch_one<64, 1, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
+    if (CH > 16) return launch_one<32, 1, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
+    if (CH > 8) return launch_one<16, 1, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
+    if (CH > 4) return launch_one<8, 1, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
+    if (CH > 2) return launch_one<4, 1, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
+    if (CH > 1) return launch_one<2, 1, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
+    return launch_one<1, 1, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
 }
 
 
@@ -264,7 +277,8 @@ void launch_batched(hipStream_t st, const swarm_keys* keys, const uint16_t* whi,
 
 }  // namespace
 
-swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores) {
+swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores, const int32_t* row_ids,
+                          int M) {
     if (B > 65535 || keys->H > 65535) {
         snprintf(ctx->err, sizeof(ctx->err), "score: B=%d and H=%d must each be below 65536", B, keys->H);
         return SWARM_EINVAL;
@@ -273,7 +287,7 @@ swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q,
     const int L = page ? 2 * keys->d : keys->d;
     const int CH = L / 8;
     // many streams: matrix-core path (row lengths of 128 and 256 values, i.e. d = 128 or page rows of d = 64 / 128)
-    if (B >= SWARM_BATCHED_MIN_STREAMS && (L == 128 || L == 256) && keys->H <= 65535) {
+    if (!row_ids && B >= SWARM_BATCHED_MIN_STREAMS && (L == 128 || L == 256) && keys->H <= 65535) {
         const size_t wbytes = (size_t)B * keys->H * L * sizeof(uint16_t);
         swarm_status st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->weights), &ctx->weights_bytes, 2 * wbytes);
         if (st != SWARM_OK) return st;
@@ -293,7 +307,7 @@ swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q,
         else launch_batched<8>(ctx->stream, keys, whi, wlo, B, scores);
         return swarm_check_launch(ctx, "score_batched_kernel");
     }
-    if (page) dispatch<true>(ctx->stream, keys, q, B, scores, CH);
-    else dispatch<false>(ctx->stream, keys, q, B, scores, CH);
+    if (page) dispatch<true>(ctx->stream, keys, q, B, scores, CH, row_ids, M, ctx->dev_flags);
+    else dispatch<false>(ctx->stream, keys, q, B, scores, CH, row_ids, M, ctx->dev_flags);
     return swarm_check_launch(ctx, "score_kernel");
 }

@@ -429,6 +429,73 @@ def test_window_assign_bit_exact(sw, Wn, H, k, N, n_new, Nc):
     assert int(f[0, 0].abs().sum()) == 0 and sw.device_status() == binding.SWARM_DEV_BAD_ENTRY
 
 
+# --------------------------------------------------------------------------- medoid-indexed retrieval
+
+def test_medoid_indexed_retrieval_chain(sw):
+    """Medoid scoring -> cluster selection -> expansion into entries -> entry-level mapping (entries held by
+    several clusters, variable replication, DRAM-resident entries) -> submission order; every stage against
+    the oracle on the device's own inputs, bit-exact (scores within tolerance)."""
+    from paper_2603_17803_amd import binding
+    cfg = W.CONFIGS["llama8b_32k"].scaled(N=1536, T=4, H=3, k=24)
+    H, N, D, Nc = cfg.H, cfg.N, 6, 96
+    rng = np.random.default_rng(33)
+    K = W.keys(cfg)
+    Kd = dev(K)
+    medoids = np.stack([np.sort(rng.choice(N, Nc, replace=False)) for _ in range(H)]).astype(np.int32)
+    # clusters of 3..20 entries around their medoid; entries may sit in several clusters
+    sizes = rng.integers(3, 21, (H, Nc))
+    cl_off = np.zeros((H, Nc + 1), np.int32)
+    cl_off[:, 1:] = np.cumsum(sizes, axis=1)
+    E = int(cl_off[:, -1].max())
+    cl_entries = np.zeros((H, E), np.int32)
+    copies = [[[] for _ in range(N)] for _ in range(H)]       # SSDs holding each entry: one per membership
+    for h in range(H):
+        for c in range(Nc):
+            members = np.concatenate([[medoids[h, c]], rng.choice(N, sizes[h, c] - 1, replace=False)])
+            cl_entries[h, cl_off[h, c]:cl_off[h, c + 1]] = members
+            start = int(rng.integers(0, D))                    # the cluster's entries are striped from its first SSD on
+            for j, e in enumerate(members):
+                copies[h][e].append((start + j) % D)
+    R = 4
+    rep = np.full((H * N, R), -1, np.int32)
+    for h in range(H):
+        for e in range(N):
+            ssds = sorted(set(copies[h][e]))[:R] or [int(rng.integers(0, D))]
+            rep[h * N + e, :len(ssds)] = ssds
+    e2c_id = np.tile(np.arange(N, dtype=np.int32), (H, 1))
+    resident = rng.integers(0, 2 ** 32, (H * N + 31) // 32, dtype=np.uint32) & rng.integers(0, 2 ** 32, (H * N + 31) // 32, dtype=np.uint32)
+    med_d, off_d, ent_d, rep_d, e2c_d, res_d = dev(medoids), dev(cl_off), dev(cl_entries), dev(rep), dev(e2c_id), dev(resident)
+    cap_e = cfg.k * 20
+    for t in range(cfg.T):
+        q = W.queries(cfg, t, t + 1)[0]
+        pos, sc = sw.score_select_indexed(cfg.unit, Kd, med_d, dev(q), cfg.k, G=cfg.G, want_scores=True)
+        sc_h, pos_h = sc.cpu().numpy(), pos.cpu().numpy()
+        _, ref64, ab = oracle.score_rows(cfg.unit, K, medoids, q, G=cfg.G)
+        assert (np.abs(sc_h - ref64) <= score_tol(ref64, ab, 2 * cfg.d * cfg.G)).all()
+        assert np.array_equal(pos_h, oracle.select(sc_h, cfg.k, nthreads=4))
+        clusters = pos[0]                                       # [H][k]: positions in the medoid list = cluster ids
+        entries, count = sw.expand_clusters(clusters, H, Nc, off_d, ent_d, cap_e)
+        r_entries, r_count = oracle.expand_clusters(pos_h[0], H, Nc, cl_off, cl_entries, cap_e)
+        assert np.array_equal(entries.cpu().numpy(), r_entries) and np.array_equal(count.cpu().numpy(), r_count)
+        cap = int(r_count.max())
+        queues = sw.map_requests(entries, H, N, e2c_d, N, rep_d, D, None, res_d, cap=cap)
+        r_queues = oracle.map_requests(r_entries, H, N, e2c_id, N, rep, D, None, resident, cap=cap, nthreads=4)
+        for a_, b_ in zip(queues, r_queues):
+            assert np.array_equal(a_.cpu().numpy(), b_)
+        order, batch_off, nb = sw.submission_order(queues[0], queues[1])
+        r_order, r_batch, r_nb = oracle.submission_order(r_queues[0], r_queues[1])
+        assert np.array_equal(order.cpu().numpy(), r_order) and np.array_equal(batch_off.cpu().numpy(), r_batch)
+        assert np.array_equal(nb.cpu().numpy(), r_nb)
+    assert sw.device_status() == 0
+    # too small an expansion buffer truncates and flags; a bad medoid id scores 0 and flags
+    sw.expand_clusters(clusters, H, Nc, off_d, ent_d, 5)
+    assert sw.device_status() == binding.SWARM_DEV_CAP
+    bad = medoids.copy()
+    bad[1, 7] = N + 3
+    _, sc = sw.score_select_indexed(cfg.unit, Kd, dev(bad), dev(q), cfg.k, G=cfg.G, want_scores=True)
+    assert float(sc[0, 1, 7]) == 0.0 and sw.device_status() == binding.SWARM_DEV_BAD_ENTRY
+
+
 # --------------------------------------------------------------------------- one-call decode step
 
 STEP_CASES = [
