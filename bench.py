@@ -163,6 +163,11 @@ def main():
     step_us, step_us_min = stage(decode_steps, reps, T)
     map_us, map_us_min = stage(map_steps, reps, T)
     coact_us, coact_us_min = stage(coact, reps, 1)
+    def coact_popcount():
+        sw.coact_accumulate(idx_all, N, Cm, decay_q16=0, flags=binding.SWARM_COACT_POPCOUNT)
+
+    pop_us, pop_us_min = stage(coact_popcount, max(3, reps // 4), 1)
+    coact()                                                                      # leave the matrix-core result in C
     tau = 1.0 - 0.25 * float(Cm.max()) / (float(T) * k * k)
 
     def density():
@@ -232,7 +237,8 @@ def main():
                            "issued_ops": issued_ops, "dense_equivalent_tops": round(dense_ops / (coact_ms * 1e-3) / 1e12, 1),
                            "ms_per_build_incl_trace": round(coact_ms, 3), "ms_min": round(coact_us_min * 1e-3, 3),
                            "frac_of_measured_mfma_peak": round(coact_tops / peaks["mfma_i8_TOPs"], 4),
-                           "pair_increments_per_s": round(increments / (coact_ms * 1e-3), 0)},
+                           "pair_increments_per_s": round(increments / (coact_ms * 1e-3), 0),
+                           "popcount_route_ms": round(pop_us * 1e-3, 3)},
         "density_pass": {"what": "grand total, rho and medoid queue from C (two sweeps of C plus an N^2 ranking)",
                          "ms": round(dens_us * 1e-3, 3), "ms_min": round(dens_us_min * 1e-3, 3), "bound": "hbm",
                          "bytes": 2 * H * N * N * 4, "achieved_GBs": round(2 * H * N * N * 4 / (dens_us * 1e-6) / 1e9, 1)},

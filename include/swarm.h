@@ -62,6 +62,8 @@ typedef struct {
 
 /* flags of swarm_coact_accumulate */
 #define SWARM_CHECK_IDX 1u   /* validate range and distinctness of every selection on the device */
+#define SWARM_COACT_POPCOUNT 2u /* count with AND + popcount on the vector ALUs instead of the matrix cores:
+                                  same result by an independent route (cross-check, slower) */
 
 /* bits of swarm_device_status()'s *flags */
 #define SWARM_DEV_BAD_ENTRY   1u  /* entry id outside [0,N)                      */
@@ -129,7 +131,8 @@ swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, 
  * rows   trace rows in this call (steps x streams since the last call), 1 <= rows <= 2^24.
  * C      device, int32 [H][N][N] row-major, in/out, 16-byte aligned.
  * flags  SWARM_CHECK_IDX additionally flags repeated entries (SWARM_DEV_DUP_ENTRY); a repeated
- *        entry counts once either way, because the trace is binary.
+ *        entry counts once either way, because the trace is binary.  SWARM_COACT_POPCOUNT computes the
+ *        same counts as popcount(bits_i & bits_j) over the bit trace, without the matrix cores.
  * Errors: SWARM_EINVAL as above or decay_q16 > 65536; SWARM_ENOMEM if the trace (H*N*rows/8 bytes,
  * rows rounded up to 512, N to 256) cannot be allocated.
  */

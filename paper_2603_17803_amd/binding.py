@@ -121,6 +121,7 @@ def swarm_step(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q
 
 SWARM_CAL_HBM_READ, SWARM_CAL_HBM_WRITE, SWARM_CAL_MFMA_I8 = 0, 1, 2
 SWARM_RHO_EXCLUDE_SELF, SWARM_RHO_STRICT = 1, 2
+SWARM_COACT_POPCOUNT = 2
 
 
 def swarm_window_assign(ctx: int, sel: int, W: int, H: int, k: int, N: int, new_ids: int, n_new: int, medoids: int, Nc: int,

@@ -194,7 +194,7 @@ swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t 
     if (rows < 1 || rows > ((int64_t)1 << 24)) SWARM_REJECT(ctx, "coact_accumulate: rows=%lld outside [1,2^24]", (long long)rows);
     if (decay_q16 > 65536u) SWARM_REJECT(ctx, "coact_accumulate: decay_q16=%u above 65536", decay_q16);
     if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "coact_accumulate: C must be 16-byte aligned");
-    if (flags & ~SWARM_CHECK_IDX) SWARM_REJECT(ctx, "coact_accumulate: unknown flags 0x%x", flags);
+    if (flags & ~(SWARM_CHECK_IDX | SWARM_COACT_POPCOUNT)) SWARM_REJECT(ctx, "coact_accumulate: unknown flags 0x%x", flags);
 
     const int nruns = (int)((rows + 511) / 512 * 4);      // contraction in runs of 128 trace rows, zero-padded to a multiple of 4 runs
     const int Npad = (N + 255) / 256 * 256;               // entries, zero-padded to the C tile
@@ -202,6 +202,7 @@ swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t 
     if (st != SWARM_OK) return st;
     st = launch_trace_build(ctx, idx, rows, H, k, N, Npad, nruns, flags);
     if (st != SWARM_OK) return st;
+    if (flags & SWARM_COACT_POPCOUNT) return launch_coact_popcount(ctx, H, N, Npad, nruns, C, decay_q16);
     return launch_coact_syrk(ctx, H, N, Npad, nruns, C, decay_q16);
 }
 

@@ -345,6 +345,66 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     else emit(std::true_type{});
 }
 
+// The same counts without the matrix cores: C[i][j] = sum over the trace's 32-bit words of
+// popcount(bits_i & bits_j), on the plain vector ALUs (v_and + v_bcnt, which adds the popcount to
+// its accumulator).  A cross-check of the matrix-core path by an independent route, and its
+// competitor: a sixteenth of the LDS traffic per trace row, but 2 ALU operations per 32 products
+// where the matrix cores do 65536 per instruction.
+// Workgroup = 64 x 64 tile of C on or above the diagonal, thread = 4 x 4 outputs (rows ty + 16 i,
+// columns tx + 16 j), eight runs of 128 trace rows staged in LDS per pass.
+constexpr int PT = 64, PRUNS = 8;
+
+template <int MODE>
+__global__ __launch_bounds__(256) void coact_popcount_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns,
+                                                             int32_t* __restrict__ C, uint32_t decay_q16) {
+    __shared__ v4i sa[PRUNS][PT], sb[PRUNS][PT];
+    const int h = blockIdx.z, ti = blockIdx.y, tj = blockIdx.x;
+    if (tj < ti) return;
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const v4i* panel = bits + (size_t)h * nruns * Npad;
+    uint32_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0u;
+    for (int r0 = 0; r0 < nruns; r0 += PRUNS) {
+        __syncthreads();
+        for (int u = tid; u < PRUNS * PT; u += 256) {
+            const int r = r0 + u / PT, e = u % PT;
+            const v4i zero = {0, 0, 0, 0};
+            sa[u / PT][e] = r < nruns ? panel[(size_t)r * Npad + ti * PT + e] : zero;
+            sb[u / PT][e] = r < nruns ? panel[(size_t)r * Npad + tj * PT + e] : zero;
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int r = 0; r < PRUNS; ++r) {
+            v4i a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = sa[r][ty + 16 * i]; b[i] = sb[r][tx + 16 * i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] += __popc((uint32_t)(a[i].x & b[j].x)) + __popc((uint32_t)(a[i].y & b[j].y)) +
+                                 __popc((uint32_t)(a[i].z & b[j].z)) + __popc((uint32_t)(a[i].w & b[j].w));
+        }
+    }
+    int32_t* Ch = C + (size_t)h * N * N;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gi = ti * PT + ty + 16 * i, gj = tj * PT + tx + 16 * j;
+            if (gi >= N || gj >= N) continue;
+            const int32_t v = (int32_t)acc[i][j];
+            int32_t* p = Ch + (size_t)gi * N + gj;
+            int32_t* q = Ch + (size_t)gj * N + gi;
+            if (MODE == 0) { *p = v; if (ti != tj) *q = v; }
+            else if (MODE == 1) { *p += v; if (ti != tj) *q += v; }
+            else { *p = decayed(*p, decay_q16) + v; if (ti != tj) *q = decayed(*q, decay_q16) + v; }
+        }
+}
+
 }  // namespace
 
 swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
@@ -447,4 +507,18 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
                        reinterpret_cast<const v4i*>(ctx->trace), N, Npad, nruns, C, decay_q16, tph, tot, per_xcd,
                        static_cast<const int32_t*>(ctx->tile_order));
     return swarm_check_launch(ctx, "coact_syrk_kernel");
+}
+
+swarm_status launch_coact_popcount(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16) {
+    const unsigned nt = (unsigned)(Npad / PT);
+    if (nt > 65535u || H > 65535) {
+        snprintf(ctx->err, sizeof(ctx->err), "coact: N=%d, H=%d too large for the popcount route", N, H);
+        return SWARM_EINVAL;
+    }
+    const dim3 grid(nt, nt, (unsigned)H), block(256);
+    const v4i* bits = reinterpret_cast<const v4i*>(ctx->trace);
+    if (decay_q16 == 0u) hipLaunchKernelGGL(coact_popcount_kernel<0>, grid, block, 0, ctx->stream, bits, N, Npad, nruns, C, decay_q16);
+    else if (decay_q16 == 65536u) hipLaunchKernelGGL(coact_popcount_kernel<1>, grid, block, 0, ctx->stream, bits, N, Npad, nruns, C, decay_q16);
+    else hipLaunchKernelGGL(coact_popcount_kernel<2>, grid, block, 0, ctx->stream, bits, N, Npad, nruns, C, decay_q16);
+    return swarm_check_launch(ctx, "coact_popcount_kernel");
 }

@@ -59,6 +59,7 @@ swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, in
 swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
                                 int nruns, uint32_t flags);
 swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16);
+swarm_status launch_coact_popcount(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16);
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                         const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap);

@@ -99,6 +99,11 @@ def run_full(sw, cfg, sample_steps, rng):
         got = c[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()].cpu().numpy()
         want = np.array([int((member[int(a)] & member[int(b)]).sum()) for a, b in zip(ii, jj)])
         assert np.array_equal(got, want)
+    # the whole matrix once more by the independent route (AND + popcount on the bit trace), compared on the device
+    C2 = torch.empty_like(Cm)
+    sw.coact_accumulate(idx_all, N, C2, decay_q16=0, flags=2)
+    assert torch.equal(Cm, C2)
+    del C2
     if N <= 8192:
         # density pass over the C just built, against the oracle on the same matrix (Section 5.1, Steps 1-3)
         C_host = Cm.cpu().numpy()

@@ -166,19 +166,21 @@ COACT_CASES = [
 ]
 
 
+@pytest.mark.parametrize("route", [0, 2], ids=["matrix-cores", "popcount"])
 @pytest.mark.parametrize("rows,H,k,N", COACT_CASES)
-def test_coact_counts_bit_exact(sw, rows, H, k, N):
+def test_coact_counts_bit_exact(sw, rows, H, k, N, route):
+    """route 2 = SWARM_COACT_POPCOUNT: the same counts by AND + popcount on the bit trace."""
     sel = W.random_selections(rows, H, k, N, seed=rows + N)
     Cd = torch.full((H, N, N), -7, dtype=torch.int32, device="cuda")
-    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=0)                       # overwrite mode ignores old C
+    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=0, flags=route)          # overwrite mode ignores old C
     ref = oracle.coact_update(sel, N, nthreads=8)
     assert np.array_equal(Cd.cpu().numpy(), ref)
     # accumulate a second window, then a decayed third
     sel2 = W.random_selections(rows // 2 + 1, H, k, N, seed=99)
-    sw.coact_accumulate(dev(sel2), N, Cd, decay_q16=65536)
+    sw.coact_accumulate(dev(sel2), N, Cd, decay_q16=65536, flags=route)
     oracle.coact_update(sel2, N, ref, 65536, nthreads=8)
     assert np.array_equal(Cd.cpu().numpy(), ref)
-    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=64881)
+    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=64881, flags=route)
     oracle.coact_update(sel, N, ref, 64881, nthreads=8)
     assert np.array_equal(Cd.cpu().numpy(), ref)
     assert sw.device_status() == 0
