@@ -566,3 +566,42 @@ def test_host_side_argument_errors(sw):
     with pytest.raises(binding.SwarmError):
         sw.map_requests(sel[:, 0], 1, 64, e2c, 1, dev(np.zeros((1, 3), np.int32)), 2)      # R > D
     assert sw.device_status() == 0
+
+
+def test_host_side_argument_errors_of_the_widened_entry_points(sw):
+    from paper_2603_17803_amd import binding
+    cfg = W.CONFIGS["tiny"].scaled(N=64, k=8, T=1)
+    Kd = dev(W.keys(cfg))
+    qd = dev(W.queries(cfg, 0, 1)[0])
+    ids = dev(np.arange(16, dtype=np.int32)[None])
+    with pytest.raises(binding.SwarmError) as e:
+        sw.score_select_indexed("token", Kd, ids, qd, 17)                       # k > M
+    assert e.value.code == binding.SWARM_EINVAL
+    Cd = torch.zeros((1, 64, 64), dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.SwarmError):
+        sw.coact_density(Cd, 0.5, flags=4)                                      # unknown flag
+    sel = dev(W.random_selections(4, 1, 8, 64, seed=1))
+    with pytest.raises(binding.SwarmError):
+        sw.coact_accumulate(sel, 64, Cd, decay_q16=0, flags=8)                  # unknown flag
+    big_w = torch.zeros((2049, 1, 8), dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.SwarmError):
+        sw.window_assign(big_w, 64, ids, ids, 0.5)                              # window longer than 2048 steps
+    with pytest.raises(binding.SwarmError):
+        sw.window_assign(sel, 64, ids, ids, 0.5, primary=ids, size=ids, D=0)    # placement without SSDs
+    e2c = dev(np.zeros((1, 64), np.int32))
+    rep = dev(np.zeros((1, 3), np.int32))
+    with pytest.raises(binding.SwarmError):
+        sw.step("token", Kd, qd[0], 8, e2c, 1, rep, 2)                          # R > D
+    with pytest.raises(binding.SwarmError):
+        sw.step("token", Kd, qd[0], 65, e2c, 1, rep, 4)                         # k > N
+    assert sw.device_status() == 0
+
+
+def test_calibration_reports_plausible_rates(sw):
+    from paper_2603_17803_amd import binding
+    buf = torch.empty(1 << 28, dtype=torch.int32, device="cuda")                 # 1 GiB
+    rd = sw.calibrate(binding.SWARM_CAL_HBM_READ, buf, 3)
+    wr = sw.calibrate(binding.SWARM_CAL_HBM_WRITE, buf, 3)
+    mf = sw.calibrate(binding.SWARM_CAL_MFMA_I8, buf, 2)
+    assert 1000.0 < rd < 8000.0 and 1000.0 < wr < 8000.0                         # GB/s, below the nominal HBM peak
+    assert 1000.0 < mf < 5100.0                                                  # TOP/s, below the nominal int8 peak
