@@ -184,3 +184,41 @@ def test_drifting_batch_decayed_windows_scaled(sw):
         assert np.array_equal(Cd.cpu().numpy(), Cref)
     assert np.array_equal(Cref, np.transpose(Cref, (0, 2, 1)))
     assert sw.device_status() == 0
+
+
+def test_drifting_batch_full_size_window(sw):
+    """The drifting batch at its full shape (8 heads x 2048 pages, 64 streams x 4 query heads per KV head, k = 128):
+    one whole decay window of 256 steps (16384 trace rows) and a decayed second window of 64 steps.  Scores run on
+    the matrix-core scorer; sampled steps against the oracle, C of both windows against the oracle in full."""
+    cfg = W.CONFIGS["drift_batch"]
+    H, N, B, k = cfg.H, cfg.N, cfg.B, cfg.k
+    K = W.keys(cfg)
+    Kd = dev(K)
+    e2c, weight, rep = W.cluster_tables(cfg)
+    e2c_d, w_d, rep_d = dev(e2c), dev(weight), dev(rep)
+    Cd = torch.zeros((H, N, N), dtype=torch.int32, device="cuda")
+    Cref = np.zeros((H, N, N), np.int32)
+    t0 = 0
+    for steps, decay in ((cfg.decay_window, 65536), (64, cfg.decay_q16)):
+        qs = W.queries(cfg, t0, t0 + steps)
+        idx_win = torch.empty((steps * B, H, k), dtype=torch.int32, device="cuda")
+        for t in range(steps):
+            out_idx = idx_win[t * B:(t + 1) * B]
+            want = t in (0, steps // 2, steps - 1)
+            _, sc = sw.score_select("page", Kd, dev(qs[t]), k, G=cfg.G, out_idx=out_idx, want_scores=want)
+            sel = out_idx.permute(1, 0, 2).reshape(H, B * k).contiguous()          # the 64 streams of a step merged per head
+            got = sw.map_requests(sel, H, N, e2c_d, cfg.Nc, rep_d, cfg.D, w_d)
+            if want:
+                sc_h = sc.cpu().numpy()
+                _, ref64, ab = oracle.score("page", K, qs[t], G=cfg.G, nthreads=16)
+                tol = np.maximum(1e-3 * np.abs(ref64), 2 * cfg.d * cfg.G * 2.0 ** -24 * ab)
+                assert (np.abs(sc_h - ref64) <= tol).all()
+                assert np.array_equal(out_idx.cpu().numpy(), oracle.select(sc_h, k, nthreads=16))
+                ref = oracle.map_requests(sel.cpu().numpy(), H, N, e2c, cfg.Nc, rep, cfg.D, weight, nthreads=16)
+                for g_, r_ in zip(got, ref):
+                    assert np.array_equal(g_.cpu().numpy(), r_)
+        sw.coact_accumulate(idx_win, N, Cd, decay_q16=decay)
+        oracle.coact_update(idx_win.cpu().numpy(), N, Cref, decay, nthreads=16)
+        assert np.array_equal(Cd.cpu().numpy(), Cref)
+        t0 += steps
+    assert sw.device_status() == 0
