@@ -39,12 +39,24 @@ __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __rest
     const int64_t row0 = (int64_t)run * 128;
     const int nrows = (int)min((int64_t)128, rows - row0);                       // <= 0 for a run of pure padding
     bool bad = false;
-    for (int s = 0; s < nrows; ++s) {
-        const int32_t* sel = idx + ((row0 + s) * H + h) * (int64_t)k;
-        for (int j = threadIdx.x; j < k; j += blockDim.x) {
-            const int32_t e = sel[j];
-            if (e < 0 || e >= N) bad = true;
-            else if (e >= e0 && e < e0 + span) atomicOr(&words[(e - e0) * 4 + (s >> 5)], 1u << (s & 31));
+    // the run's nrows x k selected ids as one flat list: every thread busy, four independent loads in flight
+    const int total = nrows > 0 ? nrows * k : 0;
+    const int64_t row_stride = (int64_t)H * k;
+    const int32_t* sel0 = idx + (row0 * H + h) * (int64_t)k;
+    for (int i0 = threadIdx.x; i0 < total; i0 += 4 * blockDim.x) {
+        int32_t e[4];
+        int s[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * blockDim.x;
+            s[u] = i / k;
+            e[u] = i < total ? sel0[s[u] * row_stride + (i - s[u] * k)] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (i0 + u * (int)blockDim.x >= total) continue;
+            if (e[u] < 0 || e[u] >= N) bad = true;
+            else if (e[u] >= e0 && e[u] < e0 + span) atomicOr(&words[(e[u] - e0) * 4 + (s[u] >> 5)], 1u << (s[u] & 31));
         }
     }
     if (bad && blockIdx.z == 0) atomicOr(dev_flags, SWARM_DEV_BAD_ENTRY);
