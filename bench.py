@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=0, help="override T (0 = the workload's)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-coact", action="store_true",
+                    help="profiling aid: only the trace + C build of the workload, on seeded synthetic selections")
     ap.add_argument("--stage-reps", type=int, default=20, help="replays per stage-isolated timing (median and min reported)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -62,6 +64,10 @@ def main():
     def dev(a):
         a = np.ascontiguousarray(a)
         return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+
+    if args.only_coact:
+        only_coact(args, cfg, binding, W, torch, stream)
+        return
 
     t0 = time.time()
     K = W.keys(cfg)
@@ -262,6 +268,31 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, K, qs, e2c, weight, rep, np)
     print(json.dumps(out), flush=True)
+    sw.close()
+
+
+def only_coact(args, cfg, binding, W, torch, stream):
+    """The co-activation build alone (for counter runs: a handful of dispatches instead of a whole pass)."""
+    T, H, N, k = cfg.T, cfg.H, cfg.N, cfg.k
+    with torch.cuda.stream(stream):
+        idx = torch.from_numpy(W.random_selections(T, H, k, N, seed=cfg.seed)).cuda()
+        Cm = torch.zeros((H, N, N), dtype=torch.int32, device="cuda")
+    stream.synchronize()
+    sw = binding.Swarm(0, stream=stream)
+    for _ in range(max(args.warmup, 1)):
+        sw.coact_accumulate(idx, N, Cm, decay_q16=0)
+    stream.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        sw.coact_accumulate(idx, N, Cm, decay_q16=0)
+    e1.record(stream)
+    stream.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    tiles = (N + 255) // 256
+    issued = 2.0 * H * tiles * (tiles + 1) * 256 * 128 * ((T + 511) // 512 * 512)
+    print(json.dumps({"only": "coact", "workload": cfg.name, "ms_per_build_incl_trace": round(ms, 3), "issued_ops": issued,
+                      "TOPs": round(issued / (ms * 1e-3) / 1e12, 1), "frac_of_5_POPs": round(issued / (ms * 1e-3) / 5e15, 4)}), flush=True)
     sw.close()
 
 
