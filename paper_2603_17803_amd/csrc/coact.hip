@@ -429,15 +429,14 @@ swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows
     }
     const int span = Npad < TRACE_SPAN ? Npad : TRACE_SPAN;
     const size_t lds_bytes = (size_t)span * 16;
-    static bool lds_opt_in = false;
-    if (!lds_opt_in) {
+    if (!ctx->trace_lds_opt_in) {                          // per context: the attribute belongs to the device the context is bound to
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trace_build_kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, TRACE_SPAN * 16);
         if (e != hipSuccess) {
             snprintf(ctx->err, sizeof(ctx->err), "coact: cannot opt in to %d bytes of LDS: %s", TRACE_SPAN * 16, hipGetErrorString(e));
             return SWARM_EHIP;
         }
-        lds_opt_in = true;
+        ctx->trace_lds_opt_in = true;
     }
     const dim3 grid((unsigned)nruns, (unsigned)H, (unsigned)((Npad + TRACE_SPAN - 1) / TRACE_SPAN));
     hipLaunchKernelGGL(trace_build_kernel, grid, dim3(1024), lds_bytes, ctx->stream, idx, rows, H, k, N, Npad, nruns,
@@ -500,8 +499,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
     static const kernel_t kernels[3][2] = {{coact_syrk_kernel<0, false>, coact_syrk_kernel<0, true>},
                                            {coact_syrk_kernel<1, false>, coact_syrk_kernel<1, true>},
                                            {coact_syrk_kernel<2, false>, coact_syrk_kernel<2, true>}};
-    static bool lds_opt_in = false;
-    if (!lds_opt_in) {
+    if (!ctx->syrk_lds_opt_in) {
         for (int m = 0; m < 3; ++m)
             for (int v = 0; v < 2; ++v) {
                 const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[m][v]),
@@ -511,7 +509,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
                     return SWARM_EHIP;
                 }
             }
-        lds_opt_in = true;
+        ctx->syrk_lds_opt_in = true;
     }
     dim3 grid((unsigned)(per_xcd * 8)), block(256);
     const int tph = (int)tiles_per_head, tot = (int)total;

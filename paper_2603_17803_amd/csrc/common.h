@@ -26,6 +26,7 @@ struct swarm_ctx {
     size_t trace_bytes = 0;
     int64_t* totals = nullptr;     // per-head grand totals of C when the caller keeps none
     size_t totals_bytes = 0;
+    bool trace_lds_opt_in = false, syrk_lds_opt_in = false;   // large dynamic LDS enabled for this context's device
     uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
     int32_t* tile_order = nullptr; // co-activation tile schedule for tile_order_nt tiles per edge
     int tile_order_nt = 0;

@@ -432,9 +432,9 @@ swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int 
     return swarm_check_launch(ctx, "map_requests_kernel");
 }
 
-// Fused selection + mapping for one stream (groups = H, S = k).  Returns SWARM_OK after launching, or
-// SWARM_EINVAL *without touching ctx->err* when the shapes do not fit the fused kernel (the caller
-// then launches the two kernels separately).
+// Fused selection + mapping for one stream (groups = H, S = k).  *launched tells whether the shapes fit
+// the fused kernel; when they do not, nothing is enqueued and the caller launches the two kernels
+// separately.
 swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N, int k, int32_t* out_idx,
                                const int32_t* e2c, int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                                const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap,
