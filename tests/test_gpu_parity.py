@@ -605,3 +605,67 @@ def test_calibration_reports_plausible_rates(sw):
     mf = sw.calibrate(binding.SWARM_CAL_MFMA_I8, buf, 2)
     assert 1000.0 < rd < 8000.0 and 1000.0 < wr < 8000.0                         # GB/s, below the nominal HBM peak
     assert 1000.0 < mf < 5100.0                                                  # TOP/s, below the nominal int8 peak
+
+
+# --------------------------------------------------------------------------- seeded random sweeps over shapes
+
+def test_select_random_shapes_and_distributions(sw):
+    """Selection over many row lengths and k, on score distributions that stress the value binning: few distinct
+    values (massive ties), huge dynamic range, one outlier stretching the range, constant rows, infinities."""
+    rng = np.random.default_rng(2024)
+    for trial in range(48):
+        N = int(rng.choice([1, 2, 3, 63, 64, 65, 1000, 1023, 1025, 4096, 4097, 9000, 20000, 40000]))
+        k = int(rng.integers(1, N + 1)) if trial % 3 else min(N, int(rng.choice([1, 2, N // 2 + 1, N])))
+        kind = trial % 6
+        if kind == 0:
+            vals = rng.choice(np.array([-2.0, -0.0, 0.0, 1.5, 3.0], np.float32), N)
+        elif kind == 1:
+            vals = (rng.standard_normal(N) * 10.0 ** rng.integers(-30, 30, N)).astype(np.float32)
+        elif kind == 2:
+            vals = rng.standard_normal(N).astype(np.float32)
+            vals[int(rng.integers(0, N))] = 3.0e38
+        elif kind == 3:
+            vals = np.full(N, float(rng.standard_normal()), np.float32)
+        elif kind == 4:
+            vals = rng.standard_normal(N).astype(np.float32)
+            vals[rng.integers(0, N, max(1, N // 50))] = rng.choice(np.array([np.inf, -np.inf, np.nan], np.float32), max(1, N // 50))
+        else:
+            vals = np.round(rng.standard_normal(N) * 4).astype(np.float32)
+        vals = W.bf16_to_f32(W.f32_to_bf16(vals))
+        Kd, qd = crafted_scores(sw, vals)
+        idx, sc = sw.score_select("token", Kd, qd, k, want_scores=True)
+        sc_h = sc.cpu().numpy()[0]
+        assert idx.cpu().numpy()[0, 0].tolist() == oracle.select(sc_h, k)[0].tolist(), (trial, N, k, kind)
+    assert sw.device_status() == 0
+
+
+def test_coact_and_map_random_shapes(sw):
+    rng = np.random.default_rng(77)
+    for trial in range(24):
+        H = int(rng.integers(1, 4))
+        N = int(rng.choice([5, 64, 100, 255, 256, 257, 513, 777, 1200]))
+        k = int(rng.integers(1, min(N, 96) + 1))
+        rows = int(rng.choice([1, 2, 63, 64, 65, 127, 128, 129, 511, 513, 900]))
+        sel = W.random_selections(rows, H, k, N, seed=1000 + trial, topic_like=bool(trial % 2))
+        ref = None
+        Cd = torch.zeros((H, N, N), dtype=torch.int32, device="cuda")
+        for w, decay in enumerate((0, 65536, int(rng.integers(1, 65536)))):
+            sw.coact_accumulate(dev(sel), N, Cd, decay_q16=decay, flags=2 * (trial % 2))
+            ref = oracle.coact_update(sel, N, ref, decay, nthreads=8) if ref is not None else oracle.coact_update(sel, N, nthreads=8)
+            assert np.array_equal(Cd.cpu().numpy(), ref), (trial, H, N, k, rows, decay)
+        # mapping of the same selections: clusters of random size, random replica rows with holes
+        Nc = int(rng.integers(1, min(N, 300) + 1))
+        D = int(rng.integers(1, 65))
+        R = int(rng.integers(1, min(D, 5) + 1))
+        e2c = rng.integers(0, Nc, (H, N)).astype(np.int32)
+        rep = np.full((H * Nc, R), -1, np.int32)
+        for c in range(H * Nc):
+            r = int(rng.integers(1, R + 1))
+            rep[c, rng.choice(R, r, replace=False)] = rng.choice(D, r, replace=False)
+        weight = rng.integers(0, 1000, H * Nc).astype(np.int32) if trial % 3 else None
+        groups = sel[: min(rows, 6)].reshape(-1, k)[: (min(rows, 6) * H // H) * H]
+        out = sw.map_requests(dev(groups), H, N, dev(e2c), Nc, dev(rep), D, None if weight is None else dev(weight))
+        want = oracle.map_requests(groups, H, N, e2c, Nc, rep, D, weight, nthreads=8)
+        for g_, r_ in zip(out, want):
+            assert np.array_equal(g_.cpu().numpy(), r_), (trial, H, N, k, Nc, D, R)
+    assert sw.device_status() == 0
