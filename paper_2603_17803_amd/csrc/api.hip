@@ -74,6 +74,7 @@ swarm_status swarm_destroy(swarm_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->scores) (void)hipFree(ctx->scores);
     if (ctx->trace) (void)hipFree(ctx->trace);
+    if (ctx->cand) (void)hipFree(ctx->cand);
     if (ctx->totals) (void)hipFree(ctx->totals);
     if (ctx->weights) (void)hipFree(ctx->weights);
     if (ctx->tile_order) (void)hipFree(ctx->tile_order);

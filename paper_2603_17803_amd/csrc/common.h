@@ -19,6 +19,8 @@ struct swarm_ctx {
 
     // scratch, grown on demand
     float* scores = nullptr;       // [B][H][N] when the caller passes no score buffer
+    int32_t* cand = nullptr;       // winners of the slices of long rows (two-stage selection)
+    size_t cand_bytes = 0;
     size_t scores_bytes = 0;
     uint16_t* weights = nullptr;   // folded query weights of the batched scorer: bf16 hi then lo, each [B][H][L]
     size_t weights_bytes = 0;
@@ -57,6 +59,7 @@ constexpr int SWARM_BATCHED_MIN_STREAMS = 8;   // from this many streams on, sco
 swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores,
                           const int32_t* row_ids = nullptr, int M = 0);
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx);
+bool select_uses_slices(int64_t rows, int N, int k);   // long rows, few of them: sliced two-stage selection
 swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
                                 int nruns, uint32_t flags);
 swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16);

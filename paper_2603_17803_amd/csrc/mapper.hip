@@ -440,7 +440,7 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
                                const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap,
                                bool* launched) {
     *launched = false;
-    if (N > 64 * selcore::NT) return SWARM_OK;
+    if (N > 64 * selcore::NT || select_uses_slices(H, N, k)) return SWARM_OK;   // long rows: the sliced selection is faster than fusing
     constexpr int NT = selcore::NT;
     MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags};
     size_t lds = map_lds_base_bytes(Nc, cap);

@@ -19,6 +19,47 @@ __global__ __launch_bounds__(selcore::NT) void topk_select_kernel(const float* _
     selcore::block_select<IPT>(key, N, k, out_idx + (size_t)blockIdx.x * k, sm);
 }
 
+// ---- long rows, few of them: two stages -----------------------------------------------------------
+// A single workgroup selecting a 65536-entry row spends tens of microseconds on it.  When there are too
+// few rows to fill the device, a row is cut into slices of SLICE entries: every slice keeps its own
+// top-min(k, slice length) (exactly, with the same tie-break), and one workgroup per row then selects
+// among the slices' winners.  An entry dropped by its slice is beaten by that many entries of the same
+// slice, each with a higher score or an equal score and a lower index, so it cannot belong to the
+// row's result; the winners are listed in ascending entry id, so position order is index order and
+// the lowest-index tie-break carries over.
+constexpr int SLICE = 8192, SLICE_IPT = 8;
+
+__global__ __launch_bounds__(selcore::NT) void topk_slice_kernel(const float* __restrict__ scores, int N, int k,
+                                                                 int32_t* __restrict__ cand, int cand_stride) {
+    __shared__ selcore::Smem sm;
+    const int p = blockIdx.x;
+    const int64_t row = blockIdx.y;
+    const int lo = p * SLICE, len = min(SLICE, N - lo);
+    const int kk = min(k, len);
+    uint32_t key[SLICE_IPT];
+    selcore::load_keys<SLICE_IPT>(scores + row * N + lo, len, key);
+    // slices before this one are full, so their winner counts are min(k, SLICE) each
+    selcore::block_select<SLICE_IPT>(key, len, kk, cand + row * cand_stride + (size_t)p * min(k, SLICE), sm, lo);
+}
+
+template <int IPT>
+__global__ __launch_bounds__(selcore::NT) void topk_merge_kernel(const float* __restrict__ scores, int N, int k,
+                                                                 const int32_t* __restrict__ cand, int cand_stride, int M,
+                                                                 int32_t* __restrict__ out_idx) {
+    __shared__ selcore::Smem sm;
+    const int64_t row = blockIdx.x;
+    const int32_t* c = cand + row * cand_stride;
+    const float* s = scores + row * N;
+    uint32_t key[IPT];
+    const int base = threadIdx.x * IPT;
+#pragma unroll
+    for (int e = 0; e < IPT; ++e) key[e] = (base + e < M) ? order_key(s[c[base + e]]) : 0u;
+    int32_t* out = out_idx + row * k;
+    selcore::block_select<IPT>(key, M, k, out, sm);      // positions in the winners' list, ascending
+    __syncthreads();
+    for (int j = threadIdx.x; j < k; j += selcore::NT) out[j] = c[out[j]];
+}
+
 constexpr int SEL_THREADS = 1024;
 
 // Streaming fallback for rows longer than 65536 entries.
@@ -102,9 +143,34 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_select_stream_kernel(const f
 
 }  // namespace
 
+bool select_uses_slices(int64_t rows, int N, int k) {
+    if (N <= 2 * SLICE || rows > 32) return false;
+    const int64_t P = (N + SLICE - 1) / SLICE;
+    const int64_t M = (P - 1) * (k < SLICE ? k : SLICE) + (k < N - (P - 1) * SLICE ? k : N - (P - 1) * SLICE);
+    return M <= N / 2 && M <= 64 * selcore::NT;
+}
+
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx) {
     const dim3 grid((unsigned)rows), block(selcore::NT);
     hipStream_t st = ctx->stream;
+    if (select_uses_slices(rows, N, k)) {
+        const int P = (N + SLICE - 1) / SLICE;
+        const int per = k < SLICE ? k : SLICE;
+        const int last = N - (P - 1) * SLICE;
+        const int M = (P - 1) * per + (k < last ? k : last);
+        const int stride = P * per;
+        swarm_status rc = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->cand), &ctx->cand_bytes, sizeof(int32_t) * (size_t)rows * stride);
+        if (rc != SWARM_OK) return rc;
+        hipLaunchKernelGGL(topk_slice_kernel, dim3((unsigned)P, (unsigned)rows), block, 0, st, scores, N, k, ctx->cand, stride);
+        rc = swarm_check_launch(ctx, "topk_slice_kernel");
+        if (rc != SWARM_OK) return rc;
+        if (M <= 4 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<4>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
+        else if (M <= 8 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<8>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
+        else if (M <= 16 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<16>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
+        else if (M <= 32 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<32>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
+        else hipLaunchKernelGGL(topk_merge_kernel<64>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
+        return swarm_check_launch(ctx, "topk_merge_kernel");
+    }
     if (N <= 4 * selcore::NT) hipLaunchKernelGGL(topk_select_kernel<4>, grid, block, 0, st, scores, N, k, out_idx);
     else if (N <= 8 * selcore::NT) hipLaunchKernelGGL(topk_select_kernel<8>, grid, block, 0, st, scores, N, k, out_idx);
     else if (N <= 16 * selcore::NT) hipLaunchKernelGGL(topk_select_kernel<16>, grid, block, 0, st, scores, N, k, out_idx);

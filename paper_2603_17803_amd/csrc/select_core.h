@@ -83,9 +83,10 @@ __device__ __forceinline__ void block_excl_scan2(uint32_t a, uint32_t b, uint32_
 
 // key[e] is the key of index tid*IPT + e; slots at or beyond N must hold key 0.
 // All NT threads of the block must call this.  out receives k ascending indices.
+// index_offset is added to every emitted index (a block selecting inside a slice of a longer row).
 template <int IPT>
 __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, int k, int32_t* __restrict__ out,
-                                             Smem& sm) {
+                                             Smem& sm, int index_offset = 0) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int base = tid * IPT;
 
@@ -208,7 +209,7 @@ __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, 
         const bool take = (b < bstar) || (b == bstar && key[e] > T) || (is_eq && eq_seen < need_eq);
         eq_seen += is_eq;
         if (take) {
-            if (pos < (uint32_t)k) out[pos] = base + e;     // pos < k always holds; the guard keeps a slip in bounds
+            if (pos < (uint32_t)k) out[pos] = index_offset + base + e;     // pos < k always holds; the guard keeps a slip in bounds
             ++pos;
         }
     }

@@ -138,8 +138,29 @@ def test_token_stress_full_size(sw):
     run_full(sw, cfg, rng.choice(cfg.T, 3, replace=False), rng)
 
 
+def test_select_long_rows_sliced_and_streaming(sw):
+    """Few long rows are selected in two stages (slices, then their winners); many rows of more than 65536
+    entries take the streaming kernel.  Both against the oracle on the device's own scores."""
+    for B, N, k in ((1, 65536, 1024), (2, 40000, 700), (1, 200000, 300), (40, 66000, 50)):
+        cfg = W.CONFIGS["tiny"].scaled(N=N, k=k, T=1, d=8, B=B)
+        K = W.keys(cfg)
+        q = W.queries(cfg, 0, 1)[0]
+        idx, sc = sw.score_select("token", dev(K), dev(q), k, want_scores=True)
+        sc = sc.cpu().numpy()
+        assert np.array_equal(idx.cpu().numpy(), oracle.select(sc, k, nthreads=8)), (B, N, k)
+    # heavy ties across slices: the lowest indices win
+    vals = np.zeros(50000, np.float32)
+    vals[::7] = 1.0
+    cfg = W.CONFIGS["tiny"].scaled(N=50000, k=9000, T=1, d=8)
+    K = np.full((1, 50000, 8), 0x8000, np.uint16)
+    K[0, :, 0] = (vals.view(np.uint32) >> 16).astype(np.uint16)
+    qd = dev(np.full((1, 1, 8), 0x3F80, np.uint16))
+    idx, sc = sw.score_select("token", dev(K), qd, 9000, want_scores=True)
+    assert np.array_equal(idx.cpu().numpy(), oracle.select(sc.cpu().numpy(), 9000))
+
+
 def test_select_rows_longer_than_the_register_path(sw):
-    """More than 65536 entries per row takes the streaming select kernel."""
+    """More than 65536 entries in a single row (sliced selection)."""
     cfg = W.CONFIGS["tiny"].scaled(N=70000, k=300, T=1, d=8)
     K = W.keys(cfg)
     q = W.queries(cfg, 0, 1)[0]
