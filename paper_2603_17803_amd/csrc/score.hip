@@ -232,13 +232,26 @@ __global__ __launch_bounds__(256) void score_batched_kernel(const u32x4* __restr
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
+    // The weights of a 32-stream tile (hi and lo halves, CH 16-byte chunks per stream) are the same for the
+    // four waves: they are staged in LDS with coalesced loads, one tile at a time, instead of every wave
+    // gathering them from the L2 in 16-byte pieces.  Rows are padded by one chunk so that the 16 lanes a
+    // 16-byte LDS read serves together (16 streams, same chunk) fall into 16 different bank groups.
+    constexpr int WROW = CH + 1;
+    __shared__ u32x4 wtile[2][32 * WROW];
     const int ntiles = min(SB_TILES, (B - b0 + 31) / 32);
 #pragma unroll
     for (int t = 0; t < SB_TILES; ++t) {
         if (t < ntiles) {
-            const int b = min(b0 + t * 32 + r32, B - 1);
-            const u32x4* wh = whi + ((size_t)b * H + h) * CH + hf * KSTEPS;
-            const u32x4* wl = wlo + ((size_t)b * H + h) * CH + hf * KSTEPS;
+            __syncthreads();
+            for (int u = threadIdx.x; u < 32 * CH; u += 256) {
+                const int sb = u / CH, c = u % CH;
+                const int b = min(b0 + t * 32 + sb, B - 1);
+                wtile[0][sb * WROW + c] = whi[((size_t)b * H + h) * CH + c];
+                wtile[1][sb * WROW + c] = wlo[((size_t)b * H + h) * CH + c];
+            }
+            __syncthreads();
+            const u32x4* wh = &wtile[0][r32 * WROW + hf * KSTEPS];
+            const u32x4* wl = &wtile[1][r32 * WROW + hf * KSTEPS];
 #pragma unroll
             for (int s = 0; s < KSTEPS; ++s) {
                 const u32x4 bh_ = wh[s], bl_ = wl[s];
