@@ -7,6 +7,9 @@
  *  -> record the selection as one row of a binary activation trace
  *  -> count how often two entries are activated together, C = A^T A       (Section 5.1, Step 1)
  *  -> turn the step's selection into per-SSD request queues               (Section 6.1)
+ * and, around that path: the density pass over C that starts the clustering (Section 5.1, Steps 1-3),
+ * cluster maintenance over the local window (Section 6.2), and retrieval through the medoid index
+ * (Section 5.2 Tier 1, Section 6.1).
  *
  * Conventions that hold for every call below:
  *  - Every data pointer is a DEVICE pointer owned by the caller.  The library never frees,
