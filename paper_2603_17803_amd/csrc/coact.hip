@@ -2,8 +2,8 @@
 // rows in which entries i and j are both activated, i.e. C = A^T A for the binary trace A.
 //
 // The trace is binary, so it is kept in memory as bits: for every head and every run of 128 trace
-// rows one 16-byte word per entry, bits[h][run][entry], bit s = "entry activated in trace row
-// 128*run + s".  Both operands of the product are entry panels of this one array.  On the way
+// rows one 16-byte word per entry, bits[h][run][entry], one bit per trace row of the run (rows 32w ..
+// 32w+31 in dword w, in the order of trace_bit below).  Both operands of the product are entry panels of this one array.  On the way
 // to the matrix cores a workgroup expands the bits of its two entry panels to int8 0/1 rows in
 // LDS (contraction index contiguous), and the product runs on v_mfma_i32_32x32x32_i8 with exact
 // int32 accumulation.  Feeding int8 from memory instead would make every workgroup pull
@@ -21,6 +21,12 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Position, inside its 32-bit word, of the bit of trace row r (0..31) of the word's group: row 4q + b is
+// bit 8b + q, i.e. four consecutive rows are the same bit of the four bytes.  Any fixed order serves the
+// counts (both operands of a product, and both sides of an AND + popcount, use the same one); this one
+// makes the expansion to bytes a shift and a mask.
+__device__ __forceinline__ int trace_bit(int r) { return 8 * (r & 3) + (r >> 2); }
 
 constexpr int TRACE_SPAN = 8192;   // entries one trace-building workgroup covers (128 KiB of LDS)
 
@@ -56,7 +62,7 @@ __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __rest
         for (int u = 0; u < 4; ++u) {
             if (i0 + u * (int)blockDim.x >= total) continue;
             if (e[u] < 0 || e[u] >= N) bad = true;
-            else if (e[u] >= e0 && e[u] < e0 + span) atomicOr(&words[(e[u] - e0) * 4 + (s[u] >> 5)], 1u << (s[u] & 31));
+            else if (e[u] >= e0 && e[u] < e0 + span) atomicOr(&words[(e[u] - e0) * 4 + (s[u] >> 5)], 1u << trace_bit(s[u] & 31));
         }
     }
     if (bad && blockIdx.z == 0) atomicOr(dev_flags, SWARM_DEV_BAD_ENTRY);
@@ -103,8 +109,9 @@ static_assert(SYRK_LDS_BYTES >= 2 * BUF_BYTES, "operand ring must fit");
 __device__ __forceinline__ int lds_swz(int row) { return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1); }
 __device__ __forceinline__ int lds_off(int row, int piece) { return row * KC + ((piece ^ lds_swz(row)) << 4); }
 
-// Expansion of trace bits to bytes of 0/1, four at a time: a nibble times (1 + 2^7 + 2^14 + 2^21) puts
-// bit b at bit 8b (the four shifted copies do not overlap, so nothing carries); a mask drops the rest.
+// Expansion of trace bits to bytes of 0/1: the rows of a 32-row group sit in their word so that the four
+// consecutive rows of an output dword are the same bit of the word's four bytes (trace_bit above), and
+// (w >> j) & 0x01010101 is the whole expansion of four rows.
 
 // C tile of 256 x 128 per workgroup of 4 waves (2 x 2, each 128 x 64 = 4 x 2 MFMA tiles, 128
 // accumulator registers), two workgroups per compute unit: while one waits at its hand-over barrier,
@@ -162,7 +169,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     };
     auto expand_quarter = [&](int set, int half, int piece, int q) __attribute__((always_inline)) {
         const uint32_t w = piece < 4 ? (uint32_t)ba[set][2 * half + (piece >> 1)] : bw;
-        ex[q] = (int)(__umul24(__builtin_amdgcn_ubfe(w, 16 * (piece & 1) + 4 * q, 4), 0x00204081u) & 0x01010101u);
+        ex[q] = (int)((w >> (4 * (piece & 1) + q)) & 0x01010101u);
     };
     auto store_piece = [&](int buf, int piece) __attribute__((always_inline)) {
         *reinterpret_cast<v4i*>(lds + buf * BUF_BYTES + st_off[piece]) = ex;
