@@ -224,20 +224,24 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     // (d+3)%4 is refilled at the start of the run, three runs (6 chunks) ahead of its use.  The work is
     // laid out as 16 slots, one per MFMA: slot m issues the MFMA, then a
     // fragment read for the second k-step (first six slots), then its share of the expansion (24 dwords
-    // of 3 operations and 6 LDS stores per chunk, spread over the first 12 slots).  The hand-over
-    // barrier sits 4 MFMAs before the end of the chunk; those and the other workgroup on the compute
-    // unit cover the LDS latency of the next chunk's first fragments.
+    // of 2 operations and 6 LDS stores per chunk, spread over the first 8 slots).  The hand-over
+    // barrier sits after the first k-step (it cannot sit earlier: the reads that follow it refill the
+    // first k-step's fragment registers); the second k-step's MFMAs and the other workgroup on the
+    // compute unit cover the LDS latency of the next chunk's first fragments.  (Measured 2% faster
+    // than a barrier 4 MFMAs before the end of the chunk.)
     auto chunk_body = [&](int d, int half, int set) __attribute__((always_inline)) {   // set = d % 4; half and set passed as literals
         const int buf = half, nbuf = half ^ 1;
         const int nset = half ? (set + 1) & 3 : set, nhalf = half ^ 1, lset = (set + 3) & 3;
         pick_b(nset, nhalf);
+        constexpr int BAR = 8;                               // MFMA slots before the hand-over barrier: the whole first k-step,
+        static_assert(BAR >= 8 && 24 % BAR == 0, "");          // whose fragment set the reads after the barrier overwrite
 #pragma unroll
-        for (int s = 0; s < 12; ++s) {
+        for (int s = 0; s < BAR; ++s) {
             mfma(s >> 3, s & 7);
             if (s < 6) read_frag(buf, 1, 1, s);
             if (half == 0 && s == 0) load_bits(lset, d + 3);
 #pragma unroll
-            for (int u = 2 * s; u < 2 * s + 2; ++u) {
+            for (int u = (24 / BAR) * s; u < (24 / BAR) * (s + 1); ++u) {
                 expand_quarter(nset, nhalf, u >> 2, u & 3);
                 if ((u & 3) == 3) store_piece(nbuf, u >> 2);
             }
@@ -247,7 +251,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
         for (int f = 0; f < 6; ++f) read_frag(nbuf, 0, 0, f);          // after the last chunk this reads stale but valid LDS and is never used
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int m = 4; m < 8; ++m) mfma(1, m);
+        for (int s = BAR; s < 16; ++s) mfma(s >> 3, s & 7);
     };
     for (int d = 0; d < nruns; d += 4) {                    // nruns is a multiple of 4
         chunk_body(d, 0, 0);
