@@ -253,6 +253,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
 #pragma unroll
         for (int s = BAR; s < 16; ++s) mfma(s >> 3, s & 7);
     };
+    __builtin_amdgcn_s_setprio(2);                          // the contraction outranks the other workgroup's epilogue stores
     for (int d = 0; d < nruns; d += 4) {                    // nruns is a multiple of 4
         chunk_body(d, 0, 0);
         chunk_body(d, 1, 0);
@@ -264,6 +265,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
         chunk_body(d + 3, 1, 3);
     }
 
+    __builtin_amdgcn_s_setprio(0);
     // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4.  One
     // register of a wave is therefore two whole 128-byte lines of the direct tile (32 consecutive
     // columns of two rows): the direct tile leaves straight from the accumulators in 4-byte stores,
