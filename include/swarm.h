@@ -23,6 +23,8 @@
  *    arguments give SWARM_EINVAL before anything is enqueued.  Bad *data* (an index outside
  *    its range) never makes a kernel read or write out of bounds: the offending item is
  *    skipped and a sticky flag is raised that swarm_device_status() reports.
+ *  - A context belongs to the device it was created on; that device must be the calling thread's
+ *    current device for every call (SWARM_EINVAL otherwise).  swarm_create makes it current.
  *  - One context per stream; a context is not thread-safe.  bf16 is the upper half of an IEEE
  *    binary32.  All integer arrays are int32 unless stated.
  */
@@ -104,7 +106,7 @@ swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags);
  * out_idx     device, int32 [B][H][k].
  * out_scores  device, fp32 [B][H][N], or NULL to keep the scores in the context's scratch.
  * Errors: SWARM_EINVAL for a NULL required pointer, misaligned data/q, k outside [1,N], d not a
- * multiple of 8 or above 512, H/N/G/B < 1.
+ * multiple of 8 or above 512, H/N/G/B < 1, N > 2^30, H > 65535, B*H > 2^24.
  */
 swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, int32_t k,
                                 int32_t* out_idx, float* out_scores);
@@ -132,6 +134,7 @@ swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, 
  * idx    device, int32 [rows][H][k]; within one (row, head) the k entries must be distinct and in
  *        [0,N) (any order).  Out-of-range entries are skipped and flagged.
  * rows   trace rows in this call (steps x streams since the last call), 1 <= rows <= 2^24.
+ * H, N   1 <= H <= 65535, 1 <= N <= 2^20.
  * C      device, int32 [H][N][N] row-major, in/out, 16-byte aligned.
  * flags  SWARM_CHECK_IDX additionally flags repeated entries (SWARM_DEV_DUP_ENTRY); a repeated
  *        entry counts once either way, because the trace is binary.  SWARM_COACT_POPCOUNT computes the

@@ -54,7 +54,10 @@ swarm_status swarm_create(swarm_ctx** out, int device, void* hip_stream) {
         return SWARM_EINVAL;
     }
     swarm_ctx* ctx = new (std::nothrow) swarm_ctx();
-    if (!ctx) return SWARM_ENOMEM;
+    if (!ctx) {
+        snprintf(g_create_err, sizeof g_create_err, "out of host memory");
+        return SWARM_ENOMEM;
+    }
     ctx->device = device;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     e = hipMalloc(reinterpret_cast<void**>(&ctx->dev_flags), 256);
@@ -86,7 +89,7 @@ swarm_status swarm_destroy(swarm_ctx* ctx) {
 const char* swarm_last_error(const swarm_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
 
 swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     if (ctx->capturing) SWARM_REJECT(ctx, "device_status: not while recording");
     uint32_t host = 0;
     SWARM_HIP(ctx, hipMemcpyAsync(&host, ctx->dev_flags, sizeof host, hipMemcpyDeviceToHost, ctx->stream));
@@ -114,11 +117,12 @@ static swarm_status check_score_args(swarm_ctx* ctx, const char* fn, const swarm
     if ((reinterpret_cast<uintptr_t>(keys->data) & 15) || (reinterpret_cast<uintptr_t>(q) & 15))
         SWARM_REJECT(ctx, "%s: keys.data and q must be 16-byte aligned", fn);
     if ((int64_t)B * keys->H > (int64_t)1 << 24) SWARM_REJECT(ctx, "%s: B*H too large", fn);
+    if (keys->N > (1 << 30) || keys->H > 65535) SWARM_REJECT(ctx, "%s: N=%d above 2^30 or H=%d above 65535", fn, keys->N, keys->H);
     return SWARM_OK;
 }
 
 swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, float* out_scores) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     swarm_status st = check_score_args(ctx, "score", keys, q, B);
     if (st != SWARM_OK) return st;
     if (!out_scores || (reinterpret_cast<uintptr_t>(out_scores) & 3)) SWARM_REJECT(ctx, "score: NULL or misaligned out_scores");
@@ -127,7 +131,7 @@ swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, 
 
 swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, int32_t k,
                                 int32_t* out_idx, float* out_scores) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     swarm_status st = check_score_args(ctx, "score_select", keys, q, B);
     if (st != SWARM_OK) return st;
     if (!out_idx) SWARM_REJECT(ctx, "score_select: NULL out_idx");
@@ -148,7 +152,7 @@ swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const vo
 
 swarm_status swarm_score_select_indexed(swarm_ctx* ctx, const swarm_keys* keys, const int32_t* row_ids, int32_t M, const void* q,
                                         int32_t B, int32_t k, int32_t* out_idx, float* out_scores) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     swarm_status st = check_score_args(ctx, "score_select_indexed", keys, q, B);
     if (st != SWARM_OK) return st;
     if (!row_ids || !out_idx) SWARM_REJECT(ctx, "score_select_indexed: NULL row_ids or out_idx");
@@ -169,7 +173,7 @@ swarm_status swarm_score_select_indexed(swarm_ctx* ctx, const swarm_keys* keys, 
 swarm_status swarm_expand_clusters(swarm_ctx* ctx, const int32_t* clusters, int64_t groups, int32_t Sc, int32_t H, int32_t Nc,
                                    const int32_t* cl_off, const int32_t* cl_entries, int32_t E, int32_t* entries, int32_t* count,
                                    int32_t cap_e) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     if (!clusters || !cl_off || !cl_entries || !entries || !count) SWARM_REJECT(ctx, "expand_clusters: NULL required pointer");
     if (groups < 1 || groups > ((int64_t)1 << 30) || Sc < 1 || H < 1 || Nc < 1 || E < 1 || cap_e < 1)
         SWARM_REJECT(ctx, "expand_clusters: groups=%lld Sc=%d H=%d Nc=%d E=%d cap_e=%d must all be >= 1", (long long)groups, Sc,
@@ -180,7 +184,7 @@ swarm_status swarm_expand_clusters(swarm_ctx* ctx, const int32_t* clusters, int6
 
 swarm_status swarm_submission_order(swarm_ctx* ctx, const int32_t* q_off, const int32_t* q_cluster, int64_t groups, int32_t D,
                                     int32_t cap, int32_t* order, int32_t* batch_off, int32_t* nb) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     if (!q_off || !q_cluster || !order || !batch_off || !nb) SWARM_REJECT(ctx, "submission_order: NULL required pointer");
     if (groups < 1 || groups > ((int64_t)1 << 30) || D < 1 || D > 64 || cap < 1)
         SWARM_REJECT(ctx, "submission_order: groups=%lld D=%d cap=%d out of range", (long long)groups, D, cap);
@@ -189,11 +193,14 @@ swarm_status swarm_submission_order(swarm_ctx* ctx, const int32_t* q_off, const 
 
 swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int32_t H, int32_t k,
                                     int32_t N, int32_t* C, uint32_t decay_q16, uint32_t flags) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     if (!idx || !C) SWARM_REJECT(ctx, "coact_accumulate: NULL idx or C");
     if (H < 1 || N < 1 || k < 1 || k > N) SWARM_REJECT(ctx, "coact_accumulate: H=%d N=%d k=%d invalid", H, N, k);
+    if (N > (1 << 20) || H > 65535) SWARM_REJECT(ctx, "coact_accumulate: N=%d above 2^20 or H=%d above 65535", N, H);
     if (rows < 1 || rows > ((int64_t)1 << 24)) SWARM_REJECT(ctx, "coact_accumulate: rows=%lld outside [1,2^24]", (long long)rows);
     if (decay_q16 > 65536u) SWARM_REJECT(ctx, "coact_accumulate: decay_q16=%u above 65536", decay_q16);
+    if ((flags & SWARM_CHECK_IDX) && rows * H > ((int64_t)1 << 30))
+        SWARM_REJECT(ctx, "coact_accumulate: SWARM_CHECK_IDX handles at most 2^30 (row, head) selections per call");
     if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "coact_accumulate: C must be 16-byte aligned");
     if (flags & ~(SWARM_CHECK_IDX | SWARM_COACT_POPCOUNT)) SWARM_REJECT(ctx, "coact_accumulate: unknown flags 0x%x", flags);
 
@@ -209,9 +216,10 @@ swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t 
 
 swarm_status swarm_coact_density(swarm_ctx* ctx, const int32_t* C, int32_t H, int32_t N, const int64_t* totals_in,
                                  double tau, uint32_t flags, int32_t* rho, int32_t* queue, int64_t* totals_out) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     if (!C || !rho) SWARM_REJECT(ctx, "coact_density: NULL C or rho");
     if (H < 1 || N < 1) SWARM_REJECT(ctx, "coact_density: H=%d N=%d must be >= 1", H, N);
+    if (N > (1 << 20) || H > 65535) SWARM_REJECT(ctx, "coact_density: N=%d above 2^20 or H=%d above 65535", N, H);
     if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "coact_density: C must be 16-byte aligned");
     if (flags & ~(SWARM_RHO_EXCLUDE_SELF | SWARM_RHO_STRICT)) SWARM_REJECT(ctx, "coact_density: unknown flags 0x%x", flags);
     if ((totals_in && (reinterpret_cast<uintptr_t>(totals_in) & 7)) || (totals_out && (reinterpret_cast<uintptr_t>(totals_out) & 7)))
@@ -229,11 +237,12 @@ swarm_status swarm_window_assign(swarm_ctx* ctx, const int32_t* sel, int32_t W, 
                                  const int32_t* new_ids, int32_t n_new, const int32_t* medoids, int32_t Nc, double tau,
                                  const int32_t* primary, const int32_t* size, int32_t D, int32_t* f_out, uint8_t* member,
                                  int32_t* disk) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     if (!sel || !new_ids || !medoids || !member) SWARM_REJECT(ctx, "window_assign: NULL required pointer");
     if (W < 1 || W > 2048) SWARM_REJECT(ctx, "window_assign: W=%d outside [1,2048]", W);
     if (H < 1 || N < 1 || k < 1 || k > N || n_new < 1 || Nc < 1)
         SWARM_REJECT(ctx, "window_assign: H=%d N=%d k=%d n_new=%d Nc=%d invalid", H, N, k, n_new, Nc);
+    if (N > (1 << 24) || H > 65535) SWARM_REJECT(ctx, "window_assign: N=%d above 2^24 or H=%d above 65535", N, H);
     if ((primary == nullptr) != (size == nullptr)) SWARM_REJECT(ctx, "window_assign: primary and size go together");
     if (disk && (!primary || D < 1)) SWARM_REJECT(ctx, "window_assign: disk needs primary, size and D >= 1");
     const int nruns = (W + 127) / 128;
@@ -264,7 +273,7 @@ swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t grou
                                 const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
                                 const int32_t* weight, const uint32_t* resident,
                                 int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     if (!sel) SWARM_REJECT(ctx, "map_requests: NULL sel");
     const swarm_status st = check_map_args(ctx, "map_requests", groups, S, H, N, e2c, Nc, replicas, R, D, q_off, q_cluster,
                                            q_load, cap);
@@ -277,7 +286,7 @@ swarm_status swarm_step(swarm_ctx* ctx, const swarm_keys* keys, const void* q, i
                         float* out_scores, const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
                         const int32_t* weight, const uint32_t* resident, int32_t* q_off, int32_t* q_cluster,
                         int32_t* q_load, int32_t cap) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     swarm_status st = check_score_args(ctx, "step", keys, q, 1);
     if (st != SWARM_OK) return st;
     if (!out_idx) SWARM_REJECT(ctx, "step: NULL out_idx");
@@ -306,7 +315,7 @@ swarm_status swarm_step(swarm_ctx* ctx, const swarm_keys* keys, const void* q, i
 }
 
 swarm_status swarm_capture_begin(swarm_ctx* ctx) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     if (ctx->capturing) SWARM_REJECT(ctx, "capture_begin: already recording");
     if (!ctx->stream) SWARM_REJECT(ctx, "capture_begin: the NULL stream cannot be recorded");
     SWARM_HIP(ctx, hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal));

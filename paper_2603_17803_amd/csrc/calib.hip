@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void calib_mfma_i8_kernel(int iters, int seed,
 }  // namespace
 
 swarm_status swarm_calibrate(swarm_ctx* ctx, int32_t what, void* buf, size_t bytes, int32_t reps, double* out) {
-    if (!ctx) return SWARM_EINVAL;
+    SWARM_ENTER(ctx);
     if (!out || reps < 1) SWARM_REJECT(ctx, "calibrate: NULL out or reps < 1");
     if (ctx->capturing) SWARM_REJECT(ctx, "calibrate: not while recording");
     if (what != SWARM_CAL_MFMA_I8) {

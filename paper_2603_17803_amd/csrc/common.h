@@ -51,6 +51,16 @@ struct swarm_ctx {
         return SWARM_EINVAL;                                                                      \
     } while (0)
 
+// First statement of every entry point: a context is required, and its device must be the calling
+// thread's current device (kernels and allocations go to the current device).
+#define SWARM_ENTER(ctx)                                                                          \
+    do {                                                                                          \
+        if (!(ctx)) return SWARM_EINVAL;                                                          \
+        int cur_ = -1;                                                                            \
+        if (hipGetDevice(&cur_) != hipSuccess || cur_ != (ctx)->device)                           \
+            SWARM_REJECT(ctx, "the context belongs to device %d but device %d is current", (ctx)->device, cur_); \
+    } while (0)
+
 // Grows a scratch buffer to at least `bytes` (never shrinks).  Allocation synchronises the stream.
 swarm_status swarm_grow(swarm_ctx* ctx, void** buf, size_t* have, size_t bytes);
 

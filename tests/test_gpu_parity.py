@@ -597,6 +597,23 @@ def test_host_side_argument_errors_of_the_widened_entry_points(sw):
     assert sw.device_status() == 0
 
 
+def test_size_limits_are_rejected_before_anything_is_enqueued(sw):
+    # Through the plain C-ABI functions: the binding derives sizes from tensor shapes, so limits that no
+    # tensor of this size could reach are exercised with the pointers of a small, valid buffer.
+    from paper_2603_17803_amd import binding
+    Cd = torch.zeros((1, 64, 64), dtype=torch.int32, device="cuda")
+    sel = dev(W.random_selections(4, 1, 8, 64, seed=1))
+    rc = binding.swarm_coact_accumulate(sw.ctx, sel.data_ptr(), 4, 1, 8, (1 << 20) + 1, Cd.data_ptr(), 0, 0)
+    assert rc == binding.SWARM_EINVAL and "2^20" in binding.swarm_last_error(sw.ctx)
+    rc = binding.swarm_coact_accumulate(sw.ctx, sel.data_ptr(), (1 << 24) + 1, 1, 8, 64, Cd.data_ptr(), 0, 0)
+    assert rc == binding.SWARM_EINVAL
+    rho = torch.zeros((1, 64), dtype=torch.int32, device="cuda")
+    rc = binding.swarm_coact_density(sw.ctx, Cd.data_ptr(), 1, (1 << 20) + 1, None, 0.5, 0, rho.data_ptr(), None, None)
+    assert rc == binding.SWARM_EINVAL
+    torch.cuda.synchronize()
+    assert int(Cd.abs().sum()) == 0 and sw.device_status() == 0
+
+
 def test_calibration_reports_plausible_rates(sw):
     from paper_2603_17803_amd import binding
     buf = torch.empty(1 << 28, dtype=torch.int32, device="cuda")                 # 1 GiB
