@@ -287,7 +287,9 @@ swarm_status swarm_step(swarm_ctx* ctx, const swarm_keys* keys, const void* q, i
  * the recorded calls must not need to grow scratch: run the same sequence once beforehand).
  * swarm_graph_launch enqueues one replay on the context's stream; pointers and shapes are those
  * of the recorded calls, so the caller keeps those buffers alive and refreshes their contents.
- * swarm_device_status must not be called while recording.
+ * swarm_device_status must not be called while recording.  A recorded graph also refers to the
+ * context's scratch: once a context has recorded, scratch that later calls outgrow is kept (not
+ * freed) until swarm_destroy, so earlier graphs stay replayable; destroy graphs before their context.
  */
 typedef struct swarm_graph swarm_graph;
 swarm_status swarm_capture_begin(swarm_ctx* ctx);

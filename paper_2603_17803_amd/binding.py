@@ -282,15 +282,21 @@ class Swarm:
         self._check("swarm_coact_accumulate", rc)
         return Cm
 
-    def coact_density(self, Cm, tau: float, flags: int = 0, totals_in=None, want_queue: bool = True):
-        """Cm int32 [H][N][N] -> (rho int32 [H][N], queue int32 [H][N] or None, totals int64 [H])."""
+    def coact_density(self, Cm, tau: float, flags: int = 0, totals_in=None, want_queue: bool = True, out=None):
+        """Cm int32 [H][N][N] -> (rho int32 [H][N], queue int32 [H][N] or None, totals int64 [H]);
+        `out` = (rho, queue or None, totals) reuses the caller's tensors (needed while recording)."""
         torch = self.torch
         H, N, N2 = Cm.shape
         if N != N2:
             raise ValueError("C must be [H][N][N]")
-        rho = torch.empty((H, N), dtype=torch.int32, device=self.device)
-        queue = torch.empty((H, N), dtype=torch.int32, device=self.device) if want_queue else None
-        totals = torch.empty((H,), dtype=torch.int64, device=self.device)
+        if out is not None:
+            rho, queue, totals = out
+            if tuple(rho.shape) != (H, N) or (queue is not None and tuple(queue.shape) != (H, N)) or tuple(totals.shape) != (H,):
+                raise ValueError("out must be (rho [H][N], queue [H][N] or None, totals [H])")
+        else:
+            rho = torch.empty((H, N), dtype=torch.int32, device=self.device)
+            queue = torch.empty((H, N), dtype=torch.int32, device=self.device) if want_queue else None
+            totals = torch.empty((H,), dtype=torch.int64, device=self.device)
         rc = swarm_coact_density(self.ctx, self._dev(Cm, torch.int32, "C"), H, N,
                                  None if totals_in is None else self._dev(totals_in, torch.int64, "totals_in"), float(tau),
                                  flags, self._dev(rho, torch.int32, "rho"),

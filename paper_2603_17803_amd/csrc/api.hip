@@ -14,7 +14,19 @@ swarm_status swarm_grow(swarm_ctx* ctx, void** buf, size_t* have, size_t bytes) 
         return SWARM_EINVAL;
     }
     SWARM_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    if (*buf) SWARM_HIP(ctx, hipFree(*buf));
+    if (*buf) {
+        if (ctx->recorded) {
+            // a recorded graph may replay kernels that use the old buffer: keep it until the context goes
+            try {
+                ctx->retired.push_back(*buf);
+            } catch (...) {
+                snprintf(ctx->err, sizeof(ctx->err), "out of host memory");
+                return SWARM_ENOMEM;
+            }
+        } else {
+            SWARM_HIP(ctx, hipFree(*buf));
+        }
+    }
     *buf = nullptr;
     *have = 0;
     hipError_t e = hipMalloc(buf, bytes);
@@ -80,7 +92,8 @@ swarm_status swarm_destroy(swarm_ctx* ctx) {
     if (ctx->cand) (void)hipFree(ctx->cand);
     if (ctx->totals) (void)hipFree(ctx->totals);
     if (ctx->weights) (void)hipFree(ctx->weights);
-    if (ctx->tile_order) (void)hipFree(ctx->tile_order);
+    for (auto& t : ctx->tile_orders) (void)hipFree(t.second);
+    for (void* p : ctx->retired) (void)hipFree(p);
     if (ctx->dev_flags) (void)hipFree(ctx->dev_flags);
     delete ctx;
     return SWARM_OK;
@@ -320,6 +333,7 @@ swarm_status swarm_capture_begin(swarm_ctx* ctx) {
     if (!ctx->stream) SWARM_REJECT(ctx, "capture_begin: the NULL stream cannot be recorded");
     SWARM_HIP(ctx, hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal));
     ctx->capturing = true;
+    ctx->recorded = true;
     return SWARM_OK;
 }
 

@@ -461,37 +461,52 @@ swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows
 // (1024 x 2048 entries), so that the workgroups resident on one XCD share few panels in its L2.
 // Tile (ti, tj) covers rows [256 ti, +256) and columns [128 tj, +128); the tiles of a row start at
 // tj = 2 ti, the left half of the diagonal block.
-static swarm_status ensure_tile_order(swarm_ctx* ctx, int ntm) {
-    if (ctx->tile_order && ctx->tile_order_nt == ntm) return SWARM_OK;
+static swarm_status tile_order_for(swarm_ctx* ctx, int ntm, const int32_t** out) {
+    for (const auto& t : ctx->tile_orders)
+        if (t.first == ntm) { *out = t.second; return SWARM_OK; }
+    if (ctx->capturing) {
+        snprintf(ctx->err, sizeof(ctx->err), "coact: first call with this N while recording; run the sequence once first");
+        return SWARM_EINVAL;
+    }
     const int ntn = 2 * ntm;
     const size_t count = (size_t)ntm * (ntm + 1);
     int32_t* host = static_cast<int32_t*>(malloc(count * sizeof(int32_t)));
-    if (!host) return SWARM_ENOMEM;
+    if (!host) {
+        snprintf(ctx->err, sizeof(ctx->err), "out of host memory");
+        return SWARM_ENOMEM;
+    }
     size_t n = 0;
     for (int bi = 0; bi < ntm; bi += 4)
         for (int bj = 2 * bi / 16 * 16; bj < ntn; bj += 16)
             for (int ti = bi; ti < bi + 4 && ti < ntm; ++ti)
-                for (int tj = (bj > 2 * ti ? bj : 2 * ti); tj < bj + 16 && tj < ntn; ++tj) host[n++] = (ti << 16) | tj;
+                for (int tj = (bj > 2 * ti ? bj : 2 * ti); tj < bj + 16 && tj < ntn; ++tj)
+                    if (n < count) host[n++] = (ti << 16) | tj; else ++n;
     swarm_status st = SWARM_OK;
+    int32_t* dev = nullptr;
     if (n != count) {
         snprintf(ctx->err, sizeof(ctx->err), "coact: tile order covers %zu of %zu tiles", n, count);
         st = SWARM_EINVAL;
     }
     if (st == SWARM_OK) {
-        size_t have = ctx->tile_order ? (size_t)ctx->tile_order_nt * (ctx->tile_order_nt + 1) * 4 : 0;
-        st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->tile_order), &have, count * 4);
-    }
-    if (st == SWARM_OK) {
-        hipError_t e = hipMemcpyAsync(ctx->tile_order, host, count * 4, hipMemcpyHostToDevice, ctx->stream);
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&dev), count * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMemcpyAsync(dev, host, count * sizeof(int32_t), hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e == hipSuccess) {
+            try {
+                ctx->tile_orders.emplace_back(ntm, dev);
+            } catch (...) {
+                e = hipErrorOutOfMemory;
+            }
+        }
         if (e != hipSuccess) {
-            snprintf(ctx->err, sizeof(ctx->err), "coact: tile order upload failed: %s", hipGetErrorString(e));
+            (void)hipGetLastError();
+            snprintf(ctx->err, sizeof(ctx->err), "coact: tile order set-up failed: %s", hipGetErrorString(e));
+            if (dev) (void)hipFree(dev);
             st = SWARM_EHIP;
-        } else {
-            ctx->tile_order_nt = ntm;
         }
     }
     free(host);
+    *out = dev;
     return st;
 }
 
@@ -503,7 +518,8 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
         snprintf(ctx->err, sizeof(ctx->err), "coact: N=%d, H=%d give too many tiles for one launch", N, H);
         return SWARM_EINVAL;
     }
-    swarm_status st = ensure_tile_order(ctx, ntm);
+    const int32_t* tile_order = nullptr;
+    swarm_status st = tile_order_for(ctx, ntm, &tile_order);
     if (st != SWARM_OK) return st;
     const int per_xcd = (int)((total + 7) / 8);
     const int mode = decay_q16 == 0u ? 0 : decay_q16 == 65536u ? 1 : 2;
@@ -528,7 +544,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
     const int tph = (int)tiles_per_head, tot = (int)total;
     hipLaunchKernelGGL(kernels[mode][vec ? 1 : 0], grid, block, SYRK_LDS_BYTES, ctx->stream,
                        reinterpret_cast<const v4i*>(ctx->trace), N, Npad, nruns, C, decay_q16, tph, tot, per_xcd,
-                       static_cast<const int32_t*>(ctx->tile_order));
+                       tile_order);
     return swarm_check_launch(ctx, "coact_syrk_kernel");
 }
 

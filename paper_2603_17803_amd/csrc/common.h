@@ -5,6 +5,9 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <utility>
+#include <vector>
+
 #include "swarm.h"
 
 struct swarm_graph {
@@ -30,9 +33,10 @@ struct swarm_ctx {
     size_t totals_bytes = 0;
     bool trace_lds_opt_in = false, syrk_lds_opt_in = false;   // large dynamic LDS enabled for this context's device
     uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
-    int32_t* tile_order = nullptr; // co-activation tile schedule for tile_order_nt tiles per edge
-    int tile_order_nt = 0;
+    std::vector<std::pair<int, int32_t*>> tile_orders;   // co-activation tile schedules, one per tile count, never rewritten
     bool capturing = false;
+    bool recorded = false;         // a graph has been recorded on this context: it may refer to any scratch address
+    std::vector<void*> retired;    // outgrown scratch that recorded graphs may still use; freed with the context
 };
 
 #define SWARM_HIP(ctx, call)                                                                      \
