@@ -45,7 +45,7 @@ typedef enum {
     SWARM_EINVAL = -1,    /* argument rejected on the host; nothing was enqueued            */
     SWARM_ENOMEM = -2,    /* scratch allocation failed                                      */
     SWARM_EHIP = -3,      /* a HIP runtime call failed; text in swarm_last_error()          */
-    SWARM_EOVERFLOW = -4, /* a count could exceed int32                                      */
+    SWARM_EOVERFLOW = -4, /* reserved (count overflow is detected on the device: SWARM_DEV_OVERFLOW) */
     SWARM_EDATA = -5      /* swarm_device_status(): a kernel met an out-of-range index      */
 } swarm_status;
 
@@ -76,6 +76,8 @@ typedef struct {
 #define SWARM_DEV_BAD_SSD     4u  /* replica slot >= D, or a cluster with none   */
 #define SWARM_DEV_CAP         8u  /* a group had more distinct clusters than cap */
 #define SWARM_DEV_DUP_ENTRY   16u /* repeated entry within one selection         */
+#define SWARM_DEV_BAD_OFFSETS 32u /* bucket offsets not non-decreasing from 0 to at most cap */
+#define SWARM_DEV_OVERFLOW    64u /* a co-activation count passed INT32_MAX (it wrapped) */
 
 /* Creates a context bound to HIP device `device` and to `hip_stream` (a hipStream_t; NULL is the
  * default stream).  The stream stays the caller's.  */
@@ -139,6 +141,8 @@ swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, 
  * flags  SWARM_CHECK_IDX additionally flags repeated entries (SWARM_DEV_DUP_ENTRY); a repeated
  *        entry counts once either way, because the trace is binary.  SWARM_COACT_POPCOUNT computes the
  *        same counts as popcount(bits_i & bits_j) over the bit trace, without the matrix cores.
+ * Counts are exact as long as they fit int32: rows <= 2^24 cannot overflow a fresh C, and when an
+ * accumulating or decayed update passes INT32_MAX the count wraps and SWARM_DEV_OVERFLOW is raised.
  * Errors: SWARM_EINVAL as above or decay_q16 > 65536; SWARM_ENOMEM if the trace (H*N*rows/8 bytes,
  * rows rounded up to 512, N to 256) cannot be allocated.
  */
@@ -252,7 +256,9 @@ swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t grou
  * swarm_submission_order: order[g] lists the items of swarm_map_requests' buckets batch by batch (batch
  *   b = the b-th item of every bucket that has one, ascending SSD id), -1 padded to cap;
  *   batch_off[g][b] is where batch b starts (entries from nb[g] on repeat the item count), int32
- *   [groups][cap+1]; nb[g] = number of batches = longest bucket.
+ *   [groups][cap+1]; nb[g] = number of batches = longest bucket.  q_off[g] must run from 0 in
+ *   non-decreasing steps to at most cap; a group where it does not gets an empty order, nb = 0 and
+ *   SWARM_DEV_BAD_OFFSETS.
  * In swarm_map_requests an entry id of -1 is padding and is skipped, so ragged entry lists can be mapped.
  */
 swarm_status swarm_score_select_indexed(swarm_ctx* ctx, const swarm_keys* keys, const int32_t* row_ids, int32_t M, const void* q,

@@ -17,6 +17,7 @@
 // Build: g++ -O2 -std=c++17 -shared -fPIC -pthread swarm_oracle.cpp -o liboracle.so
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -197,7 +198,8 @@ int oracle_coact_dense(const uint8_t* A, int64_t rows, int N, int32_t* C) {
 //     decay_q16 = 65536 keeps C (plain accumulation), 0 discards it.
 // New evidence enters undecayed.  The decay is not in the paper; it addresses the degradation of
 // stale co-activation statistics the paper describes as its fourth challenge (Section 3.2).
-// idx[rows][H][k], C[H][N][N] in/out.  Returns -2 on a bad index, -3 on a repeated index in a row.
+// idx[rows][H][k], C[H][N][N] in/out.  Returns -2 on a bad index, -3 on a repeated index in a row,
+// -5 when a count would pass INT32_MAX (counts are exact or the call fails; C is then partly updated).
 // ---------------------------------------------------------------------------------------
 int oracle_coact_update(const int32_t* idx, int64_t rows, int H, int k, int N, int32_t* C,
                         uint32_t decay_q16, int nthreads) {
@@ -209,6 +211,7 @@ int oracle_coact_update(const int32_t* idx, int64_t rows, int H, int k, int N, i
         if (std::adjacent_find(v.begin(), v.end()) != v.end()) return -3;
     }
     // Row i of C[h] only depends on the trace rows that contain i: split (h, i) over workers.
+    std::atomic<bool> overflow(false);
     parallel_for((int64_t)H * N, nthreads, [&](int64_t lo, int64_t hi) {
         if (decay_q16 != 65536u) {
             for (int64_t hi_row = lo; hi_row < hi; ++hi_row) {
@@ -224,11 +227,14 @@ int oracle_coact_update(const int32_t* idx, int64_t rows, int H, int k, int N, i
                     const int64_t hrow = (int64_t)h * N + sel[a];
                     if (hrow < lo || hrow >= hi) continue;
                     int32_t* crow = C + hrow * N;
-                    for (int b = 0; b < k; ++b) ++crow[sel[b]];
+                    for (int b = 0; b < k; ++b) {
+                        if (crow[sel[b]] == INT32_MAX) { overflow.store(true); continue; }
+                        ++crow[sel[b]];
+                    }
                 }
             }
     });
-    return 0;
+    return overflow.load() ? -5 : 0;
 }
 
 // ---------------------------------------------------------------------------------------

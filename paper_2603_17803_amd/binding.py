@@ -17,6 +17,7 @@ SWARM_OK, SWARM_EINVAL, SWARM_ENOMEM, SWARM_EHIP, SWARM_EOVERFLOW, SWARM_EDATA =
 SWARM_KEYS_TOKEN, SWARM_KEYS_PAGE_MINMAX = 0, 1
 SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
+SWARM_DEV_BAD_OFFSETS, SWARM_DEV_OVERFLOW = 32, 64
 
 EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score", "swarm_score_select",
            "swarm_coact_accumulate", "swarm_map_requests", "swarm_coact_density", "swarm_window_assign", "swarm_score_select_indexed", "swarm_expand_clusters",

@@ -89,6 +89,16 @@ __device__ __forceinline__ int32_t decayed(int32_t old, uint32_t decay_q16) {
     return (int32_t)(((int64_t)old * (int64_t)decay_q16 + 32768) >> 16);
 }
 
+// Updated count for the accumulating (MODE 1) and decayed (MODE 2) forms: v >= 0 is added to the old
+// count or to its decayed value.  A sum that passes INT32_MAX wraps and sets `ovf`.
+template <int MODE>
+__device__ __forceinline__ int32_t updated_count(int32_t old, int32_t v, uint32_t decay_q16, bool& ovf) {
+    const int32_t base = MODE == 1 ? old : decayed(old, decay_q16);
+    const int32_t s = (int32_t)((uint32_t)base + (uint32_t)v);
+    ovf |= s < base;
+    return s;
+}
+
 constexpr int TM = 256;                        // C tile rows per workgroup
 constexpr int TN = 128;                        // C tile columns per workgroup
 constexpr int KC = 64;                         // trace rows (= contraction bytes) per chunk: two 32-byte MFMA k-steps
@@ -127,7 +137,8 @@ template <int MODE, bool VEC>
 __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns,
                                                             int32_t* __restrict__ C, uint32_t decay_q16,
                                                             int tiles_per_head, int total_tiles, int per_xcd,
-                                                            const int32_t* __restrict__ tile_order) {
+                                                            const int32_t* __restrict__ tile_order,
+                                                            uint32_t* __restrict__ dev_flags) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int xcd = blockIdx.x & 7, slot_id = blockIdx.x >> 3;
     const int t = xcd * per_xcd + slot_id;
@@ -280,8 +291,9 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     // that is the same for every store of a tile.
     const uint32_t lane_direct = (uint32_t)row_in * (uint32_t)N + col_in;
     const uint32_t lane_mirror = (uint32_t)half * (uint32_t)N + col_in * 4;
+    bool ovf = false;
     auto combine = [&](int32_t old, int32_t v) __attribute__((always_inline)) {
-        return MODE == 1 ? old + v : decayed(old, decay_q16) + v;
+        return updated_count<MODE == 0 ? 1 : MODE>(old, v, decay_q16, ovf);
     };
     // GUARD: the tile reaches past N (only tiles of the last tile row / column when N is not a multiple of 256)
     auto emit = [&](auto guard_tag) __attribute__((always_inline)) {
@@ -368,6 +380,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     };
     if (MODE == 0 && (ti + 1) * TM <= N && (tj + 1) * TN <= N) emit(std::false_type{});   // whole tile inside C: no per-store checks
     else emit(std::true_type{});
+    if (MODE != 0 && ovf) atomicOr(dev_flags, SWARM_DEV_OVERFLOW);
 }
 
 // The same counts without the matrix cores: C[i][j] = sum over the trace's 32-bit words of
@@ -381,7 +394,8 @@ constexpr int PT = 64, PRUNS = 8;
 
 template <int MODE>
 __global__ __launch_bounds__(256) void coact_popcount_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns,
-                                                             int32_t* __restrict__ C, uint32_t decay_q16) {
+                                                             int32_t* __restrict__ C, uint32_t decay_q16,
+                                                             uint32_t* __restrict__ dev_flags) {
     __shared__ v4i sa[PRUNS][PT], sb[PRUNS][PT];
     const int h = blockIdx.z, ti = blockIdx.y, tj = blockIdx.x;
     if (tj < ti) return;
@@ -415,6 +429,7 @@ __global__ __launch_bounds__(256) void coact_popcount_kernel(const v4i* __restri
         }
     }
     int32_t* Ch = C + (size_t)h * N * N;
+    bool ovf = false;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -425,9 +440,12 @@ __global__ __launch_bounds__(256) void coact_popcount_kernel(const v4i* __restri
             int32_t* p = Ch + (size_t)gi * N + gj;
             int32_t* q = Ch + (size_t)gj * N + gi;
             if (MODE == 0) { *p = v; if (ti != tj) *q = v; }
-            else if (MODE == 1) { *p += v; if (ti != tj) *q += v; }
-            else { *p = decayed(*p, decay_q16) + v; if (ti != tj) *q = decayed(*q, decay_q16) + v; }
+            else {
+                *p = updated_count<MODE == 0 ? 1 : MODE>(*p, v, decay_q16, ovf);
+                if (ti != tj) *q = updated_count<MODE == 0 ? 1 : MODE>(*q, v, decay_q16, ovf);
+            }
         }
+    if (MODE != 0 && ovf) atomicOr(dev_flags, SWARM_DEV_OVERFLOW);
 }
 
 }  // namespace
@@ -524,7 +542,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
     const int per_xcd = (int)((total + 7) / 8);
     const int mode = decay_q16 == 0u ? 0 : decay_q16 == 65536u ? 1 : 2;
     const bool vec = (N & 3) == 0;
-    using kernel_t = void (*)(const v4i*, int, int, int, int32_t*, uint32_t, int, int, int, const int32_t*);
+    using kernel_t = void (*)(const v4i*, int, int, int, int32_t*, uint32_t, int, int, int, const int32_t*, uint32_t*);
     static const kernel_t kernels[3][2] = {{coact_syrk_kernel<0, false>, coact_syrk_kernel<0, true>},
                                            {coact_syrk_kernel<1, false>, coact_syrk_kernel<1, true>},
                                            {coact_syrk_kernel<2, false>, coact_syrk_kernel<2, true>}};
@@ -544,7 +562,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
     const int tph = (int)tiles_per_head, tot = (int)total;
     hipLaunchKernelGGL(kernels[mode][vec ? 1 : 0], grid, block, SYRK_LDS_BYTES, ctx->stream,
                        reinterpret_cast<const v4i*>(ctx->trace), N, Npad, nruns, C, decay_q16, tph, tot, per_xcd,
-                       tile_order);
+                       tile_order, ctx->dev_flags);
     return swarm_check_launch(ctx, "coact_syrk_kernel");
 }
 
@@ -556,8 +574,8 @@ swarm_status launch_coact_popcount(swarm_ctx* ctx, int H, int N, int Npad, int n
     }
     const dim3 grid(nt, nt, (unsigned)H), block(256);
     const v4i* bits = reinterpret_cast<const v4i*>(ctx->trace);
-    if (decay_q16 == 0u) hipLaunchKernelGGL(coact_popcount_kernel<0>, grid, block, 0, ctx->stream, bits, N, Npad, nruns, C, decay_q16);
-    else if (decay_q16 == 65536u) hipLaunchKernelGGL(coact_popcount_kernel<1>, grid, block, 0, ctx->stream, bits, N, Npad, nruns, C, decay_q16);
-    else hipLaunchKernelGGL(coact_popcount_kernel<2>, grid, block, 0, ctx->stream, bits, N, Npad, nruns, C, decay_q16);
+    if (decay_q16 == 0u) hipLaunchKernelGGL(coact_popcount_kernel<0>, grid, block, 0, ctx->stream, bits, N, Npad, nruns, C, decay_q16, ctx->dev_flags);
+    else if (decay_q16 == 65536u) hipLaunchKernelGGL(coact_popcount_kernel<1>, grid, block, 0, ctx->stream, bits, N, Npad, nruns, C, decay_q16, ctx->dev_flags);
+    else hipLaunchKernelGGL(coact_popcount_kernel<2>, grid, block, 0, ctx->stream, bits, N, Npad, nruns, C, decay_q16, ctx->dev_flags);
     return swarm_check_launch(ctx, "coact_popcount_kernel");
 }

@@ -82,12 +82,23 @@ __global__ __launch_bounds__(EXP_THREADS) void expand_clusters_kernel(const int3
 // rank = sum over buckets of min(length, pos) + number of lower-numbered buckets longer than pos.
 __global__ __launch_bounds__(256) void submission_order_kernel(const int32_t* __restrict__ q_off, const int32_t* __restrict__ q_cluster,
                                                                int D, int cap, int32_t* __restrict__ order,
-                                                               int32_t* __restrict__ batch_off, int32_t* __restrict__ nb) {
+                                                               int32_t* __restrict__ batch_off, int32_t* __restrict__ nb,
+                                                               uint32_t* __restrict__ dev_flags) {
     __shared__ int32_t off[65];
     const int64_t g = blockIdx.x;
     for (int d = threadIdx.x; d <= D; d += 256) off[d] = q_off[g * (D + 1) + d];
     __syncthreads();
-    const int32_t total = min(off[D], cap);
+    // offsets that are not a non-decreasing sequence from 0 to at most cap would send ranks out of range:
+    // such a group gets an empty order and a flag (every thread takes the same decision)
+    bool bad = off[0] != 0 || off[D] > cap;
+    for (int e = 0; e < D; ++e) bad |= off[e + 1] < off[e];
+    if (bad) {
+        for (int32_t p = threadIdx.x; p < cap; p += 256) order[g * cap + p] = -1;
+        for (int32_t b = threadIdx.x; b <= cap; b += 256) batch_off[g * (cap + 1) + b] = 0;
+        if (threadIdx.x == 0) { nb[g] = 0; atomicOr(dev_flags, SWARM_DEV_BAD_OFFSETS); }
+        return;
+    }
+    const int32_t total = off[D];
     for (int32_t p = threadIdx.x; p < cap; p += 256) {
         if (p >= total) { order[g * cap + p] = -1; continue; }
         int d = 0;
@@ -124,6 +135,6 @@ swarm_status launch_expand_clusters(swarm_ctx* ctx, const int32_t* clusters, int
 swarm_status launch_submission_order(swarm_ctx* ctx, const int32_t* q_off, const int32_t* q_cluster, int64_t groups, int D, int cap,
                                      int32_t* order, int32_t* batch_off, int32_t* nb) {
     hipLaunchKernelGGL(submission_order_kernel, dim3((unsigned)groups), dim3(256), 0, ctx->stream, q_off, q_cluster, D, cap, order,
-                       batch_off, nb);
+                       batch_off, nb, ctx->dev_flags);
     return swarm_check_launch(ctx, "submission_order_kernel");
 }

@@ -196,6 +196,42 @@ def test_coact_decay_of_large_counts(sw):
     assert np.array_equal(Cd.cpu().numpy(), oracle.coact_update(sel, N, C0.copy(), 64881))
 
 
+@pytest.mark.parametrize("route", [0, 2], ids=["mfma", "popcount"])
+def test_coact_count_overflow_is_flagged(sw, route):
+    from paper_2603_17803_amd import binding
+    N = 300                                                              # tile with a ragged edge
+    sel = W.random_selections(9, 2, 5, N, seed=11, topic_like=False)
+    big = np.iinfo(np.int32).max
+    counts = oracle.coact_update(sel, N)
+    # every count lands exactly on the limit: no flag, and the oracle agrees
+    C0 = (big - counts).astype(np.int32)
+    for decay, start in ((65536, C0),):
+        Cd = dev(start.copy())
+        sw.coact_accumulate(dev(sel), N, Cd, decay_q16=decay, flags=route)
+        assert sw.device_status() == 0
+        assert np.array_equal(Cd.cpu().numpy(), oracle.coact_update(sel, N, start.copy(), decay))
+        assert (Cd.cpu().numpy() == big).all()
+    # one element one short of room: flagged, and the oracle refuses the same update
+    h, i, j = 1, int(sel[0, 1, 0]), int(sel[0, 1, 1])
+    C1 = C0.copy()
+    C1[h, i, j] += 1
+    with pytest.raises(oracle.OracleError):
+        oracle.coact_update(sel, N, C1.copy(), 65536)
+    Cd = dev(C1.copy())
+    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=65536, flags=route)
+    assert sw.device_status() == binding.SWARM_DEV_OVERFLOW
+    got = Cd.cpu().numpy()
+    mask = np.ones_like(got, bool)
+    mask[h, i, j] = False
+    assert (got[mask] == big).all()                                     # every other count is still exact
+    # decayed form: flagged only when the decayed count plus the new evidence passes the limit
+    C2 = np.full((2, N, N), big, np.int32)
+    Cd = dev(C2.copy())
+    sw.coact_accumulate(dev(sel), N, Cd, decay_q16=65535, flags=route)   # big*65535/65536 leaves 32768 of room
+    assert sw.device_status() == 0
+    assert np.array_equal(Cd.cpu().numpy(), oracle.coact_update(sel, N, C2.copy(), 65535))
+
+
 def test_coact_bad_and_repeated_entries_are_flagged_not_fatal(sw):
     from paper_2603_17803_amd import binding
     N = 32
@@ -595,6 +631,25 @@ def test_host_side_argument_errors_of_the_widened_entry_points(sw):
     with pytest.raises(binding.SwarmError):
         sw.step("token", Kd, qd[0], 65, e2c, 1, rep, 4)                         # k > N
     assert sw.device_status() == 0
+
+
+def test_submission_order_bad_offsets_are_flagged_not_fatal(sw):
+    from paper_2603_17803_amd import binding
+    D, cap = 4, 8
+    q_off = np.array([[0, 2, 5, 6, 8],          # valid
+                      [0, 3, 2, 6, 8],          # decreasing
+                      [1, 2, 5, 6, 8],          # does not start at 0
+                      [0, 2, 5, 6, 9],          # beyond cap
+                      [0, 0, 0, 0, 0]], np.int32)
+    q_clu = np.arange(5 * cap, dtype=np.int32).reshape(5, cap)
+    order, batch_off, nb = sw.submission_order(dev(q_off), dev(q_clu))
+    flags = sw.device_status()
+    assert flags == binding.SWARM_DEV_BAD_OFFSETS
+    r_order, r_batch, r_nb = oracle.submission_order(q_off[[0, 4]], q_clu[[0, 4]])
+    order, batch_off, nb = order.cpu().numpy(), batch_off.cpu().numpy(), nb.cpu().numpy()
+    assert np.array_equal(order[[0, 4]], r_order) and np.array_equal(batch_off[[0, 4]], r_batch)
+    assert np.array_equal(nb[[0, 4]], r_nb)
+    assert (order[1:4] == -1).all() and (batch_off[1:4] == 0).all() and (nb[1:4] == 0).all()
 
 
 def test_size_limits_are_rejected_before_anything_is_enqueued(sw):

@@ -122,6 +122,24 @@ def test_coact_rejects_bad_selections():
         oracle.coact_update(np.array([[[2, 2]]], np.int32), 5)
 
 
+def test_coact_count_overflow_is_an_error_not_a_wrap():
+    # counts are exact in int32 or the update fails: the last representable count may be reached, not passed
+    sel = np.array([[[0, 1]], [[0, 2]]], np.int32)                       # entry 0 twice, pairs (0,1), (0,2) once
+    big = np.iinfo(np.int32).max
+    C0 = np.zeros((1, 3, 3), np.int32)
+    C0[0, 0, 0] = big - 2
+    C0[0, 0, 1] = C0[0, 1, 0] = big - 1
+    out = oracle.coact_update(sel, 3, C0.copy(), 65536)
+    assert out[0, 0, 0] == big and out[0, 0, 1] == big and out[0, 1, 0] == big and out[0, 0, 2] == 1
+    C0[0, 0, 0] = big - 1                                                # two increments would pass the limit
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.coact_update(sel, 3, C0.copy(), 65536)
+    assert e.value.code == -5
+    # decay first, then add: the same matrix is fine once it has been halved
+    out = oracle.coact_update(sel, 3, C0.copy(), 32768)
+    assert out[0, 0, 0] == (big - 1 + 1) // 2 + 2
+
+
 # ------------------------------------------------------------------ request mapping
 
 def bitmap(ids, nbits):
