@@ -180,6 +180,17 @@ def main():
         sw.coact_density(Cm, tau)
 
     dens_us, dens_us_min = stage(density, reps, 1)
+    # the same C, rho and queue in one pass: the radius test applied to C's tiles while they are in registers
+    sep_rho, sep_queue, _ = sw.coact_density(Cm, tau)
+    fused_out = (torch.empty((H, N), dtype=torch.int32, device="cuda"), torch.empty((H, N), dtype=torch.int32, device="cuda"),
+                 torch.empty((H,), dtype=torch.int64, device="cuda"))
+
+    def build_density():
+        sw.coact_build_density(idx_all, N, Cm, tau, out=fused_out)
+
+    fused_us, fused_us_min = stage(build_density, reps, 1)
+    stream.synchronize()
+    assert torch.equal(fused_out[0], sep_rho) and torch.equal(fused_out[1], sep_queue), "fused density differs from the two-call result"
     # cluster maintenance over the last 256 steps: 256 new entries against one medoid per cluster
     g = np.random.default_rng(cfg.seed + 17)
     new_d = dev(np.stack([g.choice(N, 256, replace=False) for _ in range(H)]).astype(np.int32))
@@ -248,6 +259,9 @@ def main():
         "density_pass": {"what": "grand total, rho and medoid queue from C (two sweeps of C plus an N^2 ranking)",
                          "ms": round(dens_us * 1e-3, 3), "ms_min": round(dens_us_min * 1e-3, 3), "bound": "hbm",
                          "bytes": 2 * H * N * N * 4, "achieved_GBs": round(2 * H * N * N * 4 / (dens_us * 1e-6) / 1e9, 1)},
+        "build_density_one_pass": {"what": "trace + C + rho + queue with the radius test in the C kernel's epilogue (C written once, never read)",
+                                   "ms": round(fused_us * 1e-3, 3), "ms_min": round(fused_us_min * 1e-3, 3),
+                                   "two_calls_ms": round(coact_ms + dens_us * 1e-3, 3)},
         "window_maintenance": {"what": "last 256 steps, 256 new entries x %d medoids per head: trace bits + counts + membership" % cfg.Nc,
                                "us": round(win_us, 1), "us_min": round(win_us_min, 1)},
         "medoid_index": {"what": "score + select over %d medoids per head (top %d) instead of %d pages" % (cfg.Nc, kc, N),

@@ -174,6 +174,24 @@ swarm_status swarm_coact_density(swarm_ctx* ctx, const int32_t* C, int32_t H, in
                                  double tau, uint32_t flags, int32_t* rho, int32_t* queue, int64_t* totals_out);
 
 /*
+ * Co-activation build and density pass in one go (Section 5.1, Steps 1-3): C = A^T A as
+ * swarm_coact_accumulate computes it with decay_q16 = 0, and rho / queue / totals exactly as
+ * swarm_coact_density would then compute them from that C with totals_in = NULL.  The grand total of
+ * a fresh build is known before C exists (it is the sum over trace rows of the squared number of
+ * activated entries), so the radius test "d(i,j) <= tau" is an integer threshold on the count and is
+ * applied to every tile of C while it is still in registers: C is written once and never read back.
+ * (When N is not a multiple of 4 the two steps run one after the other, with the same results.)
+ *
+ * idx, rows, H, k, N, C   as in swarm_coact_accumulate; C is overwritten.
+ * flags                   SWARM_CHECK_IDX or 0.
+ * tau, rho_flags, rho, queue, totals_out   as in swarm_coact_density (queue and totals_out may be NULL).
+ * Errors: those of the two calls.
+ */
+swarm_status swarm_coact_build_density(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int32_t H, int32_t k, int32_t N,
+                                       int32_t* C, uint32_t flags, double tau, uint32_t rho_flags, int32_t* rho, int32_t* queue,
+                                       int64_t* totals_out);
+
+/*
  * Cluster maintenance over the local window (Section 6.2: the distance between a newly generated entry
  * and a cluster is 1 - f(e_new, m_i) / W, with f the number of the window's W steps in which the entry
  * and the cluster's medoid m_i are activated together; the entry joins every cluster whose distance is

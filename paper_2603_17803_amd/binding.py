@@ -20,7 +20,7 @@ SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SW
 SWARM_DEV_BAD_OFFSETS, SWARM_DEV_OVERFLOW = 32, 64
 
 EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score", "swarm_score_select",
-           "swarm_coact_accumulate", "swarm_map_requests", "swarm_coact_density", "swarm_window_assign", "swarm_score_select_indexed", "swarm_expand_clusters",
+           "swarm_coact_accumulate", "swarm_coact_build_density", "swarm_map_requests", "swarm_coact_density", "swarm_window_assign", "swarm_score_select_indexed", "swarm_expand_clusters",
            "swarm_submission_order", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
 
@@ -58,6 +58,7 @@ def load() -> C.CDLL:
     L.swarm_coact_accumulate.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, u32]
     L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
+    L.swarm_coact_build_density.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, C.c_double, u32, vp, vp, vp]
     L.swarm_coact_density.argtypes = [vp, vp, i32, i32, vp, C.c_double, C.c_uint32, vp, vp, vp]
     L.swarm_window_assign.argtypes = [vp, vp, i32, i32, i32, i32, vp, i32, vp, i32, C.c_double, vp, vp, i32, vp, vp, vp]
     L.swarm_score_select_indexed.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp]
@@ -168,6 +169,12 @@ def swarm_coact_accumulate(ctx: int, idx: int, rows: int, H: int, k: int, N: int
                            flags: int) -> int:
     return load().swarm_coact_accumulate(C.c_void_p(ctx), C.c_void_p(idx), rows, H, k, N, C.c_void_p(Cptr),
                                          decay_q16, flags)
+
+
+def swarm_coact_build_density(ctx: int, idx: int, rows: int, H: int, k: int, N: int, Cptr: int, flags: int, tau: float,
+                              rho_flags: int, rho: int, queue: Optional[int], totals_out: Optional[int]) -> int:
+    return load().swarm_coact_build_density(C.c_void_p(ctx), C.c_void_p(idx), rows, H, k, N, C.c_void_p(Cptr), flags, tau,
+                                            rho_flags, C.c_void_p(rho), C.c_void_p(queue), C.c_void_p(totals_out))
 
 
 def swarm_map_requests(ctx: int, sel: int, groups: int, S: int, H: int, N: int, e2c: int, Nc: int, replicas: int,
@@ -282,6 +289,29 @@ class Swarm:
                                     self._dev(Cm, torch.int32, "C"), decay_q16, flags)
         self._check("swarm_coact_accumulate", rc)
         return Cm
+
+    def coact_build_density(self, idx, N: int, Cm, tau: float, flags: int = 0, rho_flags: int = 0, want_queue: bool = True,
+                            out=None):
+        """idx int32 [rows][H][k]; Cm int32 [H][N][N] overwritten with the counts -> (rho, queue or None, totals) as
+        coact_density gives them for that Cm; `out` = (rho, queue or None, totals) reuses the caller's tensors."""
+        torch = self.torch
+        rows, H, k = idx.shape
+        if tuple(Cm.shape) != (H, N, N):
+            raise ValueError(f"C has shape {tuple(Cm.shape)}, expected {(H, N, N)}")
+        if out is not None:
+            rho, queue, totals = out
+            if tuple(rho.shape) != (H, N) or (queue is not None and tuple(queue.shape) != (H, N)) or tuple(totals.shape) != (H,):
+                raise ValueError("out must be (rho [H][N], queue [H][N] or None, totals [H])")
+        else:
+            rho = torch.empty((H, N), dtype=torch.int32, device=self.device)
+            queue = torch.empty((H, N), dtype=torch.int32, device=self.device) if want_queue else None
+            totals = torch.empty((H,), dtype=torch.int64, device=self.device)
+        rc = swarm_coact_build_density(self.ctx, self._dev(idx, torch.int32, "idx"), rows, H, k, N, self._dev(Cm, torch.int32, "C"),
+                                       flags, float(tau), rho_flags, self._dev(rho, torch.int32, "rho"),
+                                       None if queue is None else self._dev(queue, torch.int32, "queue"),
+                                       self._dev(totals, torch.int64, "totals"))
+        self._check("swarm_coact_build_density", rc)
+        return rho, queue, totals
 
     def coact_density(self, Cm, tau: float, flags: int = 0, totals_in=None, want_queue: bool = True, out=None):
         """Cm int32 [H][N][N] -> (rho int32 [H][N], queue int32 [H][N] or None, totals int64 [H]);

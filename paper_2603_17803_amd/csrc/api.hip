@@ -204,27 +204,73 @@ swarm_status swarm_submission_order(swarm_ctx* ctx, const int32_t* q_off, const 
     return launch_submission_order(ctx, q_off, q_cluster, groups, D, cap, order, batch_off, nb);
 }
 
+static swarm_status check_coact_args(swarm_ctx* ctx, const char* fn, const int32_t* idx, int64_t rows, int32_t H, int32_t k,
+                                     int32_t N, const int32_t* C, uint32_t flags, uint32_t allowed_flags) {
+    if (!idx || !C) SWARM_REJECT(ctx, "%s: NULL idx or C", fn);
+    if (H < 1 || N < 1 || k < 1 || k > N) SWARM_REJECT(ctx, "%s: H=%d N=%d k=%d invalid", fn, H, N, k);
+    if (N > (1 << 20) || H > 65535) SWARM_REJECT(ctx, "%s: N=%d above 2^20 or H=%d above 65535", fn, N, H);
+    if (rows < 1 || rows > ((int64_t)1 << 24)) SWARM_REJECT(ctx, "%s: rows=%lld outside [1,2^24]", fn, (long long)rows);
+    if (flags & ~allowed_flags) SWARM_REJECT(ctx, "%s: unknown flags 0x%x", fn, flags);
+    if ((flags & SWARM_CHECK_IDX) && rows * H > ((int64_t)1 << 30))
+        SWARM_REJECT(ctx, "%s: SWARM_CHECK_IDX handles at most 2^30 (row, head) selections per call", fn);
+    if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "%s: C must be 16-byte aligned", fn);
+    return SWARM_OK;
+}
+
 swarm_status swarm_coact_accumulate(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int32_t H, int32_t k,
                                     int32_t N, int32_t* C, uint32_t decay_q16, uint32_t flags) {
     SWARM_ENTER(ctx);
-    if (!idx || !C) SWARM_REJECT(ctx, "coact_accumulate: NULL idx or C");
-    if (H < 1 || N < 1 || k < 1 || k > N) SWARM_REJECT(ctx, "coact_accumulate: H=%d N=%d k=%d invalid", H, N, k);
-    if (N > (1 << 20) || H > 65535) SWARM_REJECT(ctx, "coact_accumulate: N=%d above 2^20 or H=%d above 65535", N, H);
-    if (rows < 1 || rows > ((int64_t)1 << 24)) SWARM_REJECT(ctx, "coact_accumulate: rows=%lld outside [1,2^24]", (long long)rows);
+    swarm_status st = check_coact_args(ctx, "coact_accumulate", idx, rows, H, k, N, C, flags, SWARM_CHECK_IDX | SWARM_COACT_POPCOUNT);
+    if (st != SWARM_OK) return st;
     if (decay_q16 > 65536u) SWARM_REJECT(ctx, "coact_accumulate: decay_q16=%u above 65536", decay_q16);
-    if ((flags & SWARM_CHECK_IDX) && rows * H > ((int64_t)1 << 30))
-        SWARM_REJECT(ctx, "coact_accumulate: SWARM_CHECK_IDX handles at most 2^30 (row, head) selections per call");
-    if (reinterpret_cast<uintptr_t>(C) & 15) SWARM_REJECT(ctx, "coact_accumulate: C must be 16-byte aligned");
-    if (flags & ~(SWARM_CHECK_IDX | SWARM_COACT_POPCOUNT)) SWARM_REJECT(ctx, "coact_accumulate: unknown flags 0x%x", flags);
 
     const int nruns = (int)((rows + 511) / 512 * 4);      // contraction in runs of 128 trace rows, zero-padded to a multiple of 4 runs
     const int Npad = (N + 255) / 256 * 256;               // entries, zero-padded to the C tile
-    swarm_status st = swarm_grow(ctx, &ctx->trace, &ctx->trace_bytes, (size_t)H * nruns * Npad * 16);
+    st = swarm_grow(ctx, &ctx->trace, &ctx->trace_bytes, (size_t)H * nruns * Npad * 16);
     if (st != SWARM_OK) return st;
     st = launch_trace_build(ctx, idx, rows, H, k, N, Npad, nruns, flags);
     if (st != SWARM_OK) return st;
     if (flags & SWARM_COACT_POPCOUNT) return launch_coact_popcount(ctx, H, N, Npad, nruns, C, decay_q16);
     return launch_coact_syrk(ctx, H, N, Npad, nruns, C, decay_q16);
+}
+
+swarm_status swarm_coact_build_density(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int32_t H, int32_t k, int32_t N,
+                                       int32_t* C, uint32_t flags, double tau, uint32_t rho_flags, int32_t* rho, int32_t* queue,
+                                       int64_t* totals_out) {
+    SWARM_ENTER(ctx);
+    swarm_status st = check_coact_args(ctx, "coact_build_density", idx, rows, H, k, N, C, flags, SWARM_CHECK_IDX);
+    if (st != SWARM_OK) return st;
+    if (!rho) SWARM_REJECT(ctx, "coact_build_density: NULL rho");
+    if (rho_flags & ~(SWARM_RHO_EXCLUDE_SELF | SWARM_RHO_STRICT)) SWARM_REJECT(ctx, "coact_build_density: unknown rho_flags 0x%x", rho_flags);
+    if (totals_out && (reinterpret_cast<uintptr_t>(totals_out) & 7)) SWARM_REJECT(ctx, "coact_build_density: totals_out must be 8-byte aligned");
+
+    const int nruns = (int)((rows + 511) / 512 * 4);
+    const int Npad = (N + 255) / 256 * 256;
+    st = swarm_grow(ctx, &ctx->trace, &ctx->trace_bytes, (size_t)H * nruns * Npad * 16);
+    if (st != SWARM_OK) return st;
+    // auxiliary scratch: totals [H] and thresholds [H] (int64), then the trace rows' entry counts [H][nruns * 128] (int32)
+    st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->totals), &ctx->totals_bytes,
+                    sizeof(int64_t) * 2 * (size_t)H + sizeof(int32_t) * (size_t)H * nruns * 128);
+    if (st != SWARM_OK) return st;
+    int64_t* totals = totals_out ? totals_out : ctx->totals;
+    int64_t* cstar = ctx->totals + H;
+    int32_t* row_count = reinterpret_cast<int32_t*>(ctx->totals + 2 * (size_t)H);
+
+    if (N & 3) {
+        // rows of C are not 16-byte aligned: the epilogue has no vector pass to count in; build, then sweep
+        st = launch_trace_build(ctx, idx, rows, H, k, N, Npad, nruns, flags);
+        if (st == SWARM_OK) st = launch_coact_syrk(ctx, H, N, Npad, nruns, C, 0u);
+        if (st != SWARM_OK) return st;
+        return launch_density(ctx, C, H, N, nullptr, tau, rho_flags, rho, queue, totals);
+    }
+    st = launch_trace_build(ctx, idx, rows, H, k, N, Npad, nruns, flags, row_count);
+    if (st == SWARM_OK) st = launch_trace_totals(ctx, row_count, H, nruns, totals);
+    if (st == SWARM_OK) st = launch_thresholds(ctx, totals, H, tau, rho_flags, cstar);
+    if (st == SWARM_OK) st = launch_fill_i32(ctx, rho, (size_t)H * N, 0);
+    if (st == SWARM_OK) st = launch_coact_syrk(ctx, H, N, Npad, nruns, C, 0u, cstar, rho);
+    if (st == SWARM_OK && (rho_flags & SWARM_RHO_EXCLUDE_SELF)) st = launch_rho_exclude_self(ctx, C, H, N, cstar, rho);
+    if (st == SWARM_OK && queue) st = launch_medoid_rank(ctx, rho, H, N, queue);
+    return st;
 }
 
 swarm_status swarm_coact_density(swarm_ctx* ctx, const int32_t* C, int32_t H, int32_t N, const int64_t* totals_in,

@@ -33,14 +33,18 @@ constexpr int TRACE_SPAN = 8192;   // entries one trace-building workgroup cover
 // One workgroup per (run of 128 trace rows, head, span of entries): the 128 selections are merged
 // into an LDS image of the run's bit words, which then leaves as one contiguous, fully written block
 // (no separate clearing pass, no global atomics).
+// COUNT: also count, per trace row, the bits this workgroup sets for the first time (= the row's number
+// of distinct valid entries inside the span) and add them to row_count[h][run * 128 + row].
+template <bool COUNT>
 __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __restrict__ idx, int64_t rows, int H, int k, int N,
                                                            int Npad, int nruns, uint4* __restrict__ bits,
-                                                           uint32_t* __restrict__ dev_flags) {
-    extern __shared__ __attribute__((aligned(16))) uint32_t words[];          // [span][4]
+                                                           uint32_t* __restrict__ dev_flags, int32_t* __restrict__ row_count) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t words[];          // [span][4], then 128 row counters when COUNT
     const int run = blockIdx.x, h = blockIdx.y;
     const int e0 = blockIdx.z * TRACE_SPAN;
     const int span = min(TRACE_SPAN, Npad - e0);
-    for (int i = threadIdx.x; i < span * 4; i += blockDim.x) words[i] = 0u;
+    uint32_t* fresh = words + span * 4;
+    for (int i = threadIdx.x; i < span * 4 + (COUNT ? 128 : 0); i += blockDim.x) words[i] = 0u;
     __syncthreads();
     const int64_t row0 = (int64_t)run * 128;
     const int nrows = (int)min((int64_t)128, rows - row0);                       // <= 0 for a run of pure padding
@@ -62,7 +66,14 @@ __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __rest
         for (int u = 0; u < 4; ++u) {
             if (i0 + u * (int)blockDim.x >= total) continue;
             if (e[u] < 0 || e[u] >= N) bad = true;
-            else if (e[u] >= e0 && e[u] < e0 + span) atomicOr(&words[(e[u] - e0) * 4 + (s[u] >> 5)], 1u << trace_bit(s[u] & 31));
+            else if (e[u] >= e0 && e[u] < e0 + span) {
+                const uint32_t bit = 1u << trace_bit(s[u] & 31);
+                if (COUNT) {
+                    if (!(atomicOr(&words[(e[u] - e0) * 4 + (s[u] >> 5)], bit) & bit)) atomicAdd(&fresh[s[u]], 1u);
+                } else {
+                    atomicOr(&words[(e[u] - e0) * 4 + (s[u] >> 5)], bit);
+                }
+            }
         }
     }
     if (bad && blockIdx.z == 0) atomicOr(dev_flags, SWARM_DEV_BAD_ENTRY);
@@ -70,6 +81,29 @@ __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __rest
     uint4* out = bits + ((size_t)h * nruns + run) * Npad + e0;
     const uint4* src = reinterpret_cast<const uint4*>(words);
     for (int i = threadIdx.x; i < span; i += blockDim.x) out[i] = src[i];
+    if (COUNT && threadIdx.x < 128 && fresh[threadIdx.x])
+        atomicAdd(&row_count[((size_t)h * nruns + run) * 128 + threadIdx.x], (int32_t)fresh[threadIdx.x]);
+}
+
+// Grand total of A^T A per head, straight from the trace: the sum over trace rows of the square of the
+// row's number of activated entries (each of a row's activated pairs adds one to C).
+__global__ __launch_bounds__(256) void trace_total_kernel(const int32_t* __restrict__ row_count, int nrows, int64_t* __restrict__ totals) {
+    __shared__ int64_t part[4];
+    const int h = blockIdx.x;
+    int64_t sum = 0;
+    for (int r = threadIdx.x; r < nrows; r += 256) {
+        const int64_t n = row_count[(size_t)h * nrows + r];
+        sum += n * n;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) totals[h] = part[0] + part[1] + part[2] + part[3];
+}
+
+__global__ void fill_i32_kernel(int32_t* __restrict__ p, size_t n, int32_t v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
 // Optional validation: flags a repeated entry inside one (row, head) selection.
@@ -133,12 +167,21 @@ __device__ __forceinline__ int lds_off(int row, int piece) { return row * KC + (
 // Because the operands travel as bits, the smaller tile costs next to nothing in memory traffic.
 // Workgroups are numbered so that the eight L2 slices (one per XCD, workgroups are dealt to them
 // round-robin) each walk a contiguous run of the tile schedule.
-template <int MODE, bool VEC>
+// RHO (MODE 0, VEC): the epilogue also counts, for every row of C, the elements that reach the head's
+// threshold cstar[h] (Algorithm 1, Step 3: the density of an entry is the number of entries within the
+// radius, and "within the radius" is "count >= threshold", see the density pass).  A lane's register
+// column of the direct tile gives the counts of the mirrored tile's rows, the mirrored tile's vectors
+// give those of the direct tile's rows; a diagonal block's two tiles are computed in full, and by
+// symmetry their column counts are the block's row counts.  Counts meet in LDS and leave as one
+// atomic add per row and tile.
+template <int MODE, bool VEC, bool RHO = false>
 __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns,
                                                             int32_t* __restrict__ C, uint32_t decay_q16,
                                                             int tiles_per_head, int total_tiles, int per_xcd,
                                                             const int32_t* __restrict__ tile_order,
-                                                            uint32_t* __restrict__ dev_flags) {
+                                                            uint32_t* __restrict__ dev_flags,
+                                                            const int64_t* __restrict__ cstar, int32_t* __restrict__ rho) {
+    static_assert(!RHO || (MODE == 0 && VEC), "the fused density count belongs to the overwriting, vectorised form");
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int xcd = blockIdx.x & 7, slot_id = blockIdx.x >> 3;
     const int t = xcd * per_xcd + slot_id;
@@ -289,8 +332,30 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     const int gi_base = ti * TM + wy * 128;
     // Addresses are a wave-uniform row pointer (scalar arithmetic) plus one per-lane element offset
     // that is the same for every store of a tile.
-    const uint32_t lane_direct = (uint32_t)row_in * (uint32_t)N + col_in;
-    const uint32_t lane_mirror = (uint32_t)half * (uint32_t)N + col_in * 4;
+    // The lane part is a 32-bit BYTE offset, so that an access is "scalar base + 32-bit lane offset", the
+    // addressing form that needs no per-store 64-bit vector arithmetic and no register pair per address.
+    const uint32_t lane_direct = ((uint32_t)row_in * (uint32_t)N + col_in) * 4u;
+    const uint32_t lane_mirror = ((uint32_t)half * (uint32_t)N + col_in * 4) * 4u;
+    auto at = [](int32_t* base, uint32_t byte_off) __attribute__((always_inline)) {
+        return reinterpret_cast<int32_t*>(reinterpret_cast<char*>(base) + byte_off);
+    };
+    // density counters behind everything else in LDS: 256 direct-tile rows, then 128 direct-tile columns
+    uint32_t* cnt_row = reinterpret_cast<uint32_t*>(lds + SYRK_LDS_BYTES);
+    uint32_t* cnt_col = cnt_row + TM;
+    int32_t c32 = 0x7fffffff;                              // counts never reach it (rows <= 2^24): "nothing is within the radius"
+    if (RHO) {
+        const int64_t c = cstar[h];
+        if (c < 0x7fffffffll) c32 = (int32_t)c;
+        cnt_row[threadIdx.x] = 0u;
+        if (threadIdx.x < TN) cnt_col[threadIdx.x] = 0u;
+        __syncthreads();                                   // the waves' counts meet in these counters
+    }
+    // 1 where v >= c32, 0 elsewhere, without a compare: counts lie in [0, 2^24] and c32 in [0, 2^31), so
+    // (c32 - 1) - v cannot wrap and is negative exactly when v >= c32 (plain arithmetic: the compare form
+    // kept its lane masks in scalar registers until those ran out)
+    const int32_t c32m1 = c32 - 1;
+    auto reaches = [&](int32_t v) __attribute__((always_inline)) { return (uint32_t)(c32m1 - v) >> 31; };
+    uint32_t rowc[4] = {0u, 0u, 0u, 0u};
     bool ovf = false;
     auto combine = [&](int32_t old, int32_t v) __attribute__((always_inline)) {
         return updated_count<MODE == 0 ? 1 : MODE>(old, v, decay_q16, ovf);
@@ -315,7 +380,9 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
             }
             // direct tile: rows gi_base + 0..127, columns gj_base + 0..31
             int32_t* Cj = Ch + (size_t)gi_base * N + gj_base;                         // wave-uniform
+            if (RHO) asm volatile("" : "+s"(Cj));   // own row pointers per column block: shared ones (128 scalar registers) do not fit beside the counting
             const bool col_ok = !GUARD || gj_base + col_in < N;
+            uint32_t colc = 0u;
 #pragma unroll
             for (int ip = 0; ip < 4; ip += 2) {                                       // 32 rows x 2 in flight when C is read back
                 int32_t old[2][16];
@@ -325,7 +392,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int urow = i * 32 + (r >> 2) * 8 + (r & 3);
-                            if (col_ok && (!GUARD || gi_base + urow + row_in < N)) old[i - ip][r] = (Cj + (size_t)urow * N)[lane_direct];
+                            if (col_ok && (!GUARD || gi_base + urow + row_in < N)) old[i - ip][r] = *at(Cj + (size_t)urow * N, lane_direct);
                         }
                 }
 #pragma unroll
@@ -335,8 +402,9 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
                         const int urow = i * 32 + (r >> 2) * 8 + (r & 3);
                         int32_t* p = Cj + (size_t)urow * N;
                         if (col_ok && (!GUARD || gi_base + urow + row_in < N)) {
-                            if (MODE == 0) __builtin_nontemporal_store(acc[i][j][r], p + lane_direct);
-                            else p[lane_direct] = combine(old[i - ip][r], acc[i][j][r]);
+                            if (MODE == 0) __builtin_nontemporal_store(acc[i][j][r], at(p, lane_direct));
+                            else *at(p, lane_direct) = combine(old[i - ip][r], acc[i][j][r]);
+                            if (RHO) colc += reaches(acc[i][j][r]);
                             if (!VEC && !diag) {                                      // rows of C not 16-byte aligned: element-wise mirror
                                 int32_t* q = Ch + (size_t)(gj_base + col_in) * N + gi_base + urow + row_in;
                                 if (MODE == 0) *q = acc[i][j][r];
@@ -346,6 +414,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
                     }
                 if (MODE != 0) asm volatile("" ::: "memory");
             }
+            if (RHO) atomicAdd(&cnt_col[wx * 64 + j * 32 + col_in], colc);
             // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..127
             if (VEC && !diag) {
                 int32_t* Cm = Ch + (size_t)gj_base * N + gi_base;                     // wave-uniform
@@ -357,12 +426,16 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
                     for (int sidx = sp; sidx < sp + 8; ++sidx) {
                         v[sidx - sp] = *reinterpret_cast<const v4i*>(tbuf + (2 * sidx + half) * TROW + col_in * 16);
                         if (MODE != 0 && mcol_ok && (!GUARD || gj_base + 2 * sidx + half < N))
-                            o[sidx - sp] = *reinterpret_cast<const v4i*>(Cm + (size_t)(2 * sidx) * N + lane_mirror);
+                            o[sidx - sp] = *reinterpret_cast<const v4i*>(at(Cm + (size_t)(2 * sidx) * N, lane_mirror));
                     }
 #pragma unroll
                     for (int sidx = sp; sidx < sp + 8; ++sidx) {
                         if (mcol_ok && (!GUARD || gj_base + 2 * sidx + half < N)) {
-                            v4i* p = reinterpret_cast<v4i*>(Cm + (size_t)(2 * sidx) * N + lane_mirror);
+                            v4i* p = reinterpret_cast<v4i*>(at(Cm + (size_t)(2 * sidx) * N, lane_mirror));
+                            if (RHO) {
+                                const v4i w = v[sidx - sp];
+                                rowc[0] += reaches(w.x); rowc[1] += reaches(w.y); rowc[2] += reaches(w.z); rowc[3] += reaches(w.w);
+                            }
                             if (MODE == 0) __builtin_nontemporal_store(v[sidx - sp], p);
                             else {
                                 v4i w = v[sidx - sp];
@@ -381,6 +454,17 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     if (MODE == 0 && (ti + 1) * TM <= N && (tj + 1) * TN <= N) emit(std::false_type{});   // whole tile inside C: no per-store checks
     else emit(std::true_type{});
     if (MODE != 0 && ovf) atomicOr(dev_flags, SWARM_DEV_OVERFLOW);
+    if (RHO) {
+        if (!diag) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) atomicAdd(&cnt_row[wy * 128 + col_in * 4 + c], rowc[c]);
+        }
+        __syncthreads();
+        int32_t* rh = rho + (size_t)h * N;
+        const int u = threadIdx.x;
+        if (!diag && ti * TM + u < N && cnt_row[u]) atomicAdd(rh + ti * TM + u, (int32_t)cnt_row[u]);
+        if (u < TN && tj * TN + u < N && cnt_col[u]) atomicAdd(rh + tj * TN + u, (int32_t)cnt_col[u]);
+    }
 }
 
 // The same counts without the matrix cores: C[i][j] = sum over the trace's 32-bit words of
@@ -451,7 +535,7 @@ __global__ __launch_bounds__(256) void coact_popcount_kernel(const v4i* __restri
 }  // namespace
 
 swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
-                                int nruns, uint32_t flags) {
+                                int nruns, uint32_t flags, int32_t* row_count) {
     if (flags & SWARM_CHECK_IDX) {
         hipLaunchKernelGGL(check_distinct_kernel, dim3((unsigned)(rows * H)), dim3(256), 0, ctx->stream, idx, k,
                            ctx->dev_flags);
@@ -459,19 +543,32 @@ swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows
         if (st != SWARM_OK) return st;
     }
     const int span = Npad < TRACE_SPAN ? Npad : TRACE_SPAN;
-    const size_t lds_bytes = (size_t)span * 16;
+    const size_t lds_bytes = (size_t)span * 16 + (row_count ? 512 : 0);
     if (!ctx->trace_lds_opt_in) {                          // per context: the attribute belongs to the device the context is bound to
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trace_build_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, TRACE_SPAN * 16);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trace_build_kernel<false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, TRACE_SPAN * 16);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trace_build_kernel<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, TRACE_SPAN * 16 + 512);
         if (e != hipSuccess) {
-            snprintf(ctx->err, sizeof(ctx->err), "coact: cannot opt in to %d bytes of LDS: %s", TRACE_SPAN * 16, hipGetErrorString(e));
+            snprintf(ctx->err, sizeof(ctx->err), "coact: cannot opt in to %d bytes of LDS: %s", TRACE_SPAN * 16 + 512, hipGetErrorString(e));
             return SWARM_EHIP;
         }
         ctx->trace_lds_opt_in = true;
     }
     const dim3 grid((unsigned)nruns, (unsigned)H, (unsigned)((Npad + TRACE_SPAN - 1) / TRACE_SPAN));
-    hipLaunchKernelGGL(trace_build_kernel, grid, dim3(1024), lds_bytes, ctx->stream, idx, rows, H, k, N, Npad, nruns,
-                       reinterpret_cast<uint4*>(ctx->trace), ctx->dev_flags);
+    if (row_count) {
+        const size_t n = (size_t)H * nruns * 128;
+        hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 1023) / 1024 < 1024 ? (n + 1023) / 1024 : 1024)), dim3(1024), 0,
+                           ctx->stream, row_count, n, 0);
+        const swarm_status st = swarm_check_launch(ctx, "fill_i32_kernel");
+        if (st != SWARM_OK) return st;
+        hipLaunchKernelGGL(trace_build_kernel<true>, grid, dim3(1024), lds_bytes, ctx->stream, idx, rows, H, k, N, Npad, nruns,
+                           reinterpret_cast<uint4*>(ctx->trace), ctx->dev_flags, row_count);
+    } else {
+        hipLaunchKernelGGL(trace_build_kernel<false>, grid, dim3(1024), lds_bytes, ctx->stream, idx, rows, H, k, N, Npad, nruns,
+                           reinterpret_cast<uint4*>(ctx->trace), ctx->dev_flags, row_count);
+    }
     return swarm_check_launch(ctx, "trace_build_kernel");
 }
 
@@ -528,7 +625,21 @@ static swarm_status tile_order_for(swarm_ctx* ctx, int ntm, const int32_t** out)
     return st;
 }
 
-swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16) {
+swarm_status launch_trace_totals(swarm_ctx* ctx, const int32_t* row_count, int H, int nruns, int64_t* totals) {
+    hipLaunchKernelGGL(trace_total_kernel, dim3((unsigned)H), dim3(256), 0, ctx->stream, row_count, nruns * 128, totals);
+    return swarm_check_launch(ctx, "trace_total_kernel");
+}
+
+swarm_status launch_fill_i32(swarm_ctx* ctx, int32_t* p, size_t n, int32_t v) {
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 1023) / 1024 < 1024 ? (n + 1023) / 1024 : 1024)), dim3(1024), 0,
+                       ctx->stream, p, n, v);
+    return swarm_check_launch(ctx, "fill_i32_kernel");
+}
+
+// cstar and rho both null: plain update of C.  Both given (overwriting form, N a multiple of 4 only): the
+// epilogue adds to rho[h][i] the number of elements of row i that reach cstar[h]; rho must be zero.
+swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16,
+                               const int64_t* cstar, int32_t* rho) {
     const int ntm = Npad / TM;
     const int64_t tiles_per_head = (int64_t)ntm * (ntm + 1);
     const int64_t total = tiles_per_head * H;
@@ -542,27 +653,36 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
     const int per_xcd = (int)((total + 7) / 8);
     const int mode = decay_q16 == 0u ? 0 : decay_q16 == 65536u ? 1 : 2;
     const bool vec = (N & 3) == 0;
-    using kernel_t = void (*)(const v4i*, int, int, int, int32_t*, uint32_t, int, int, int, const int32_t*, uint32_t*);
+    const bool fused = cstar != nullptr;
+    if (fused && (!rho || mode != 0 || !vec)) {
+        snprintf(ctx->err, sizeof(ctx->err), "coact: the fused density count needs the overwriting form and N a multiple of 4");
+        return SWARM_EINVAL;
+    }
+    using kernel_t = void (*)(const v4i*, int, int, int, int32_t*, uint32_t, int, int, int, const int32_t*, uint32_t*,
+                              const int64_t*, int32_t*);
     static const kernel_t kernels[3][2] = {{coact_syrk_kernel<0, false>, coact_syrk_kernel<0, true>},
                                            {coact_syrk_kernel<1, false>, coact_syrk_kernel<1, true>},
                                            {coact_syrk_kernel<2, false>, coact_syrk_kernel<2, true>}};
+    static const kernel_t fused_kernel = coact_syrk_kernel<0, true, true>;
+    constexpr int RHO_LDS_BYTES = SYRK_LDS_BYTES + (TM + TN) * 4;
     if (!ctx->syrk_lds_opt_in) {
-        for (int m = 0; m < 3; ++m)
-            for (int v = 0; v < 2; ++v) {
-                const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[m][v]),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, SYRK_LDS_BYTES);
-                if (e != hipSuccess) {
-                    snprintf(ctx->err, sizeof(ctx->err), "coact: cannot opt in to %d bytes of LDS: %s", SYRK_LDS_BYTES, hipGetErrorString(e));
-                    return SWARM_EHIP;
-                }
-            }
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           RHO_LDS_BYTES);
+        for (int m = 0; m < 3 && e == hipSuccess; ++m)
+            for (int v = 0; v < 2 && e == hipSuccess; ++v)
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[m][v]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        SYRK_LDS_BYTES);
+        if (e != hipSuccess) {
+            snprintf(ctx->err, sizeof(ctx->err), "coact: cannot opt in to %d bytes of LDS: %s", RHO_LDS_BYTES, hipGetErrorString(e));
+            return SWARM_EHIP;
+        }
         ctx->syrk_lds_opt_in = true;
     }
     dim3 grid((unsigned)(per_xcd * 8)), block(256);
     const int tph = (int)tiles_per_head, tot = (int)total;
-    hipLaunchKernelGGL(kernels[mode][vec ? 1 : 0], grid, block, SYRK_LDS_BYTES, ctx->stream,
-                       reinterpret_cast<const v4i*>(ctx->trace), N, Npad, nruns, C, decay_q16, tph, tot, per_xcd,
-                       tile_order, ctx->dev_flags);
+    hipLaunchKernelGGL(fused ? fused_kernel : kernels[mode][vec ? 1 : 0], grid, block, fused ? RHO_LDS_BYTES : SYRK_LDS_BYTES,
+                       ctx->stream, reinterpret_cast<const v4i*>(ctx->trace), N, Npad, nruns, C, decay_q16, tph, tot, per_xcd,
+                       tile_order, ctx->dev_flags, cstar, rho);
     return swarm_check_launch(ctx, "coact_syrk_kernel");
 }
 

@@ -102,6 +102,19 @@ __global__ __launch_bounds__(256) void density_count_kernel(const int32_t* __res
     if (lane == 0) rho[(size_t)h * N + row] = count;
 }
 
+// one thread per head: the threshold of the compare-and-count form, for callers that count elsewhere
+__global__ void threshold_kernel(const int64_t* __restrict__ totals, int H, double tau, uint32_t flags, int64_t* __restrict__ cstar) {
+    const int h = blockIdx.x * blockDim.x + threadIdx.x;
+    if (h < H) cstar[h] = count_threshold(totals[h], tau, flags & SWARM_RHO_STRICT);
+}
+
+// j = i left out of the density: one less where the diagonal element itself reaches the threshold
+__global__ void rho_exclude_self_kernel(const int32_t* __restrict__ C, int N, const int64_t* __restrict__ cstar, int32_t* __restrict__ rho) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x, h = blockIdx.y;
+    if (i >= N) return;
+    if ((int64_t)C[((size_t)h * N + i) * N + i] >= cstar[h]) rho[(size_t)h * N + i] -= 1;
+}
+
 // Position of entry i in the medoid queue = entries with a higher density + entries with the same
 // density and a lower id: N^2 comparisons per head, tiled through LDS.
 __global__ __launch_bounds__(256) void medoid_rank_kernel(const int32_t* __restrict__ rho, int N, int32_t* __restrict__ queue) {
@@ -144,6 +157,21 @@ swarm_status launch_density(swarm_ctx* ctx, const int32_t* C, int H, int N, cons
     hipLaunchKernelGGL(density_count_kernel, grid, dim3(256), 0, ctx->stream, C, N, totals, tau, flags, rho);
     st = swarm_check_launch(ctx, "density_count_kernel");
     if (st != SWARM_OK || !queue) return st;
+    return launch_medoid_rank(ctx, rho, H, N, queue);
+}
+
+swarm_status launch_medoid_rank(swarm_ctx* ctx, const int32_t* rho, int H, int N, int32_t* queue) {
     hipLaunchKernelGGL(medoid_rank_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)H), dim3(256), 0, ctx->stream, rho, N, queue);
     return swarm_check_launch(ctx, "medoid_rank_kernel");
+}
+
+swarm_status launch_thresholds(swarm_ctx* ctx, const int64_t* totals, int H, double tau, uint32_t flags, int64_t* cstar) {
+    hipLaunchKernelGGL(threshold_kernel, dim3((unsigned)((H + 63) / 64)), dim3(64), 0, ctx->stream, totals, H, tau, flags, cstar);
+    return swarm_check_launch(ctx, "threshold_kernel");
+}
+
+swarm_status launch_rho_exclude_self(swarm_ctx* ctx, const int32_t* C, int H, int N, const int64_t* cstar, int32_t* rho) {
+    hipLaunchKernelGGL(rho_exclude_self_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)H), dim3(256), 0, ctx->stream, C, N, cstar,
+                       rho);
+    return swarm_check_launch(ctx, "rho_exclude_self_kernel");
 }

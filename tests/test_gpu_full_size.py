@@ -114,7 +114,14 @@ def run_full(sw, cfg, sample_steps, rng):
         assert np.array_equal(rho.cpu().numpy(), r_rho) and np.array_equal(queue.cpu().numpy(), r_queue)
         assert 0 < int(r_rho.max()) < N
         del C_host
-    del Cm
+    # build + density in one pass (the radius test inside the C kernel) against the two calls, on the device
+    tau = 1.0 - 0.25 * float(Cm.max()) / (float(T) * k * k)
+    rho2, queue2, tot2 = sw.coact_density(Cm, tau)
+    C3 = torch.empty_like(Cm)
+    rho3, queue3, tot3 = sw.coact_build_density(idx_all, N, C3, tau)
+    assert torch.equal(C3, Cm) and torch.equal(tot3, tot2) and torch.equal(rho3, rho2) and torch.equal(queue3, queue2)
+    assert 0 < int(rho3.max()) < N and sw.device_status() == 0
+    del C3, Cm
     torch.cuda.empty_cache()
 
 

@@ -434,6 +434,69 @@ def test_density_and_medoid_queue_bit_exact(sw, H, N):
     assert sw.device_status() == 0
 
 
+BUILD_DENSITY_CASES = [
+    # (rows, H, k, N): one tile, ragged tiles on a multiple of 4, several tiles with diagonal and off-diagonal
+    # blocks, a count of rows that is no multiple of the run length, N not a multiple of 4 (two-step route)
+    (40, 1, 6, 64), (70, 2, 9, 300), (96, 2, 40, 1024), (513, 1, 24, 1540), (130, 3, 11, 777), (33, 2, 7, 301),
+]
+
+
+@pytest.mark.parametrize("rows,H,k,N", BUILD_DENSITY_CASES)
+def test_build_and_density_in_one_pass_bit_exact(sw, rows, H, k, N):
+    """swarm_coact_build_density against the oracle's counts and density pass, and against the two separate calls."""
+    from paper_2603_17803_amd import binding
+    idx = W.random_selections(rows, H, k, N, seed=rows + N, topic_like=True)
+    Cm = oracle.coact_update(idx, N, nthreads=8)
+    total = rows * k * k
+    pmax = Cm.max() / total
+    idx_d = dev(idx)
+    Cd = torch.empty((H, N, N), dtype=torch.int32, device="cuda")
+    taus = [1.0, 2.0, 1.0 - 0.5 * pmax, 1.0 - 0.1 * pmax, 1.0 - 1.0 / total, 1.0 - 2.0 / total, 1.0 - 3.0 / total, 0.5, -1.0]
+    for tau in taus:
+        for rho_flags in (0, binding.SWARM_RHO_EXCLUDE_SELF, binding.SWARM_RHO_STRICT, 3):
+            Cd.fill_(-7)
+            rho, queue, tot = sw.coact_build_density(idx_d, N, Cd, tau, rho_flags=rho_flags)
+            r_rho, r_queue, r_tot = oracle.density(Cm, tau, rho_flags, nthreads=8)
+            assert np.array_equal(Cd.cpu().numpy(), Cm)
+            assert np.array_equal(tot.cpu().numpy(), r_tot) and (r_tot == total).all()
+            assert np.array_equal(rho.cpu().numpy(), r_rho), (tau, rho_flags)
+            assert np.array_equal(queue.cpu().numpy(), r_queue), (tau, rho_flags)
+    # same outputs as the two calls, queue left out
+    C2 = torch.zeros_like(Cd)
+    sw.coact_accumulate(idx_d, N, C2, decay_q16=0)
+    rho2, _, tot2 = sw.coact_density(C2, taus[3], 0, want_queue=False)
+    rho, queue, tot = sw.coact_build_density(idx_d, N, Cd, taus[3], want_queue=False)
+    assert queue is None and torch.equal(rho, rho2) and torch.equal(tot, tot2) and torch.equal(Cd, C2)
+    assert sw.device_status() == 0
+
+
+def test_build_and_density_with_skipped_and_repeated_entries(sw):
+    """The grand total comes from the trace itself, so entries that are skipped (out of range) or repeated (counted
+    once) change it exactly as they change C."""
+    from paper_2603_17803_amd import binding
+    N, H, k = 260, 2, 8
+    idx = W.random_selections(50, H, k, N, seed=9, topic_like=False)
+    idx[3, 0, 2] = N + 5              # skipped
+    idx[7, 1, 1] = idx[7, 1, 0]       # repeated
+    idx[9, 0, 4] = -3                 # skipped
+    clean_rows = []
+    A = np.zeros((H, 50, N), np.uint8)
+    for t in range(50):
+        for h in range(H):
+            for e in idx[t, h]:
+                if 0 <= e < N:
+                    A[h, t, e] = 1
+    Cm = np.stack([oracle.coact_dense(A[h]) for h in range(H)])
+    Cd = torch.empty((H, N, N), dtype=torch.int32, device="cuda")
+    tau = 1.0 - 1.5 / float(Cm[0].sum())
+    rho, queue, tot = sw.coact_build_density(dev(idx), N, Cd, tau, flags=binding.SWARM_CHECK_IDX)
+    flags = sw.device_status()
+    assert flags == binding.SWARM_DEV_BAD_ENTRY | binding.SWARM_DEV_DUP_ENTRY
+    r_rho, r_queue, r_tot = oracle.density(Cm, tau, 0, nthreads=4)
+    assert np.array_equal(Cd.cpu().numpy(), Cm) and np.array_equal(tot.cpu().numpy(), r_tot)
+    assert np.array_equal(rho.cpu().numpy(), r_rho) and np.array_equal(queue.cpu().numpy(), r_queue)
+
+
 # --------------------------------------------------------------------------- local-window cluster maintenance
 
 WINDOW_CASES = [(4, 1, 3, 8, 3, 2), (256, 8, 64, 2048, 96, 200), (300, 2, 17, 1027, 33, 61), (2048, 1, 40, 700, 5, 700)]
