@@ -379,8 +379,9 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             }
             // direct tile: rows gi_base + 0..127, columns gj_base + 0..31
-            int32_t* Cj = Ch + (size_t)gi_base * N + gj_base;                         // wave-uniform
-            if (RHO) asm volatile("" : "+s"(Cj));   // own row pointers per column block: shared ones (128 scalar registers) do not fit beside the counting
+            size_t cj_off = (size_t)gi_base * N + gj_base;                            // wave-uniform
+            if (RHO) asm volatile("" : "+s"(cj_off));   // own row pointers per column block: shared ones (128 scalar registers) do not fit beside the counting
+            int32_t* Cj = Ch + cj_off;
             const bool col_ok = !GUARD || gj_base + col_in < N;
             uint32_t colc = 0u;
 #pragma unroll
@@ -417,7 +418,9 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
             if (RHO) atomicAdd(&cnt_col[wx * 64 + j * 32 + col_in], colc);
             // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..127
             if (VEC && !diag) {
-                int32_t* Cm = Ch + (size_t)gj_base * N + gi_base;                     // wave-uniform
+                size_t cm_off = (size_t)gj_base * N + gi_base;                        // wave-uniform
+                if (RHO) asm volatile("" : "+s"(cm_off));
+                int32_t* Cm = Ch + cm_off;
                 const bool mcol_ok = !GUARD || gi_base + col_in * 4 < N;              // N is a multiple of 4 here
 #pragma unroll
                 for (int sp = 0; sp < 16; sp += 8) {
