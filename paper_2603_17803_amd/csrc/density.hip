@@ -116,28 +116,44 @@ __global__ void rho_exclude_self_kernel(const int32_t* __restrict__ C, int N, co
 }
 
 // Position of entry i in the medoid queue = entries with a higher density + entries with the same
-// density and a lower id: N^2 comparisons per head, tiled through LDS.
-__global__ __launch_bounds__(256) void medoid_rank_kernel(const int32_t* __restrict__ rho, int N, int32_t* __restrict__ queue) {
-    __shared__ int32_t tile[1024];
+// density and a lower id: N^2 comparisons per head, tiled through LDS.  A workgroup ranks 256 entries;
+// its four quarters (256 threads each) take a quarter of every staged tile of 1024 densities, and the
+// partial ranks meet in LDS: four times the waves per compute unit of one thread per entry.
+constexpr int RANK_ENTRIES = 256, RANK_PARTS = 4, RANK_TILE = 1024;
+
+__global__ __launch_bounds__(RANK_ENTRIES * RANK_PARTS) void medoid_rank_kernel(const int32_t* __restrict__ rho, int N,
+                                                                                  int32_t* __restrict__ queue) {
+    __shared__ int32_t tile[RANK_TILE];
+    __shared__ int32_t partial[RANK_PARTS - 1][RANK_ENTRIES];
     const int h = blockIdx.y;
     const int32_t* rh = rho + (size_t)h * N;
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int e = threadIdx.x % RANK_ENTRIES, part = threadIdx.x / RANK_ENTRIES;
+    const int i = blockIdx.x * RANK_ENTRIES + e;
     const int32_t mine = i < N ? rh[i] : 0;
+    constexpr int SUB = RANK_TILE / RANK_PARTS;
     int32_t rank = 0;
-    for (int j0 = 0; j0 < N; j0 += 1024) {
+    for (int j0 = 0; j0 < N; j0 += RANK_TILE) {
         __syncthreads();
-        for (int u = threadIdx.x; u < 1024; u += 256) tile[u] = (j0 + u < N) ? rh[j0 + u] : -1;
+        tile[threadIdx.x] = (j0 + (int)threadIdx.x < N) ? rh[j0 + threadIdx.x] : -1;
         __syncthreads();
-        const int lim = min(1024, N - j0);
-        // entries below i win ties, entries above lose them: count (rho_j > mine) or (rho_j == mine and j < i)
-        // as rho_j > mine - (j < i), split at j = i
-        const int below = max(0, min(lim, i - j0));
+        // this quarter's slice [s0, s0 + lim) of the tile; entries below i win ties, entries above lose them:
+        // count (rho_j >= mine) for j < i and (rho_j > mine) for j > i, split at j = i
+        const int s0 = part * SUB;
+        const int lim = max(0, min(SUB, N - j0 - s0));
+        const int below = max(0, min(lim, i - j0 - s0));
+        const int32_t* t = tile + s0;
 #pragma unroll 8
-        for (int u = 0; u < below; ++u) rank += tile[u] >= mine;
+        for (int u = 0; u < below; ++u) rank += t[u] >= mine;
 #pragma unroll 8
-        for (int u = below; u < lim; ++u) rank += tile[u] > mine;
+        for (int u = below; u < lim; ++u) rank += t[u] > mine;
     }
-    if (i < N) queue[(size_t)h * N + rank] = i;
+    if (part > 0) partial[part - 1][e] = rank;
+    __syncthreads();
+    if (part == 0 && i < N) {
+#pragma unroll
+        for (int p = 0; p < RANK_PARTS - 1; ++p) rank += partial[p][e];
+        queue[(size_t)h * N + rank] = i;
+    }
 }
 
 }  // namespace
@@ -161,7 +177,8 @@ swarm_status launch_density(swarm_ctx* ctx, const int32_t* C, int H, int N, cons
 }
 
 swarm_status launch_medoid_rank(swarm_ctx* ctx, const int32_t* rho, int H, int N, int32_t* queue) {
-    hipLaunchKernelGGL(medoid_rank_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)H), dim3(256), 0, ctx->stream, rho, N, queue);
+    hipLaunchKernelGGL(medoid_rank_kernel, dim3((unsigned)((N + RANK_ENTRIES - 1) / RANK_ENTRIES), (unsigned)H),
+                       dim3(RANK_ENTRIES * RANK_PARTS), 0, ctx->stream, rho, N, queue);
     return swarm_check_launch(ctx, "medoid_rank_kernel");
 }
 
