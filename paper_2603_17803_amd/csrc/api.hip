@@ -264,8 +264,7 @@ swarm_status swarm_coact_build_density(swarm_ctx* ctx, const int32_t* idx, int64
         return launch_density(ctx, C, H, N, nullptr, tau, rho_flags, rho, queue, totals);
     }
     st = launch_trace_build(ctx, idx, rows, H, k, N, Npad, nruns, flags, row_count);
-    if (st == SWARM_OK) st = launch_trace_totals(ctx, row_count, H, nruns, totals);
-    if (st == SWARM_OK) st = launch_thresholds(ctx, totals, H, tau, rho_flags, cstar);
+    if (st == SWARM_OK) st = launch_trace_totals_thresholds(ctx, row_count, H, nruns * 128, tau, rho_flags, totals, cstar);
     if (st == SWARM_OK) st = launch_fill_i32(ctx, rho, (size_t)H * N, 0);
     if (st == SWARM_OK) st = launch_coact_syrk(ctx, H, N, Npad, nruns, C, 0u, cstar, rho);
     if (st == SWARM_OK && (rho_flags & SWARM_RHO_EXCLUDE_SELF)) st = launch_rho_exclude_self(ctx, C, H, N, cstar, rho);

@@ -69,7 +69,16 @@ __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __rest
             else if (e[u] >= e0 && e[u] < e0 + span) {
                 const uint32_t bit = 1u << trace_bit(s[u] & 31);
                 if (COUNT) {
-                    if (!(atomicOr(&words[(e[u] - e0) * 4 + (s[u] >> 5)], bit) & bit)) atomicAdd(&fresh[s[u]], 1u);
+                    const bool first = !(atomicOr(&words[(e[u] - e0) * 4 + (s[u] >> 5)], bit) & bit);
+                    // the lanes of a wave mostly work on one trace row (k consecutive list items): one add per wave then
+                    const int s0 = __builtin_amdgcn_readfirstlane(s[u]);
+                    if (__builtin_amdgcn_ballot_w64(s[u] != s0) == 0) {
+                        const uint64_t firsts = __builtin_amdgcn_ballot_w64(first);
+                        if (firsts && (threadIdx.x & 63) == (unsigned)__builtin_ctzll(__builtin_amdgcn_ballot_w64(true)))
+                            atomicAdd(&fresh[s0], (uint32_t)__builtin_popcountll(firsts));
+                    } else if (first) {
+                        atomicAdd(&fresh[s[u]], 1u);
+                    }
                 } else {
                     atomicOr(&words[(e[u] - e0) * 4 + (s[u] >> 5)], bit);
                 }
@@ -83,23 +92,6 @@ __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __rest
     for (int i = threadIdx.x; i < span; i += blockDim.x) out[i] = src[i];
     if (COUNT && threadIdx.x < 128 && fresh[threadIdx.x])
         atomicAdd(&row_count[((size_t)h * nruns + run) * 128 + threadIdx.x], (int32_t)fresh[threadIdx.x]);
-}
-
-// Grand total of A^T A per head, straight from the trace: the sum over trace rows of the square of the
-// row's number of activated entries (each of a row's activated pairs adds one to C).
-__global__ __launch_bounds__(256) void trace_total_kernel(const int32_t* __restrict__ row_count, int nrows, int64_t* __restrict__ totals) {
-    __shared__ int64_t part[4];
-    const int h = blockIdx.x;
-    int64_t sum = 0;
-    for (int r = threadIdx.x; r < nrows; r += 256) {
-        const int64_t n = row_count[(size_t)h * nrows + r];
-        sum += n * n;
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) totals[h] = part[0] + part[1] + part[2] + part[3];
 }
 
 __global__ void fill_i32_kernel(int32_t* __restrict__ p, size_t n, int32_t v) {
@@ -626,11 +618,6 @@ static swarm_status tile_order_for(swarm_ctx* ctx, int ntm, const int32_t** out)
     free(host);
     *out = dev;
     return st;
-}
-
-swarm_status launch_trace_totals(swarm_ctx* ctx, const int32_t* row_count, int H, int nruns, int64_t* totals) {
-    hipLaunchKernelGGL(trace_total_kernel, dim3((unsigned)H), dim3(256), 0, ctx->stream, row_count, nruns * 128, totals);
-    return swarm_check_launch(ctx, "trace_total_kernel");
 }
 
 swarm_status launch_fill_i32(swarm_ctx* ctx, int32_t* p, size_t n, int32_t v) {

@@ -76,11 +76,11 @@ swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, in
 bool select_uses_slices(int64_t rows, int N, int k);   // long rows, few of them: sliced two-stage selection
 swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
                                 int nruns, uint32_t flags, int32_t* row_count = nullptr);   // row_count: int32 [H][nruns*128] out, optional
-swarm_status launch_trace_totals(swarm_ctx* ctx, const int32_t* row_count, int H, int nruns, int64_t* totals);
+swarm_status launch_trace_totals_thresholds(swarm_ctx* ctx, const int32_t* row_count, int H, int nrows, double tau, uint32_t flags,
+                                            int64_t* totals, int64_t* cstar);
 swarm_status launch_fill_i32(swarm_ctx* ctx, int32_t* p, size_t n, int32_t v);
 swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16,
                                const int64_t* cstar = nullptr, int32_t* rho = nullptr);
-swarm_status launch_thresholds(swarm_ctx* ctx, const int64_t* totals, int H, double tau, uint32_t flags, int64_t* cstar);
 swarm_status launch_rho_exclude_self(swarm_ctx* ctx, const int32_t* C, int H, int N, const int64_t* cstar, int32_t* rho);
 swarm_status launch_medoid_rank(swarm_ctx* ctx, const int32_t* rho, int H, int N, int32_t* queue);
 swarm_status launch_coact_popcount(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16);

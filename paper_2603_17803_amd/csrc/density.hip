@@ -102,10 +102,27 @@ __global__ __launch_bounds__(256) void density_count_kernel(const int32_t* __res
     if (lane == 0) rho[(size_t)h * N + row] = count;
 }
 
-// one thread per head: the threshold of the compare-and-count form, for callers that count elsewhere
-__global__ void threshold_kernel(const int64_t* __restrict__ totals, int H, double tau, uint32_t flags, int64_t* __restrict__ cstar) {
-    const int h = blockIdx.x * blockDim.x + threadIdx.x;
-    if (h < H) cstar[h] = count_threshold(totals[h], tau, flags & SWARM_RHO_STRICT);
+// Grand total of A^T A per head straight from the trace, and the threshold that goes with it, for a
+// build that counts the density in its own epilogue: total = sum over trace rows of the square of the
+// row's number of activated entries (each of a row's activated pairs adds one to C).
+__global__ __launch_bounds__(256) void trace_total_threshold_kernel(const int32_t* __restrict__ row_count, int nrows, double tau,
+                                                                    uint32_t flags, int64_t* __restrict__ totals,
+                                                                    int64_t* __restrict__ cstar) {
+    __shared__ int64_t part[4];
+    const int h = blockIdx.x;
+    int64_t sum = 0;
+    for (int r = threadIdx.x; r < nrows; r += 256) {
+        const int64_t n = row_count[(size_t)h * nrows + r];
+        sum += n * n;
+    }
+    sum = wave_sum_i64(sum);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int64_t total = part[0] + part[1] + part[2] + part[3];
+        totals[h] = total;
+        cstar[h] = count_threshold(total, tau, flags & SWARM_RHO_STRICT);
+    }
 }
 
 // j = i left out of the density: one less where the diagonal element itself reaches the threshold
@@ -182,9 +199,11 @@ swarm_status launch_medoid_rank(swarm_ctx* ctx, const int32_t* rho, int H, int N
     return swarm_check_launch(ctx, "medoid_rank_kernel");
 }
 
-swarm_status launch_thresholds(swarm_ctx* ctx, const int64_t* totals, int H, double tau, uint32_t flags, int64_t* cstar) {
-    hipLaunchKernelGGL(threshold_kernel, dim3((unsigned)((H + 63) / 64)), dim3(64), 0, ctx->stream, totals, H, tau, flags, cstar);
-    return swarm_check_launch(ctx, "threshold_kernel");
+swarm_status launch_trace_totals_thresholds(swarm_ctx* ctx, const int32_t* row_count, int H, int nrows, double tau, uint32_t flags,
+                                            int64_t* totals, int64_t* cstar) {
+    hipLaunchKernelGGL(trace_total_threshold_kernel, dim3((unsigned)H), dim3(256), 0, ctx->stream, row_count, nrows, tau, flags,
+                       totals, cstar);
+    return swarm_check_launch(ctx, "trace_total_threshold_kernel");
 }
 
 swarm_status launch_rho_exclude_self(swarm_ctx* ctx, const int32_t* C, int H, int N, const int64_t* cstar, int32_t* rho) {
