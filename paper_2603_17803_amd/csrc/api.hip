@@ -321,7 +321,7 @@ static swarm_status check_map_args(swarm_ctx* ctx, const char* fn, int64_t group
                      Nc, cap);
     if (R < 1 || R > D || D > 64) SWARM_REJECT(ctx, "%s: need 1 <= R=%d <= D=%d <= 64", fn, R, D);
     if (Nc > (1 << 20)) SWARM_REJECT(ctx, "%s: Nc=%d above 2^20", fn, Nc);
-    const size_t lds = ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + 64) * 4;
+    const size_t lds = map_lds_base_bytes(Nc, cap);
     if (lds > 64u * 1024u)
         SWARM_REJECT(ctx, "%s: cap=%d and Nc=%d need %zu bytes of on-chip staging (limit 64 KiB)", fn, cap, Nc, lds);
     return SWARM_OK;

@@ -84,6 +84,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
 swarm_status launch_rho_exclude_self(swarm_ctx* ctx, const int32_t* C, int H, int N, const int64_t* cstar, int32_t* rho);
 swarm_status launch_medoid_rank(swarm_ctx* ctx, const int32_t* rho, int H, int N, int32_t* queue);
 swarm_status launch_coact_popcount(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16);
+size_t map_lds_base_bytes(int Nc, int cap);   // on-chip staging of the mapping step before any table is staged
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                         const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap);

@@ -25,6 +25,7 @@ struct MapArgs {
     const int32_t* sel; int S; int H; int N; const int32_t* e2c; int Nc; const int32_t* replicas; int R; int D;
     const int32_t* weight; const uint32_t* resident; int32_t* q_off; int32_t* q_cluster; int32_t* q_load; int cap;
     uint32_t* dev_flags;
+    int split_off;      // word offset of the 2 * cap words the split into independent sub-problems needs; 0 = no room, never split
 };
 
 // Chain over items [0, m) in visiting order.  keybase = (load << 6) | lane.  On return assign[i]
@@ -109,7 +110,17 @@ __device__ __forceinline__ void greedy_chain_wide(uint32_t m, int lane, const ui
     }
 }
 
+__device__ __forceinline__ void run_chain_packed(int D, uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
+                                                 const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign, uint32_t& keybase,
+                                                 uint32_t& cnt) {
+    if (D <= 4) greedy_chain_packed<2>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
+    else if (D <= 8) greedy_chain_packed<3>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
+    else if (D <= 16) greedy_chain_packed<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
+    else greedy_chain_packed<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
+}
+
 constexpr int MAP_THREADS = 256;
+constexpr uint32_t MAP_SPLIT_MIN_ITEMS = 96;     // below this a single chain is shorter than finding the sub-problems
 
 // Copies n words from global memory to LDS with batches of independent loads (all loads of a batch
 // are in flight together, so a small table costs one memory round trip).  16-byte loads when the
@@ -152,8 +163,11 @@ __device__ __forceinline__ void stage_words(int32_t* __restrict__ dst, const int
 }
 
 // LDS layout shared by the stand-alone and the fused kernel.
+constexpr int MAP_AUX_WORDS = 8 * 64;        // off, adj_lo, adj_hi, comp_of, seg_off, seg_cnt, pub_load, pub_cnt: 64 words each
+
 struct MapLds {
-    uint32_t *bitmap, *list, *mask_lo, *mask_hi, *wgt, *order, *assign, *off;
+    uint32_t *bitmap, *list, *mask_lo, *mask_hi, *wgt, *order, *assign, *order2, *comp_item, *off;
+    uint32_t *adj_lo, *adj_hi, *comp_of, *seg_off, *seg_cnt, *pub_load, *pub_cnt;
     int32_t *s_e2c, *s_rep, *s_wgt;
     int nwords;
     __device__ __forceinline__ MapLds(uint32_t* smem, const MapArgs& a, int stage_e2c, int stage_tab) {
@@ -165,8 +179,17 @@ struct MapLds {
         wgt = mask_hi + a.cap;
         order = wgt + a.cap;
         assign = order + a.cap;
-        off = assign + a.cap;                 // 64 words
-        s_e2c = reinterpret_cast<int32_t*>(smem + ((off + 64 - smem + 3) & ~3));   // N words when staged (16-byte aligned)
+        off = assign + a.cap;                 // MAP_AUX_WORDS words from here
+        order2 = smem + a.split_off;          // visiting order regrouped by independent sub-problem (only when split_off != 0)
+        comp_item = order2 + a.cap;           // sub-problem of every item
+        adj_lo = off + 64;
+        adj_hi = adj_lo + 64;
+        comp_of = adj_hi + 64;
+        seg_off = comp_of + 64;
+        seg_cnt = seg_off + 64;
+        pub_load = seg_cnt + 64;
+        pub_cnt = pub_load + 64;
+        s_e2c = reinterpret_cast<int32_t*>(smem + ((off + MAP_AUX_WORDS - smem + 3) & ~3));   // N words when staged (16-byte aligned)
         s_rep = s_e2c + (stage_e2c ? ((a.N + 3) & ~3) : 0);                // Nc*R words when staged
         s_wgt = s_rep + (stage_tab ? ((a.Nc * a.R + 3) & ~3) : 0);         // Nc words when staged
     }
@@ -184,7 +207,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     const MapLds L(smem, a, stage_e2c, stage_tab);
     const int nwords = L.nwords;
     uint32_t *bitmap = L.bitmap, *list = L.list, *mask_lo = L.mask_lo, *mask_hi = L.mask_hi, *wgt = L.wgt, *order = L.order,
-             *assign = L.assign, *off = L.off;
+             *assign = L.assign, *off = L.off, *order2 = L.order2;
     int32_t *s_e2c = L.s_e2c, *s_rep = L.s_rep, *s_wgt = L.s_wgt;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -237,13 +260,26 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     }
     __syncthreads();
 
-    if (wave != 0) {                                 // the rest is single-wave work
+    // Every wave counts the merged clusters (a popcount of the bitmap).  Few of them: wave 0 does all the rest
+    // alone, as one chain.  Many: wave 0 compacts, orders and looks for independent sub-problems, whose chains
+    // then run side by side on the other waves; all waves meet at the barriers in between (the decision is
+    // the same in every wave, so either all of them go to the barriers or none).
+    uint32_t m_all = 0;
+    for (int w0 = 0; w0 < nwords; w0 += 64) m_all += (w0 + lane < nwords) ? __popc(bitmap[w0 + lane]) : 0;
+    {
+        uint32_t total;
+        (void)wave_excl_scan(m_all, &total);
+        m_all = min(total, (uint32_t)a.cap);
+    }
+    const bool try_split = NT > 64 && a.split_off != 0 && m_all >= MAP_SPLIT_MIN_ITEMS;
+    if (wave != 0 && !try_split) {
         if (flags) atomicOr(a.dev_flags, flags);
         return;
     }
-
+    uint32_t m = 0, load = 0, cnt = 0, wsum = 0;
+    const int D = a.D;
+    if (wave == 0) {
     // compaction in ascending cluster id
-    uint32_t m = 0;
     for (int w0 = 0; w0 < nwords; w0 += 64) {
         const int w = w0 + lane;
         uint32_t bits = (w < nwords) ? bitmap[w] : 0u;
@@ -261,7 +297,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
     // per item: candidate SSD mask, weight, replication factor
-    uint32_t rf_min = INF32, rf_max = 0, wsum = 0;
+    uint32_t rf_min = INF32, rf_max = 0;
     for (uint32_t i = lane; i < m; i += 64) {
         const uint32_t c = list[i];
         const int64_t gc = cbase + c;
@@ -316,21 +352,110 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
-    // greedy least-loaded assignment
-    uint32_t load = 0, cnt = 0;
-    const int D = a.D;
-    if (wsum < (1u << 26)) {
-        uint32_t keybase = (uint32_t)lane;
-        if (D <= 4) greedy_chain_packed<2>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
-        else if (D <= 8) greedy_chain_packed<3>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
-        else if (D <= 16) greedy_chain_packed<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
-        else greedy_chain_packed<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
-        load = keybase >> 6;
-    } else {
-        if (D <= 16) greedy_chain_wide<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
-        else greedy_chain_wide<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
+    // Independent sub-problems: two SSDs interact only through an item that has both as candidates, so the
+    // connected components of "share a routed item" never meet in a comparison and their chains can run side
+    // by side, each in the visiting order of its own items (an SSD's bucket is filled by one component only,
+    // so bucket positions are unchanged).  Lane d holds the set of SSDs reachable from d; Warshall's closure
+    // by rows; a component is named by its lowest SSD.
+    uint32_t ncomp = 1;
+    if (try_split && wsum < (1u << 26)) {
+        L.adj_lo[lane] = 0u;
+        L.adj_hi[lane] = 0u;
+        L.seg_cnt[lane] = 0u;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        for (uint32_t i = lane; i < m; i += 64) {
+            const uint32_t lo = mask_lo[i], hi = mask_hi[i];
+            uint64_t bits = ((uint64_t)hi << 32) | lo;
+            while (bits) {
+                const int d = __ffsll((unsigned long long)bits) - 1;
+                bits &= bits - 1;
+                if (lo) atomicOr(&L.adj_lo[d], lo);
+                if (hi) atomicOr(&L.adj_hi[d], hi);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        uint64_t reach = ((uint64_t)L.adj_hi[lane] << 32) | L.adj_lo[lane];
+        const bool active = reach != 0ull;           // some routed item has SSD `lane` as a candidate (then reach holds lane itself)
+        for (int kk = 0; kk < D; ++kk) {
+            const uint64_t rk = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(reach >> 32), kk) << 32) |
+                                (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)reach, kk);
+            if ((reach >> kk) & 1ull) reach |= rk;
+        }
+        const int rep = active ? __ffsll((unsigned long long)reach) - 1 : 64;
+        const uint64_t reps = __ballot(active && rep == lane);
+        ncomp = (uint32_t)__popcll(reps);
+        L.comp_of[lane] = active ? (uint32_t)__popcll(reps & ((1ull << rep) - 1ull)) : 0xffu;
     }
+    if (lane == 0) off[0] = ncomp;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    if (ncomp <= 1) {
+        // greedy least-loaded assignment, one chain
+        if (wsum < (1u << 26)) {
+            uint32_t keybase = (uint32_t)lane;
+            run_chain_packed(D, m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt);
+            load = keybase >> 6;
+        } else {
+            if (D <= 16) greedy_chain_wide<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
+            else greedy_chain_wide<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
+        }
+    }
+    if (lane == 0) off[1] = m;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    }   // wave 0
+    uint32_t ncomp = 1;
+    if (try_split) {
+        __syncthreads();
+        ncomp = off[0];
+        if (ncomp > 1) {
+            // all threads: the component of every item, and the components' sizes
+            const uint32_t mm = off[1];
+            for (uint32_t i = tid; i < mm; i += NT) {
+                const uint64_t mk = ((uint64_t)mask_hi[i] << 32) | mask_lo[i];
+                const uint32_t c = mk ? L.comp_of[__ffsll((unsigned long long)mk) - 1] : 0xffu;
+                L.comp_item[i] = c;
+                if (mk) atomicAdd(&L.seg_cnt[c], 1u);
+            }
+            __syncthreads();
+            // component c on wave c mod (number of waves): the wave gathers the component's items in visiting
+            // order (stable), then runs their chain; a wave that gets several components runs them one after the
+            // other on the same registers (their SSDs are disjoint)
+            constexpr uint32_t NW = NT / 64;
+            uint32_t routed;
+            const uint32_t seg = wave_excl_scan(L.seg_cnt[lane], &routed);      // lanes >= ncomp hold 0
+            uint32_t keybase = (uint32_t)lane, mycnt = 0;
+            for (uint32_t c = (uint32_t)wave; c < ncomp; c += NW) {
+                const uint32_t base = (uint32_t)__builtin_amdgcn_readlane((int)seg, (int)c);
+                uint32_t run = 0;
+                for (uint32_t i0 = 0; i0 < mm; i0 += 64) {
+                    const uint32_t i = i0 + lane;
+                    const uint32_t it = i < mm ? order[i] : 0u;
+                    const bool hit = i < mm && L.comp_item[it] == c;
+                    const uint64_t b = __ballot(hit);
+                    if (hit) order2[base + run + (uint32_t)__popcll(b & ((1ull << lane) - 1ull))] = it;
+                    run += (uint32_t)__popcll(b);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+                run_chain_packed(D, run, lane, order2 + base, mask_lo, mask_hi, wgt, assign, keybase, mycnt);
+            }
+            if (lane < D) {
+                const uint32_t c = L.comp_of[lane];
+                if (c != 0xffu && c % NW == (uint32_t)wave) {
+                    L.pub_load[lane] = keybase >> 6;
+                    L.pub_cnt[lane] = mycnt;
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (wave != 0) {                                 // emission is single-wave work
+        if (flags) atomicOr(a.dev_flags, flags);
+        return;
+    }
+    if (ncomp > 1) {
+        const bool active = lane < D && L.comp_of[lane] != 0xffu;
+        load = active ? L.pub_load[lane] : 0u;
+        cnt = active ? L.pub_cnt[lane] : 0u;
+    }
 
     // emit buckets SSD-major, insertion order inside a bucket
     uint32_t total;
@@ -414,12 +539,12 @@ __global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __
 
 }  // namespace
 
-size_t map_lds_base_bytes(int Nc, int cap) { return ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + 64) * 4; }
+size_t map_lds_base_bytes(int Nc, int cap) { return ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + MAP_AUX_WORDS) * 4; }
 
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                         const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap) {
-    MapArgs a{sel, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags};
+    MapArgs a{sel, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0};
     size_t lds = map_lds_base_bytes(Nc, cap);
     const size_t budget = 64u * 1024u;
     int stage_tab = 0, stage_e2c = 0;
@@ -427,6 +552,7 @@ swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int 
     lds = (lds + 15) / 16 * 16;
     if (lds + tab_bytes <= budget) { stage_tab = 1; lds += tab_bytes; }
     if (lds + e2c_bytes <= budget) { stage_e2c = 1; lds += e2c_bytes; }
+    if (lds + (size_t)cap * 8 <= budget) { a.split_off = (int)(lds / 4); lds += (size_t)cap * 8; }
     hipLaunchKernelGGL(map_requests_kernel, dim3((unsigned)groups), dim3(MAP_THREADS), lds, ctx->stream, a, stage_e2c,
                        stage_tab);
     return swarm_check_launch(ctx, "map_requests_kernel");
@@ -442,7 +568,7 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
     *launched = false;
     if (N > 64 * selcore::NT || select_uses_slices(H, N, k)) return SWARM_OK;   // long rows: the sliced selection is faster than fusing
     constexpr int NT = selcore::NT;
-    MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags};
+    MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0};
     size_t lds = map_lds_base_bytes(Nc, cap);
     const size_t budget = 64u * 1024u;
     lds = (lds + 15) / 16 * 16;
@@ -456,6 +582,8 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
     const int sel_off = (int)(lds / 4);
     lds += (size_t)k * 4;
     if (lds > budget) return SWARM_OK;
+    lds = (lds + 15) / 16 * 16;
+    if (lds + (size_t)cap * 8 <= budget) { a.split_off = (int)(lds / 4); lds += (size_t)cap * 8; }
     const dim3 grid((unsigned)H), block(NT);
     hipStream_t st = ctx->stream;
 #define SWARM_SELMAP(IPT) hipLaunchKernelGGL(select_map_kernel<IPT>, grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off)

@@ -319,6 +319,31 @@ def test_map_variable_replication_and_heavy_weights(sw):
         run_map(sw, sel, H, N, e2c, Nc, rep, D, weight)
 
 
+@pytest.mark.parametrize("D,F,Nc,S", [(8, 2, 500, 3000), (12, 3, 700, 4000), (40, 5, 900, 6000), (64, 8, 1200, 8000), (8, 8, 300, 2000)])
+def test_map_independent_ssd_families_run_side_by_side(sw, D, F, Nc, S):
+    """Many merged clusters whose replica sets fall into F families of SSDs that share nothing: the device runs one
+    chain per family side by side (more families than waves included), and the queues are still the sequential
+    greedy's.  Variable replication factors keep the replication-factor sort active; SSD ids beyond 31 use the
+    upper mask word; one family of single-copy clusters needs no choice at all."""
+    rng = np.random.default_rng(D * 100 + F)
+    H, N, R = 2, 3000, 4
+    e2c = rng.integers(0, Nc, size=(H, N)).astype(np.int32)
+    rep = np.full((H * Nc, R), -1, np.int32)
+    fam_size = D // F
+    for c in range(H * Nc):
+        fam = c % F
+        ssds = fam + F * np.arange(fam_size)                       # family fam: SSDs fam, fam + F, fam + 2F, ...
+        rf = int(rng.integers(1, min(R, fam_size) + 1))
+        slots = rng.permutation(R)[:rf]
+        rep[c, slots] = rng.permutation(ssds)[:rf]
+    sel = rng.integers(0, N, size=(6, S)).astype(np.int32)
+    sel[0, ::3] = -1                                               # ragged group
+    weight = rng.integers(1, 50, size=H * Nc).astype(np.int32)
+    res = rng.integers(0, 2 ** 32, (H * Nc + 31) // 32, dtype=np.uint32) & rng.integers(0, 2 ** 32, (H * Nc + 31) // 32, dtype=np.uint32)
+    run_map(sw, sel, H, N, e2c, Nc, rep, D, weight)
+    run_map(sw, sel, H, N, e2c, Nc, rep, D, None, resident=res)
+
+
 def test_map_identity_clusters_is_entry_level_scheduling(sw):
     N, D, R = 4096, 8, 3
     cfg = W.CONFIGS["long_128k"].scaled(N=N, Nc=N, M=N, H=1)
