@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 INT8_MFMA_PEAK_TOPS = 5000.0
 # HBM bytes per score_kernel launch from FETCH_SIZE / WRITE_SIZE counter runs, calibrated on plain copies
 # (profiles/score_kernel_long_128k_hbm_traffic.txt).  Valid for the kernel as profiled; None for other workloads.
-SCORE_KERNEL_HBM_TRAFFIC = {"long_128k": 33879000}
+SCORE_KERNEL_HBM_TRAFFIC = {"long_128k": 33892000}
 
 
 def main():
