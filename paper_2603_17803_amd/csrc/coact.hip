@@ -21,12 +21,14 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
-// Position, inside its 32-bit word, of the bit of trace row r (0..31) of the word's group: row 4q + b is
-// bit 8b + q, i.e. four consecutive rows are the same bit of the four bytes.  Any fixed order serves the
-// counts (both operands of a product, and both sides of an AND + popcount, use the same one); this one
-// makes the expansion to bytes a shift and a mask.
-__device__ __forceinline__ int trace_bit(int r) { return 8 * (r & 3) + (r >> 2); }
+// Position, inside its 32-bit word, of the bit of trace row r (0..31) of the word's group: row 8q + b is
+// bit 4b + q, i.e. eight consecutive rows are the same bit of the word's eight nibbles.  Any fixed order
+// serves the counts (both operands of a product, and both sides of an AND + popcount, use the same one);
+// this one makes the expansion to 4-bit operands a shift and a mask.
+__device__ __forceinline__ int trace_bit(int r) { return 4 * (r & 7) + (r >> 3); }
 
 constexpr int TRACE_SPAN = 8192;   // entries one trace-building workgroup covers (128 KiB of LDS)
 
@@ -127,7 +129,7 @@ __device__ __forceinline__ int32_t updated_count(int32_t old, int32_t v, uint32_
 
 constexpr int TM = 256;                        // C tile rows per workgroup
 constexpr int TN = 128;                        // C tile columns per workgroup
-constexpr int KC = 64;                         // trace rows (= contraction bytes) per chunk: two 32-byte MFMA k-steps
+constexpr int KC = 64;                         // contraction BYTES per chunk and operand row: 128 trace rows as 4-bit values, two MFMA k-steps of 64
 constexpr int A_BYTES = TM * KC;               // operand panels of one chunk in LDS
 constexpr int B_BYTES = TN * KC;
 constexpr int BUF_BYTES = A_BYTES + B_BYTES;   // 24 KiB; two of them form the ring
@@ -145,16 +147,22 @@ static_assert(SYRK_LDS_BYTES >= 2 * BUF_BYTES, "operand ring must fit");
 __device__ __forceinline__ int lds_swz(int row) { return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1); }
 __device__ __forceinline__ int lds_off(int row, int piece) { return row * KC + ((piece ^ lds_swz(row)) << 4); }
 
-// Expansion of trace bits to bytes of 0/1: the rows of a 32-row group sit in their word so that the four
-// consecutive rows of an output dword are the same bit of the word's four bytes (trace_bit above), and
-// (w >> j) & 0x01010101 is the whole expansion of four rows.
+// The matrix-core instruction is v_mfma_f32_32x32x64_f8f6f4 in its 4-bit form (E2M1): 0 and 1 are
+// exact in it, products of them are exact, and the fp32 accumulators hold every integer up to 2^24
+// exactly -- a call accumulates at most 2^24 trace rows, so the counts are exact, at twice the rate of
+// the int8 instruction and with half the operand bytes.  Lane l of an operand holds row l%32, contraction
+// indices [32 (l/32), +32) as 32 nibbles (16 bytes); 1.0 is the nibble 0b0010.  Both block scales are
+// 2^0 (E8M0 byte 127).
+// Expansion of trace bits to nibbles: the rows of a 32-row group sit in their word so that the eight
+// consecutive rows of an output dword are the same bit of the word's eight nibbles (trace_bit above),
+// and ((w << 1) >> q) & 0x22222222 is the whole expansion of eight rows.
 
 // C tile of 256 x 128 per workgroup of 4 waves (2 x 2, each 128 x 64 = 4 x 2 MFMA tiles, 128
 // accumulator registers), two workgroups per compute unit: while one waits at its hand-over barrier,
 // writes its tile or starts up, the other keeps the matrix cores busy.  The contraction runs in
-// chunks of 64 trace rows through a two-deep LDS ring: thread t owns row t of the A panel and half
-// of row t/2 of the B panel; the bit words of the next runs of 128 trace rows are in flight from
-// memory (three runs ahead), those of chunk c+1 are being expanded and written into the idle LDS buffer, chunk c feeds the matrix
+// chunks of 128 trace rows (one 16-byte bit word per entry) through a two-deep LDS ring: thread t owns row t
+// of the A panel and half of row t/2 of the B panel; the bit words of the next chunks are in flight from
+// memory (three chunks ahead), those of chunk c+1 are being expanded and written into the idle LDS buffer, chunk c feeds the matrix
 // cores; operand fragments of k-step s+1 are read from LDS while the MFMAs of k-step s run.
 // Because the operands travel as bits, the smaller tile costs next to nothing in memory traffic.
 // Workgroups are numbered so that the eight L2 slices (one per XCD, workgroups are dealt to them
@@ -187,47 +195,50 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wy = wave >> 1, wx = wave & 1;
 
-    // memory -> registers, one 16-byte word (a run of 128 trace rows = two chunks) per panel row at a
+    // memory -> registers, one 16-byte word (a run of 128 trace rows = one chunk) per panel row at a
     // time: thread t takes row t of the A panel and row t/2 of the B panel, of which it expands the
-    // half t%2 of either chunk.  Four register sets, indexed by run number mod 4.
+    // half t%2.  Four register sets, indexed by run number mod 4.
     const v4i* panel = bits + (size_t)h * nruns * Npad;
     const v4i* a_src = panel + (size_t)ti * TM + tid;
     const v4i* b_src = panel + (size_t)tj * TN + (tid >> 1);
     const bool odd = tid & 1;
     v4i ba[4], bb[4];
-    const size_t last_off = (size_t)(nruns - 1) * Npad;
+    const int last_run = nruns - 1;
     auto load_bits = [&](int set, int run) __attribute__((always_inline)) {           // clamped: a redundant reload past the end is harmless
-        const size_t off = run < nruns ? (size_t)run * Npad : last_off;
+        const size_t off = (size_t)min(run, last_run) * Npad;                           // a minimum, not a select: no branch inside the loop
         ba[set] = a_src[off];
         bb[set] = b_src[off];
     };
-    // registers -> LDS, in pieces of 16 contraction bytes: pieces 0..3 are the A row's, 4..5 the two of
-    // the B half row.  A piece is expanded one dword (4 trace rows) at a time and stored when complete.
+    // registers -> LDS, in pieces of 16 contraction bytes (32 trace rows = one 32-bit word of the run):
+    // pieces 0..3 are the A row's, 4..5 the two of the B half row.  A piece is expanded one dword (8 trace
+    // rows) at a time and stored when complete.
     int st_off[6];
 #pragma unroll
     for (int p = 0; p < 4; ++p) st_off[p] = lds_off(tid, p);
 #pragma unroll
     for (int q = 0; q < 2; ++q) st_off[4 + q] = A_BYTES + lds_off(tid >> 1, 2 * (tid & 1) + q);
     v4i ex;
-    uint32_t bw;                                   // the thread's half of the B row's word for the chunk being expanded
-    auto pick_b = [&](int set, int half) __attribute__((always_inline)) {
-        bw = (uint32_t)(odd ? bb[set][2 * half + 1] : bb[set][2 * half]);
+    uint32_t bw[2];                                // the thread's half of the B row's words for the chunk being expanded
+    auto pick_b = [&](int set) __attribute__((always_inline)) {
+        bw[0] = (uint32_t)(odd ? bb[set][2] : bb[set][0]);
+        bw[1] = (uint32_t)(odd ? bb[set][3] : bb[set][1]);
     };
-    auto expand_quarter = [&](int set, int half, int piece, int q) __attribute__((always_inline)) {
-        const uint32_t w = piece < 4 ? (uint32_t)ba[set][2 * half + (piece >> 1)] : bw;
-        ex[q] = (int)((w >> (4 * (piece & 1) + q)) & 0x01010101u);
+    auto expand_quarter = [&](int set, int piece, int q) __attribute__((always_inline)) {
+        const uint32_t w = piece < 4 ? (uint32_t)ba[set][piece] : bw[piece - 4];
+        ex[q] = (int)((q ? w >> (q - 1) : w << 1) & 0x22222222u);
     };
     auto store_piece = [&](int buf, int piece) __attribute__((always_inline)) {
         *reinterpret_cast<v4i*>(lds + buf * BUF_BYTES + st_off[piece]) = ex;
     };
 
-    v16i acc[4][2];
+    v16f facc[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+            for (int r = 0; r < 16; ++r) facc[i][j][r] = 0.f;
+    const int unit_scale = 0x7f7f7f7f;             // E8M0 127 = 2^0 in every byte the instruction may pick
 
     // fragment addressing: lane l reads row l%32 of an MFMA tile, bytes [16*(l/32), +16) of the 32-byte
     // k-step.  The swizzle term is the same for rows 32 apart; the tile index is a constant byte offset.
@@ -247,48 +258,49 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
         else fa[set][f - 2] = *reinterpret_cast<const v4i*>(base + fa_base[ks] + (f - 2) * 32 * KC);
     };
     auto mfma = [&](int set, int m) __attribute__((always_inline)) {
-        acc[m >> 1][m & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][m >> 1], fb[set][m & 1], acc[m >> 1][m & 1], 0, 0, 0);
+        const v4i a4 = fa[set][m >> 1], b4 = fb[set][m & 1];
+        const v8i a8 = {a4.x, a4.y, a4.z, a4.w, 0, 0, 0, 0}, b8 = {b4.x, b4.y, b4.z, b4.w, 0, 0, 0, 0};   // the 4-bit form reads 4 registers
+        facc[m >> 1][m & 1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, facc[m >> 1][m & 1], 4, 4, 0, unit_scale, 0,
+                                                                             unit_scale);
     };
 
     load_bits(0, 0);
     load_bits(1, 1);
     load_bits(2, 2);
-    pick_b(0, 0);
+    pick_b(0);
 #pragma unroll
     for (int piece = 0; piece < 6; ++piece) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) expand_quarter(0, 0, piece, q);
+        for (int q = 0; q < 4; ++q) expand_quarter(0, piece, q);
         store_piece(0, piece);
     }
     __syncthreads();
 #pragma unroll
     for (int f = 0; f < 6; ++f) read_frag(0, 0, 0, f);
 
-    // Chunk `half` of run d computes out of LDS buffer `half`; its own bits are spent.  The next chunk
-    // (the run's second half, or the first half of run d+1 in register set (d+1)%4) is expanded into
-    // the other LDS buffer, which no wave reads after the hand-over barrier of the previous chunk; set
-    // (d+3)%4 is refilled at the start of the run, three runs (6 chunks) ahead of its use.  The work is
-    // laid out as 16 slots, one per MFMA: slot m issues the MFMA, then a
+    // Chunk d (run d of 128 trace rows, bits in register set d%4) computes out of LDS buffer d%2; its own
+    // bits are spent.  The next chunk is expanded into the other LDS buffer, which no wave reads after the
+    // hand-over barrier of the previous chunk; set (d+3)%4 is refilled at the start of the chunk, three
+    // chunks ahead of its use.  The work is laid out as 16 slots, one per MFMA: slot m issues the MFMA, then a
     // fragment read for the second k-step (first six slots), then its share of the expansion (24 dwords
     // of 2 operations and 6 LDS stores per chunk, spread over the first 8 slots).  The hand-over
     // barrier sits after the first k-step (it cannot sit earlier: the reads that follow it refill the
     // first k-step's fragment registers); the second k-step's MFMAs and the other workgroup on the
-    // compute unit cover the LDS latency of the next chunk's first fragments.  (Measured 2% faster
-    // than a barrier 4 MFMAs before the end of the chunk.)
-    auto chunk_body = [&](int d, int half, int set) __attribute__((always_inline)) {   // set = d % 4; half and set passed as literals
-        const int buf = half, nbuf = half ^ 1;
-        const int nset = half ? (set + 1) & 3 : set, nhalf = half ^ 1, lset = (set + 3) & 3;
-        pick_b(nset, nhalf);
+    // compute unit cover the LDS latency of the next chunk's first fragments.
+    auto chunk_body = [&](int d, int set) __attribute__((always_inline)) {   // set = d % 4, passed as a literal
+        const int buf = set & 1, nbuf = buf ^ 1;
+        const int nset = (set + 1) & 3, lset = (set + 3) & 3;
+        pick_b(nset);
         constexpr int BAR = 8;                               // MFMA slots before the hand-over barrier: the whole first k-step,
         static_assert(BAR >= 8 && 24 % BAR == 0, "");          // whose fragment set the reads after the barrier overwrite
 #pragma unroll
         for (int s = 0; s < BAR; ++s) {
             mfma(s >> 3, s & 7);
             if (s < 6) read_frag(buf, 1, 1, s);
-            if (half == 0 && s == 0) load_bits(lset, d + 3);
+            if (s == 0) load_bits(lset, d + 3);
 #pragma unroll
             for (int u = (24 / BAR) * s; u < (24 / BAR) * (s + 1); ++u) {
-                expand_quarter(nset, nhalf, u >> 2, u & 3);
+                expand_quarter(nset, u >> 2, u & 3);
                 if ((u & 3) == 3) store_piece(nbuf, u >> 2);
             }
         }
@@ -301,14 +313,10 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     };
     __builtin_amdgcn_s_setprio(2);                          // the contraction outranks the other workgroup's epilogue stores
     for (int d = 0; d < nruns; d += 4) {                    // nruns is a multiple of 4
-        chunk_body(d, 0, 0);
-        chunk_body(d, 1, 0);
-        chunk_body(d + 1, 0, 1);
-        chunk_body(d + 1, 1, 1);
-        chunk_body(d + 2, 0, 2);
-        chunk_body(d + 2, 1, 2);
-        chunk_body(d + 3, 0, 3);
-        chunk_body(d + 3, 1, 3);
+        chunk_body(d, 0);
+        chunk_body(d + 1, 1);
+        chunk_body(d + 2, 2);
+        chunk_body(d + 3, 3);
     }
 
     __builtin_amdgcn_s_setprio(0);
@@ -318,6 +326,14 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     // with nothing to wait for.  In the mirrored tile a lane's register quadruple is 16 contiguous
     // bytes but the lines are spread over lanes, so that tile is re-laid out through the (now idle)
     // LDS and leaves in 16-byte stores that cover whole lines.  Streaming stores when C is not read.
+    // the counts as integers (exact: every partial sum is an integer below 2^24)
+    v16i acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = (int32_t)facc[i][j][r];
     int32_t* Ch = C + (size_t)h * N * N;
     const int col_in = lane & 31, half = lane >> 5, row_in = half * 4;
     int8_t* tbuf = lds + wave * (32 * TROW);
