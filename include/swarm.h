@@ -124,8 +124,10 @@ swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, 
  * i and j are activated together; the diagonal is an entry's own activation count).
  *
  * The `rows` selections are scattered into a binary trace A (rows x N per head, kept entry-major
- * as bits in the context's scratch, expanded to int8 0/1 on the way to the matrix cores) and C[h] is
- * updated with A^T A computed exactly in int32 by int8 matrix-core instructions:
+ * as bits in the context's scratch, expanded to 4-bit 0/1 operands on the way to the matrix cores) and
+ * C[h] is updated with A^T A computed exactly: the products of 0/1 operands are exact in the 4-bit form
+ * of the matrix-core instruction, its fp32 accumulators hold integers exactly up to 2^24 (the most trace
+ * rows a call accepts), and the update of C itself is int32 arithmetic:
  *     decay_q16 == 65536 : C += A^T A
  *     decay_q16 == 0     : C  = A^T A            (C is not read)
  *     otherwise          : C  = floor((C * decay_q16 + 2^15) / 2^16) + A^T A   (int64 intermediate)
@@ -329,10 +331,12 @@ swarm_status swarm_graph_destroy(swarm_graph* graph);
  *   SWARM_CAL_HBM_WRITE  overwrites `bytes` of buf with 16-byte stores         -> GB/s
  *   SWARM_CAL_MFMA_I8    register-resident loop of v_mfma_i32_32x32x32_i8, 16
  *                        independent accumulators per wave; buf >= 4 bytes     -> TOP/s
+ *   SWARM_CAL_MFMA_FP4   the same with the 4-bit form of v_mfma_f32_32x32x64_f8f6f4, the
+ *                        instruction the co-activation build runs on            -> TOP/s
  * buf: device, 16-byte aligned.  Choose bytes well above the 256 MB last-level cache to measure
  * memory, not cache.  Errors: SWARM_EINVAL for bad arguments or while recording a graph.
  */
-typedef enum { SWARM_CAL_HBM_READ = 0, SWARM_CAL_HBM_WRITE = 1, SWARM_CAL_MFMA_I8 = 2 } swarm_calibration;
+typedef enum { SWARM_CAL_HBM_READ = 0, SWARM_CAL_HBM_WRITE = 1, SWARM_CAL_MFMA_I8 = 2, SWARM_CAL_MFMA_FP4 = 3 } swarm_calibration;
 swarm_status swarm_calibrate(swarm_ctx* ctx, int32_t what, void* buf, size_t bytes, int32_t reps, double* out);
 
 #ifdef __cplusplus

@@ -121,7 +121,7 @@ def swarm_step(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q
                              C.c_void_p(q_off), C.c_void_p(q_cluster), C.c_void_p(q_load), cap)
 
 
-SWARM_CAL_HBM_READ, SWARM_CAL_HBM_WRITE, SWARM_CAL_MFMA_I8 = 0, 1, 2
+SWARM_CAL_HBM_READ, SWARM_CAL_HBM_WRITE, SWARM_CAL_MFMA_I8, SWARM_CAL_MFMA_FP4 = 0, 1, 2, 3
 SWARM_RHO_EXCLUDE_SELF, SWARM_RHO_STRICT = 1, 2
 SWARM_COACT_POPCOUNT = 2
 

@@ -4,11 +4,11 @@
 // The trace is binary, so it is kept in memory as bits: for every head and every run of 128 trace
 // rows one 16-byte word per entry, bits[h][run][entry], one bit per trace row of the run (rows 32w ..
 // 32w+31 in dword w, in the order of trace_bit below).  Both operands of the product are entry panels of this one array.  On the way
-// to the matrix cores a workgroup expands the bits of its two entry panels to int8 0/1 rows in
-// LDS (contraction index contiguous), and the product runs on v_mfma_i32_32x32x32_i8 with exact
-// int32 accumulation.  Feeding int8 from memory instead would make every workgroup pull
-// 512 bytes per contraction byte-step through the L2, which at this tile size is within 15% of
-// the L2's bandwidth at full matrix-core rate; the bit form needs an eighth of it.
+// to the matrix cores a workgroup expands the bits of its two entry panels to rows of 4-bit 0/1
+// operands in LDS (contraction index contiguous), and the product runs on the 4-bit form of
+// v_mfma_f32_32x32x64_f8f6f4, exact for these operands (see below).  Feeding expanded operands from
+// memory instead would multiply the traffic through the L2 by four to eight; the bit form keeps a
+// smaller tile affordable.
 // C is symmetric, so only tiles on or above the diagonal are computed and each off-diagonal tile is
 // stored twice (once transposed).
 #include <stdlib.h>

@@ -145,6 +145,35 @@ def test_token_stress_full_size(sw):
     run_full(sw, cfg, rng.choice(cfg.T, 3, replace=False), rng)
 
 
+def test_counts_up_to_the_row_limit_stay_exact(sw):
+    """The matrix cores accumulate the 0/1 products in fp32, which holds integers exactly up to 2^24: the most
+    trace rows one call accepts.  A trace of that length whose first entry is selected in every row must come
+    out as exactly 2^24, and the neighbouring counts as their closed forms."""
+    rows, N = 1 << 24, 8
+    t = torch.arange(rows, device="cuda", dtype=torch.int32)
+    idx = torch.empty((rows, 1, 2), dtype=torch.int32, device="cuda")
+    idx[:, 0, 0] = 0
+    idx[:, 0, 1] = torch.where(t % 5 == 0, 2, 1).to(torch.int32) + torch.where(t % 7 == 0, 2, 0).to(torch.int32)   # 1, 2, 3 or 4
+    n2 = int((torch.where(t % 5 == 0, 2, 1) + torch.where(t % 7 == 0, 2, 0) == 2).sum())
+    n1 = int((torch.where(t % 5 == 0, 2, 1) + torch.where(t % 7 == 0, 2, 0) == 1).sum())
+    n3 = int((torch.where(t % 5 == 0, 2, 1) + torch.where(t % 7 == 0, 2, 0) == 3).sum())
+    n4 = rows - n1 - n2 - n3
+    for route in (0, 2):
+        Cm = torch.full((1, N, N), -1, dtype=torch.int32, device="cuda")
+        sw.coact_accumulate(idx, N, Cm, decay_q16=0, flags=route)
+        want = np.zeros((N, N), np.int64)
+        want[0, 0] = rows
+        for e, n in ((1, n1), (2, n2), (3, n3), (4, n4)):
+            want[e, e] = want[0, e] = want[e, 0] = n
+        assert np.array_equal(Cm[0].cpu().numpy().astype(np.int64), want), route
+    assert want[0, 0] == 16777216 and sw.device_status() == 0
+    # one more such call on top of it: the update itself is integer arithmetic, so the sum passes 2^24 exactly
+    sw.coact_accumulate(idx, N, Cm, decay_q16=65536)
+    assert np.array_equal(Cm[0].cpu().numpy().astype(np.int64), 2 * want)
+    del idx, Cm
+    torch.cuda.empty_cache()
+
+
 def test_select_long_rows_sliced_and_streaming(sw):
     """Few long rows are selected in two stages (slices, then their winners); many rows of more than 65536
     entries take the streaming kernel.  Both against the oracle on the device's own scores."""
