@@ -241,7 +241,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     const int unit_scale = 0x7f7f7f7f;             // E8M0 127 = 2^0 in every byte the instruction may pick
 
     // fragment addressing: lane l reads row l%32 of an MFMA tile, bytes [16*(l/32), +16) of the 32-byte
-    // k-step.  The swizzle term is the same for rows 32 apart; the tile index is a constant byte offset.
+    // k-step (64 contraction indices as nibbles).  The swizzle term is the same for rows 32 apart; the tile index is a constant byte offset.
     const int frow = lane & 31, fhalf = lane >> 5;
     int fa_base[2], fb_base[2];
 #pragma unroll
@@ -481,7 +481,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
 // The same counts without the matrix cores: C[i][j] = sum over the trace's 32-bit words of
 // popcount(bits_i & bits_j), on the plain vector ALUs (v_and + v_bcnt, which adds the popcount to
 // its accumulator).  A cross-check of the matrix-core path by an independent route, and its
-// competitor: a sixteenth of the LDS traffic per trace row, but 2 ALU operations per 32 products
+// competitor: an eighth of the LDS traffic per trace row, but 2 ALU operations per 32 products
 // where the matrix cores do 65536 per instruction.
 // Workgroup = 64 x 64 tile of C on or above the diagonal, thread = 4 x 4 outputs (rows ty + 16 i,
 // columns tx + 16 j), eight runs of 128 trace rows staged in LDS per pass.
