@@ -371,6 +371,31 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     // GUARD: the tile reaches past N (only tiles of the last tile row / column when N is not a multiple of 256)
     auto emit = [&](auto guard_tag) __attribute__((always_inline)) {
         constexpr bool GUARD = decltype(guard_tag)::value;
+        // Overwriting form: the direct tile first, the two 32-column blocks of a row back to back, so that the two
+        // 128-byte halves of a 256-byte run reach the memory system together.
+        constexpr bool PAIRED = MODE == 0 && VEC;
+        if (PAIRED) {
+            int32_t* Cd = Ch + (size_t)gi_base * N + tj * TN + wx * 64;               // wave-uniform
+            const bool c0_ok = !GUARD || tj * TN + wx * 64 + col_in < N, c1_ok = !GUARD || tj * TN + wx * 64 + 32 + col_in < N;
+            uint32_t colc0 = 0u, colc1 = 0u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int urow = i * 32 + (r >> 2) * 8 + (r & 3);
+                    int32_t* p = Cd + (size_t)urow * N;
+                    if (!GUARD || gi_base + urow + row_in < N) {
+                        if (c0_ok) __builtin_nontemporal_store(acc[i][0][r], at(p, lane_direct));
+                        if (c1_ok) __builtin_nontemporal_store(acc[i][1][r], at(p + 32, lane_direct));
+                        if (RHO && c0_ok) colc0 += reaches(acc[i][0][r]);
+                        if (RHO && c1_ok) colc1 += reaches(acc[i][1][r]);
+                    }
+                }
+            if (RHO) {
+                atomicAdd(&cnt_col[wx * 64 + col_in], colc0);
+                atomicAdd(&cnt_col[wx * 64 + 32 + col_in], colc1);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int gj_base = tj * TN + wx * 64 + j * 32;
@@ -393,7 +418,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
             const bool col_ok = !GUARD || gj_base + col_in < N;
             uint32_t colc = 0u;
 #pragma unroll
-            for (int ip = 0; ip < 4; ip += 2) {                                       // 32 rows x 2 in flight when C is read back
+            for (int ip = 0; ip < (PAIRED ? 0 : 4); ip += 2) {                        // 32 rows x 2 in flight when C is read back
                 int32_t old[2][16];
                 if (MODE != 0) {
 #pragma unroll
@@ -423,7 +448,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
                     }
                 if (MODE != 0) asm volatile("" ::: "memory");
             }
-            if (RHO) atomicAdd(&cnt_col[wx * 64 + j * 32 + col_in], colc);
+            if (RHO && !PAIRED) atomicAdd(&cnt_col[wx * 64 + j * 32 + col_in], colc);
             // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..127
             if (VEC && !diag) {
                 size_t cm_off = (size_t)gj_base * N + gi_base;                        // wave-uniform
