@@ -92,8 +92,8 @@ const char* swarm_last_error(const swarm_ctx* ctx);
 swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags);
 
 /*
- * Score + select (Section 2.3: compute the relevance score of every KV entry against the query --
- * "e.g. query-key inner products" -- and keep the entries with the highest scores).
+ * Score + select (Section 2.3: every KV entry gets a relevance score against the query -- inner
+ * products being the example the section names -- and the entries with the highest scores are kept).
  *
  *   token keys:      s[b][h][n] = sum_g sum_c q[b][h*G+g][c] * K[h][n][c]
  *   page summaries:  s[b][h][n] = sum_g sum_c max(q_c * min[h][n][c], q_c * max[h][n][c])
@@ -200,7 +200,7 @@ swarm_status swarm_coact_build_density(swarm_ctx* ctx, const int32_t* idx, int64
  * below the radius, and is placed on that cluster's next SSD).
  *
  *   f[h][a][c]      = number of t < W with new_ids[h][a] and medoids[h][c] both in sel[t][h][0..k)
- *   member[h][a][c] = 1 - f / W < tau            (fp64; strict, as the text says "smaller than")
+ *   member[h][a][c] = 1 - f / W < tau            (fp64; strict: the text asks for a distance below the radius)
  *   disk[h][a][c]   = (primary[h][c] + size[h][c] + j + 1) mod D for the j-th entry (in the order of
  *                     new_ids, j from 0) that joins cluster c, -1 where the entry does not join
  *                     (the cluster grows by one with every joining entry: a reading, the paper places

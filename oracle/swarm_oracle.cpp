@@ -51,8 +51,8 @@ void parallel_for(int64_t n, int nthreads, const std::function<void(int64_t, int
 extern "C" {
 
 // ---------------------------------------------------------------------------------------
-// Score (Section 2.3: relevance score of every KV entry against the query, "e.g. query-key
-// inner products").
+// Score (Section 2.3: relevance score of every KV entry against the query; inner products are
+// the example the section names).
 //
 // kind 0, token keys  K[H][N][d]:      s = sum_c q_c * K_c
 // kind 1, page summaries S[H][N][2][d] (channel-wise min then max of the page's keys):
