@@ -45,7 +45,7 @@ def main():
     ap.add_argument("--stage-reps", type=int, default=20, help="replays per stage-isolated timing (median and min reported)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are built)",
+        print("bench.py: the path runs on ONE GPU; --gpus above 1 is not supported (there are no collectives)",
               file=sys.stderr)
         sys.exit(2)
 

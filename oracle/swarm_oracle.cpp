@@ -58,7 +58,7 @@ extern "C" {
 // kind 1, page summaries S[H][N][2][d] (channel-wise min then max of the page's keys):
 //                                      s = sum_c max(q_c * mn_c, q_c * mx_c)
 //   i.e. the channel-wise upper bound of q.key over any key inside the page's [min,max] box
-//   (query-aware page selection, cited in Section 9; the formula is this build's reading).
+//   (query-aware page selection, cited in Section 9; the formula is a reading, the paper gives none).
 // Grouped-query attention: the G query heads that share KV head h add their scores.
 // No 1/sqrt(d) scale: it is monotone and cannot change a top-k.
 //
