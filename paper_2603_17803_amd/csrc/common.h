@@ -74,6 +74,7 @@ swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q,
                           const int32_t* row_ids = nullptr, int M = 0);
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx);
 bool select_uses_slices(int64_t rows, int N, int k);   // long rows, few of them: sliced two-stage selection
+swarm_status launch_select_slices(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int* M_out, int* stride_out);
 swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows, int H, int k, int N, int Npad,
                                 int nruns, uint32_t flags, int32_t* row_count = nullptr);   // row_count: int32 [H][nruns*128] out, optional
 swarm_status launch_trace_totals_thresholds(swarm_ctx* ctx, const int32_t* row_count, int H, int nrows, double tau, uint32_t flags,

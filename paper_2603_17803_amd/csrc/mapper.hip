@@ -490,10 +490,13 @@ __global__ __launch_bounds__(MAP_THREADS) void map_requests_kernel(MapArgs a, in
 // in flight while the selection runs.  Per thread: up to 2 x 16 bytes of the entry->cluster table,
 // 16 bytes of the replica table and 16 bytes of the weights (the host stages a table only if it fits
 // that and is 16-byte aligned).
-template <int IPT>
+// CAND: second stage of the sliced selection of a long row -- the keys are the scores of the M listed winners of
+// the row's slices (ascending entry id), and the selected list positions are turned back into entry ids.
+template <int IPT, bool CAND>
 __global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __restrict__ scores, int N, int k,
                                                                  int32_t* __restrict__ out_idx, MapArgs a, int stage_e2c,
-                                                                 int stage_tab, int sel_off) {
+                                                                 int stage_tab, int sel_off, const int32_t* __restrict__ cand,
+                                                                 int cand_stride, int M) {
     __shared__ selcore::Smem sm;
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
     constexpr int NT = selcore::NT;
@@ -505,7 +508,15 @@ __global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __
     // the scores first (the selection waits for them), then the tables (needed only after it)
     int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + sel_off);
     uint32_t key[IPT];
-    selcore::load_keys<IPT>(scores + (size_t)h * N, N, key);
+    const int32_t* c = CAND ? cand + (size_t)h * cand_stride : nullptr;
+    if (CAND) {
+        const float* srow = scores + (size_t)h * N;
+        const int base = tid * IPT;
+#pragma unroll
+        for (int e = 0; e < IPT; ++e) key[e] = (base + e < M) ? selcore::order_key(srow[c[base + e]]) : 0u;
+    } else {
+        selcore::load_keys<IPT>(scores + (size_t)h * N, N, key);
+    }
     int4 r_e2c[2] = {make_int4(0, 0, 0, 0), make_int4(0, 0, 0, 0)}, r_rep = make_int4(0, 0, 0, 0), r_wgt = make_int4(0, 0, 0, 0);
     const int n4_e2c = a.N >> 2, n4_rep = (a.Nc * a.R) >> 2, n4_wgt = a.Nc >> 2;
     if (stage_e2c) {
@@ -520,7 +531,11 @@ __global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __
     }
     for (int w = tid; w < L.nwords; w += NT) L.bitmap[w] = 0;
 
-    selcore::block_select<IPT>(key, N, k, sel_lds, sm);
+    selcore::block_select<IPT>(key, CAND ? M : N, k, sel_lds, sm);
+    if (CAND) {
+        __syncthreads();
+        for (int i = tid; i < k; i += NT) sel_lds[i] = c[sel_lds[i]];
+    }
 
     if (stage_e2c) {
 #pragma unroll
@@ -566,8 +581,9 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
                                const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap,
                                bool* launched) {
     *launched = false;
-    if (N > 64 * selcore::NT || select_uses_slices(H, N, k)) return SWARM_OK;   // long rows: the sliced selection is faster than fusing
     constexpr int NT = selcore::NT;
+    const bool sliced = select_uses_slices(H, N, k);       // long rows: the slices' winners first, their selection fused with the mapping
+    if (N > 64 * NT && !sliced) return SWARM_OK;
     MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0};
     size_t lds = map_lds_base_bytes(Nc, cap);
     const size_t budget = 64u * 1024u;
@@ -586,7 +602,21 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
     if (lds + (size_t)cap * 8 <= budget) { a.split_off = (int)(lds / 4); lds += (size_t)cap * 8; }
     const dim3 grid((unsigned)H), block(NT);
     hipStream_t st = ctx->stream;
-#define SWARM_SELMAP(IPT) hipLaunchKernelGGL(select_map_kernel<IPT>, grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off)
+    if (sliced) {
+        int M = 0, stride = 0;
+        const swarm_status rc = launch_select_slices(ctx, scores, H, N, k, &M, &stride);
+        if (rc != SWARM_OK) return rc;
+#define SWARM_MERGEMAP(IPT) hipLaunchKernelGGL((select_map_kernel<IPT, true>), grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off, ctx->cand, stride, M)
+        if (M <= 4 * NT) SWARM_MERGEMAP(4);
+        else if (M <= 8 * NT) SWARM_MERGEMAP(8);
+        else if (M <= 16 * NT) SWARM_MERGEMAP(16);
+        else if (M <= 32 * NT) SWARM_MERGEMAP(32);
+        else SWARM_MERGEMAP(64);
+#undef SWARM_MERGEMAP
+        *launched = true;
+        return swarm_check_launch(ctx, "select_map_kernel");
+    }
+#define SWARM_SELMAP(IPT) hipLaunchKernelGGL((select_map_kernel<IPT, false>), grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off, nullptr, 0, 0)
     if (N <= 4 * NT) SWARM_SELMAP(4);
     else if (N <= 8 * NT) SWARM_SELMAP(8);
     else if (N <= 16 * NT) SWARM_SELMAP(16);

@@ -150,19 +150,26 @@ bool select_uses_slices(int64_t rows, int N, int k) {
     return M <= N / 2 && M <= 64 * selcore::NT;
 }
 
+// First stage of the sliced selection: the slices' winners of every row into ctx->cand ([rows][*stride], *M of them per row).
+swarm_status launch_select_slices(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int* M_out, int* stride_out) {
+    const int P = (N + SLICE - 1) / SLICE;
+    const int per = k < SLICE ? k : SLICE;
+    const int last = N - (P - 1) * SLICE;
+    *M_out = (P - 1) * per + (k < last ? k : last);
+    *stride_out = P * per;
+    swarm_status rc = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->cand), &ctx->cand_bytes, sizeof(int32_t) * (size_t)rows * *stride_out);
+    if (rc != SWARM_OK) return rc;
+    hipLaunchKernelGGL(topk_slice_kernel, dim3((unsigned)P, (unsigned)rows), dim3(selcore::NT), 0, ctx->stream, scores, N, k, ctx->cand,
+                       *stride_out);
+    return swarm_check_launch(ctx, "topk_slice_kernel");
+}
+
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx) {
     const dim3 grid((unsigned)rows), block(selcore::NT);
     hipStream_t st = ctx->stream;
     if (select_uses_slices(rows, N, k)) {
-        const int P = (N + SLICE - 1) / SLICE;
-        const int per = k < SLICE ? k : SLICE;
-        const int last = N - (P - 1) * SLICE;
-        const int M = (P - 1) * per + (k < last ? k : last);
-        const int stride = P * per;
-        swarm_status rc = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->cand), &ctx->cand_bytes, sizeof(int32_t) * (size_t)rows * stride);
-        if (rc != SWARM_OK) return rc;
-        hipLaunchKernelGGL(topk_slice_kernel, dim3((unsigned)P, (unsigned)rows), block, 0, st, scores, N, k, ctx->cand, stride);
-        rc = swarm_check_launch(ctx, "topk_slice_kernel");
+        int M = 0, stride = 0;
+        const swarm_status rc = launch_select_slices(ctx, scores, rows, N, k, &M, &stride);
         if (rc != SWARM_OK) return rc;
         if (M <= 4 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<4>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
         else if (M <= 8 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<8>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);

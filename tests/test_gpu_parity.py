@@ -627,13 +627,16 @@ def test_medoid_indexed_retrieval_chain(sw):
 STEP_CASES = [
     # (config, resident bitmap?, weights?)  -- shapes chosen to hit the fused kernel with both tables staged,
     # with the entry->cluster table left in memory (N > 8192 or N not a multiple of 4), with the replica
-    # table left in memory (Nc*R not a multiple of 4) and the two-kernel route (k too large for staging)
+    # table left in memory (Nc*R not a multiple of 4), the two-kernel route (k too large for staging) and the sliced
+    # selection of long rows
     (W.CONFIGS["long_128k"].scaled(T=3), False, True),
     (W.CONFIGS["llama8b_32k"].scaled(T=3), True, True),
     (W.CONFIGS["tiny"].scaled(T=3), False, False),
     (W.CONFIGS["tiny"].scaled(N=1027, k=33, T=2, Nc=37, M=37, R=3, D=5), True, True),
     (W.CONFIGS["token_stress"].scaled(N=12288, k=512, T=2), False, True),
     (W.CONFIGS["token_stress"].scaled(N=65536, k=15000, T=1, Nc=2048), False, True),
+    (W.CONFIGS["token_stress"].scaled(T=2), True, True),          # long row, sliced selection: its second stage is fused with the mapping
+    (W.CONFIGS["token_stress"].scaled(N=40000, k=700, T=1, H=2), False, False),
 ]
 
 
