@@ -344,6 +344,32 @@ def test_map_independent_ssd_families_run_side_by_side(sw, D, F, Nc, S):
     run_map(sw, sel, H, N, e2c, Nc, rep, D, None, resident=res)
 
 
+def test_map_random_ssd_families_sweep(sw):
+    """Random numbers of SSD families of random sizes (some SSDs unused, some families of one SSD), random
+    replication factors and weights, many merged clusters per group: split chains against the sequential oracle."""
+    rng = np.random.default_rng(2024)
+    for _ in range(12):
+        D = int(rng.integers(2, 65))
+        F = int(rng.integers(1, min(D, 9) + 1))
+        fam_of = rng.integers(0, F, size=D)                              # SSD -> family
+        fams = [np.flatnonzero(fam_of == f) for f in range(F)]
+        fams = [f for f in fams if len(f)]
+        H = int(rng.integers(1, 4))
+        Nc = int(rng.integers(100, 900))
+        N = int(rng.integers(Nc, 3000))
+        R = int(rng.integers(1, 5))
+        e2c = rng.integers(0, Nc, size=(H, N)).astype(np.int32)
+        rep = np.full((H * Nc, R), -1, np.int32)
+        for c in range(H * Nc):
+            ssds = fams[int(rng.integers(0, len(fams)))]
+            rf = int(rng.integers(1, min(R, len(ssds)) + 1))
+            rep[c, rng.permutation(R)[:rf]] = rng.permutation(ssds)[:rf]
+        S = int(rng.integers(200, 5000))
+        sel = rng.integers(0, N, size=(int(rng.integers(1, 7)), S)).astype(np.int32)
+        weight = rng.integers(0, 1000, size=H * Nc).astype(np.int32) if rng.random() < 0.7 else None
+        run_map(sw, sel, H, N, e2c, Nc, rep, D, weight)
+
+
 def test_map_identity_clusters_is_entry_level_scheduling(sw):
     N, D, R = 4096, 8, 3
     cfg = W.CONFIGS["long_128k"].scaled(N=N, Nc=N, M=N, H=1)
