@@ -10,6 +10,8 @@
 // (load << 6 | d), so one DPP min-reduction over the candidate lanes yields the least-loaded
 // replica with ties to the lower SSD id, and only the compare-and-add of the winner stays on the
 // dependent path.  Bucket positions are computed afterwards, in parallel, from the winners.
+#include <type_traits>
+
 #include "common.h"
 #include "select_core.h"
 #include "wave_ops.h"
@@ -201,7 +203,10 @@ struct MapLds {
 // so that the kernel pays one memory round trip instead of three dependent ones (selection ->
 // cluster of entry -> replica row).  PRESTAGED: the caller has already filled the staged tables,
 // cleared the bitmap and synchronised, and `sel` points into LDS.
-template <int NT, bool PRESTAGED>
+// BIG: the kernel is meant for long lists (thousands of merged picks, hundreds of clusters): the per-item pass and
+// the SSD adjacency run on every thread and the merge marks bytes.  The short-list kernels leave that code out --
+// it is not only unused there, its mere presence between the phases cost them 0.25 us per launch.
+template <int NT, bool PRESTAGED, bool BIG>
 __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int32_t* __restrict__ sel, uint32_t* smem,
                                           int stage_e2c, int stage_tab) {
     const MapLds L(smem, a, stage_e2c, stage_tab);
@@ -236,29 +241,90 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         __syncthreads();
     }
 
-    // merge: one bit per activated, non-resident cluster
-    for (int s0 = tid, r = 0; s0 < a.S; s0 += NT, ++r) {
-        int32_t e;
-        if (PRESTAGED) {
-            e = sel[s0];
-        } else if (r < SEL_REGS) {
-            e = my_sel[0];
-#pragma unroll
-            for (int rr = 1; rr < SEL_REGS; ++rr) e = (r == rr) ? my_sel[rr] : e;
-        } else {
-            e = sel[s0];
-        }
-        if (e == -1) continue;                       // padding of a ragged selection
-        if (e < 0 || e >= a.N) { flags |= SWARM_DEV_BAD_ENTRY; continue; }
-        const int32_t c = stage_e2c ? s_e2c[e] : e2c[e];
-        if (c < 0 || c >= a.Nc) { flags |= SWARM_DEV_BAD_CLUSTER; continue; }
+    // merge: one bit per activated, non-resident cluster.  In two steps per batch -- every entry's cluster first
+    // (independent lookups, all in flight together), then the bits -- so that a batch costs one look-up latency,
+    // not one per entry; -2 marks "nothing to set".
+    // (selects, not branches: a branch per entry would put every look-up into a basic block of its own and
+    // serialise the batch)
+    // STAGED is a compile-time copy of stage_e2c: a run-time choice between the LDS and the memory copy of the
+    // table turns the look-up into a flat load, whose wait also waits for the selection loads still in flight.
+    auto cluster_of = [&](int32_t e, auto staged_tag) __attribute__((always_inline)) -> int32_t {
+        constexpr bool STAGED = decltype(staged_tag)::value;
+        const bool e_ok = (uint32_t)e < (uint32_t)a.N;                     // -1 is padding of a ragged selection, anything else out of range is flagged
+        flags |= (!e_ok && e != -1) ? SWARM_DEV_BAD_ENTRY : 0u;
+        const int32_t ee = e_ok ? e : 0;
+        const int32_t c = STAGED ? s_e2c[ee] : e2c[ee];
+        const bool c_ok = (uint32_t)c < (uint32_t)a.Nc;
+        flags |= (e_ok && !c_ok) ? SWARM_DEV_BAD_CLUSTER : 0u;
+        return (e_ok && c_ok) ? c : -2;
+    };
+    // Long selections over few clusters (many streams merged) would send thousands of LDS atomics to a handful of
+    // bitmap words; they mark one BYTE per cluster with plain stores instead (equal values, so collisions are
+    // harmless) and the bytes are folded into the bitmap afterwards.  The byte map borrows the room of the split
+    // arrays, which are not in use yet.
+    const bool byte_marks = BIG && !PRESTAGED && a.split_off != 0 && a.S >= 2048 && (size_t)a.cap * 8 >= (size_t)a.Nc + 64;
+    uint8_t* marks = reinterpret_cast<uint8_t*>(order2);
+    if (byte_marks) {
+        for (int i = tid; i < (a.Nc + 63) / 64 * 16; i += NT) reinterpret_cast<uint32_t*>(marks)[i] = 0u;
+        __syncthreads();
+    }
+    auto set_bit = [&](int32_t c) __attribute__((always_inline)) {
+        if (c < 0) return;
         if (a.resident) {
             const int64_t gc = cbase + c;
-            if ((a.resident[gc >> 5] >> (gc & 31)) & 1u) continue;
+            if ((a.resident[gc >> 5] >> (gc & 31)) & 1u) return;
         }
-        atomicOr(&bitmap[c >> 5], 1u << (c & 31));
-    }
+        if (byte_marks) marks[c] = 1;
+        else atomicOr(&bitmap[c >> 5], 1u << (c & 31));
+    };
+    auto merge_all = [&](auto staged_tag) __attribute__((always_inline)) {
+        if (PRESTAGED) {                             // the selection is in LDS: nothing to batch
+            for (int s0 = tid; s0 < a.S; s0 += NT) {
+                const int32_t e = sel[s0];
+                if (e == -1) continue;
+                if (e < 0 || e >= a.N) { flags |= SWARM_DEV_BAD_ENTRY; continue; }
+                const int32_t c = decltype(staged_tag)::value ? s_e2c[e] : e2c[e];
+                if (c < 0 || c >= a.Nc) { flags |= SWARM_DEV_BAD_CLUSTER; continue; }
+                if (a.resident) {
+                    const int64_t gc = cbase + c;
+                    if ((a.resident[gc >> 5] >> (gc & 31)) & 1u) continue;
+                }
+                atomicOr(&bitmap[c >> 5], 1u << (c & 31));
+            }
+            return;
+        }
+        {
+            int32_t c[SEL_REGS];
+#pragma unroll
+            for (int r = 0; r < SEL_REGS; ++r) c[r] = (tid + r * NT < a.S) ? cluster_of(my_sel[r], staged_tag) : -2;
+#pragma unroll
+            for (int r = 0; r < SEL_REGS; ++r) set_bit(c[r]);
+        }
+        // long selections (many streams merged): the rest in batches of independent loads
+        constexpr int MB = 8;
+        for (int s0 = tid + SEL_REGS * NT; s0 < a.S; s0 += MB * NT) {
+            int32_t e[MB], c[MB];
+#pragma unroll
+            for (int u = 0; u < MB; ++u) e[u] = (s0 + u * NT < a.S) ? sel[s0 + u * NT] : -1;
+#pragma unroll
+            for (int u = 0; u < MB; ++u) c[u] = cluster_of(e[u], staged_tag);
+#pragma unroll
+            for (int u = 0; u < MB; ++u) set_bit(c[u]);
+        }
+    };
+    if (stage_e2c) merge_all(std::true_type{});
+    else merge_all(std::false_type{});
     __syncthreads();
+    if (byte_marks) {
+        for (int base = wave * 64; base < a.Nc; base += NT) {            // 64 clusters per wave and pass: two bitmap words
+            const uint64_t set = __ballot(marks[base + lane] != 0);      // bytes past Nc were cleared and are never marked
+            if (lane == 0) {
+                bitmap[base >> 5] = (uint32_t)set;
+                if ((base >> 5) + 1 < nwords) bitmap[(base >> 5) + 1] = (uint32_t)(set >> 32);
+            }
+        }
+        __syncthreads();
+    }
 
     // Every wave counts the merged clusters (a popcount of the bitmap).  Few of them: wave 0 does all the rest
     // alone, as one chain.  Many: wave 0 compacts, orders and looks for independent sub-problems, whose chains
@@ -279,26 +345,38 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     uint32_t m = 0, load = 0, cnt = 0, wsum = 0;
     const int D = a.D;
     if (wave == 0) {
-    // compaction in ascending cluster id
-    for (int w0 = 0; w0 < nwords; w0 += 64) {
-        const int w = w0 + lane;
-        uint32_t bits = (w < nwords) ? bitmap[w] : 0u;
+    // compaction in ascending cluster id; a lane takes a slice of 8, 16 or 32 bits, the narrowest that still puts
+    // the whole bitmap on the 64 lanes at once, so that a densely set, short bitmap is not walked by a few lanes
+    const int pw_shift = nwords <= 16 ? 2 : nwords <= 32 ? 1 : 0;     // log2 of the slices per word
+    const int sbits = 32 >> pw_shift, nslices = nwords << pw_shift;   // slice width: 8, 16 or 32 bits
+    for (int s0 = 0; s0 < nslices; s0 += 64) {
+        const int sl = s0 + lane;
+        const int w = sl >> pw_shift, sh = (sl & ((1 << pw_shift) - 1)) * sbits;
+        uint32_t bits = (sl < nslices) ? ((bitmap[w] >> sh) & (sbits == 32 ? 0xffffffffu : (1u << sbits) - 1u)) : 0u;
         uint32_t total;
         uint32_t pos = m + wave_excl_scan(__popc(bits), &total);
         while (bits) {
             const int bit = __ffs(bits) - 1;
             bits &= bits - 1;
-            if (pos < (uint32_t)a.cap) list[pos] = (uint32_t)(w * 32 + bit);
+            if (pos < (uint32_t)a.cap) list[pos] = (uint32_t)(w * 32 + sh + bit);
             ++pos;
         }
         m += total;
     }
     if (m > (uint32_t)a.cap) { flags |= SWARM_DEV_CAP; m = a.cap; }
+    if (BIG && try_split) {                          // what the other waves need for their share of the per-item pass
+        if (lane == 0) { off[1] = m; off[2] = INF32; off[3] = 0u; off[4] = 0u; }
+        L.adj_lo[lane] = 0u;
+        L.adj_hi[lane] = 0u;
+        L.seg_cnt[lane] = 0u;
+    }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    }   // wave 0
 
-    // per item: candidate SSD mask, weight, replication factor
+    // per item: candidate SSD mask, weight, replication factor -- by wave 0 alone for a short list, by every thread
+    // for a long one (which also gathers, per SSD, the union of the candidate masks that contain it)
     uint32_t rf_min = INF32, rf_max = 0;
-    for (uint32_t i = lane; i < m; i += 64) {
+    auto item = [&](uint32_t i) __attribute__((always_inline)) {
         const uint32_t c = list[i];
         const int64_t gc = cbase + c;
         uint64_t mask = 0;
@@ -319,14 +397,45 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         assign[i] = INF32;
         rf_min = min(rf_min, rf);
         rf_max = max(rf_max, rf);
-    }
-    rf_min = waveops::wave_min_u32(rf_min);
-    rf_max = ~waveops::wave_min_u32(~rf_max);
-    {
+        return mask;
+    };
+    auto reduce_wave = [&]() __attribute__((always_inline)) {
+        rf_min = waveops::wave_min_u32(rf_min);
+        rf_max = ~waveops::wave_min_u32(~rf_max);
         const bool any_big = __ballot(wsum >= (1u << 26)) != 0ull;
         uint32_t total;
         (void)wave_excl_scan(min(wsum, (1u << 26) - 1u), &total);     // <= 64 * (2^26 - 1): no wrap
-        wsum = any_big ? (1u << 26) : total;
+        wsum = any_big ? (1u << 26) : min(total, 1u << 26);
+    };
+    if (BIG && try_split) {
+        __syncthreads();
+        const uint32_t mm = off[1];
+        for (uint32_t i = tid; i < mm; i += NT) {
+            uint64_t bits = item(i);
+            const uint32_t lo = (uint32_t)bits, hi = (uint32_t)(bits >> 32);
+            while (bits) {
+                const int d = __ffsll((unsigned long long)bits) - 1;
+                bits &= bits - 1;
+                if (lo) atomicOr(&L.adj_lo[d], lo);
+                if (hi) atomicOr(&L.adj_hi[d], hi);
+            }
+        }
+        reduce_wave();
+        if (lane == 0) {                             // at most 16 waves x 2^26: no wrap
+            atomicMin(&off[2], rf_min);
+            atomicMax(&off[3], rf_max);
+            atomicAdd(&off[4], wsum);
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+    if (BIG && try_split) {
+        rf_min = off[2];
+        rf_max = off[3];
+        wsum = min(off[4], 1u << 26);
+    } else {
+        for (uint32_t i = lane; i < m; i += 64) (void)item(i);
+        reduce_wave();
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
@@ -359,21 +468,23 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     // by rows; a component is named by its lowest SSD.
     uint32_t ncomp = 1;
     if (try_split && wsum < (1u << 26)) {
-        L.adj_lo[lane] = 0u;
-        L.adj_hi[lane] = 0u;
-        L.seg_cnt[lane] = 0u;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-        for (uint32_t i = lane; i < m; i += 64) {
-            const uint32_t lo = mask_lo[i], hi = mask_hi[i];
-            uint64_t bits = ((uint64_t)hi << 32) | lo;
-            while (bits) {
-                const int d = __ffsll((unsigned long long)bits) - 1;
-                bits &= bits - 1;
-                if (lo) atomicOr(&L.adj_lo[d], lo);
-                if (hi) atomicOr(&L.adj_hi[d], hi);
+        if (!BIG) {                                  // the adjacency was not gathered with the per-item pass
+            L.adj_lo[lane] = 0u;
+            L.adj_hi[lane] = 0u;
+            L.seg_cnt[lane] = 0u;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+            for (uint32_t i = lane; i < m; i += 64) {
+                const uint32_t lo = mask_lo[i], hi = mask_hi[i];
+                uint64_t bits = ((uint64_t)hi << 32) | lo;
+                while (bits) {
+                    const int d = __ffsll((unsigned long long)bits) - 1;
+                    bits &= bits - 1;
+                    if (lo) atomicOr(&L.adj_lo[d], lo);
+                    if (hi) atomicOr(&L.adj_hi[d], hi);
+                }
             }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         uint64_t reach = ((uint64_t)L.adj_hi[lane] << 32) | L.adj_lo[lane];
         const bool active = reach != 0ull;           // some routed item has SSD `lane` as a candidate (then reach holds lane itself)
         for (int kk = 0; kk < D; ++kk) {
@@ -478,10 +589,13 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     if (flags) atomicOr(a.dev_flags, flags);
 }
 
-__global__ __launch_bounds__(MAP_THREADS) void map_requests_kernel(MapArgs a, int stage_e2c, int stage_tab) {
+// NT = 256 for a step's selection; 1024 for long merged selections, whose merge is plain per-entry work that
+// scales with the number of threads.
+template <int NT>
+__global__ __launch_bounds__(NT) void map_requests_kernel(MapArgs a, int stage_e2c, int stage_tab) {
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
     const int64_t g = blockIdx.x;
-    map_group<MAP_THREADS, false>(a, g, a.sel + g * a.S, smem, stage_e2c, stage_tab);
+    map_group<NT, false, (NT > 256)>(a, g, a.sel + g * a.S, smem, stage_e2c, stage_tab);
 }
 
 // Selection and request mapping of one decode step of a single stream in one kernel: block h selects
@@ -549,7 +663,7 @@ __global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __
     }
     __syncthreads();
     for (int i = tid; i < k; i += NT) out_idx[(size_t)h * k + i] = sel_lds[i];
-    map_group<NT, true>(a, h, sel_lds, smem, stage_e2c, stage_tab);
+    map_group<NT, true, CAND>(a, h, sel_lds, smem, stage_e2c, stage_tab);
 }
 
 }  // namespace
@@ -568,8 +682,11 @@ swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int 
     if (lds + tab_bytes <= budget) { stage_tab = 1; lds += tab_bytes; }
     if (lds + e2c_bytes <= budget) { stage_e2c = 1; lds += e2c_bytes; }
     if (lds + (size_t)cap * 8 <= budget) { a.split_off = (int)(lds / 4); lds += (size_t)cap * 8; }
-    hipLaunchKernelGGL(map_requests_kernel, dim3((unsigned)groups), dim3(MAP_THREADS), lds, ctx->stream, a, stage_e2c,
-                       stage_tab);
+    if (S >= 2048)
+        hipLaunchKernelGGL(map_requests_kernel<1024>, dim3((unsigned)groups), dim3(1024), lds, ctx->stream, a, stage_e2c, stage_tab);
+    else
+        hipLaunchKernelGGL(map_requests_kernel<MAP_THREADS>, dim3((unsigned)groups), dim3(MAP_THREADS), lds, ctx->stream, a, stage_e2c,
+                           stage_tab);
     return swarm_check_launch(ctx, "map_requests_kernel");
 }
 
