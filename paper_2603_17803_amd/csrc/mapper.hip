@@ -330,14 +330,15 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     // alone, as one chain.  Many: wave 0 compacts, orders and looks for independent sub-problems, whose chains
     // then run side by side on the other waves; all waves meet at the barriers in between (the decision is
     // the same in every wave, so either all of them go to the barriers or none).
+    constexpr bool SPLIT = BIG || !PRESTAGED;        // the fused short-list kernel (one step's selection) leaves the split out
     uint32_t m_all = 0;
-    for (int w0 = 0; w0 < nwords; w0 += 64) m_all += (w0 + lane < nwords) ? __popc(bitmap[w0 + lane]) : 0;
-    {
+    if (SPLIT) {
+        for (int w0 = 0; w0 < nwords; w0 += 64) m_all += (w0 + lane < nwords) ? __popc(bitmap[w0 + lane]) : 0;
         uint32_t total;
         (void)wave_excl_scan(m_all, &total);
         m_all = min(total, (uint32_t)a.cap);
     }
-    const bool try_split = NT > 64 && a.split_off != 0 && m_all >= MAP_SPLIT_MIN_ITEMS;
+    const bool try_split = SPLIT && NT > 64 && a.split_off != 0 && m_all >= MAP_SPLIT_MIN_ITEMS;
     if (wave != 0 && !try_split) {
         if (flags) atomicOr(a.dev_flags, flags);
         return;
