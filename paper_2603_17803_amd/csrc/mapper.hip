@@ -364,7 +364,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         }
         m += total;
     }
-    if (m > (uint32_t)a.cap) { flags |= SWARM_DEV_CAP; m = a.cap; }
+    if (__builtin_expect(m > (uint32_t)a.cap, 0)) { flags |= SWARM_DEV_CAP; m = a.cap; }
     if (BIG && try_split) {                          // what the other waves need for their share of the per-item pass
         if (lane == 0) { off[1] = m; off[2] = INF32; off[3] = 0u; off[4] = 0u; }
         L.adj_lo[lane] = 0u;
@@ -441,7 +441,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
     // visiting order: stable by replication factor (identity when all factors agree)
-    if (m > 0 && rf_min == rf_max) {
+    if (__builtin_expect(m > 0 && rf_min == rf_max, 1)) {
         for (uint32_t i = lane; i < m; i += 64) order[i] = i;
     } else if (m > 0) {
         uint32_t* rfv = assign;                      // assign is rewritten below, before the chain runs
@@ -502,7 +502,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
     if (ncomp <= 1) {
         // greedy least-loaded assignment, one chain
-        if (wsum < (1u << 26)) {
+        if (__builtin_expect(wsum < (1u << 26), 1)) {
             uint32_t keybase = (uint32_t)lane;
             run_chain_packed(D, m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt);
             load = keybase >> 6;

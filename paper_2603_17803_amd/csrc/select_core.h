@@ -131,7 +131,7 @@ __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, 
     const uint32_t c = sm.hist[bstar];
 
     if (need < c) {
-        if (c <= (uint32_t)CMAX) {
+        if (__builtin_expect(c <= (uint32_t)CMAX, 1)) {           // the massive-tie path is laid out off the straight line
             // rank the candidates of b* against each other
 #pragma unroll
             for (int e = 0; e < IPT; ++e)
