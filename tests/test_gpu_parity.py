@@ -98,6 +98,8 @@ CASES = [
     W.CONFIGS["tiny"].scaled(d=24, N=100, k=5, T=1),                         # row not a power of two of chunks
     W.CONFIGS["llama8b_32k"].scaled(d=320, N=100, k=5, T=1, H=2),            # page row longer than one wave-load
     W.CONFIGS["tiny"].scaled(d=512, N=64, k=3, T=1),
+    W.CONFIGS["llama8b_32k"].scaled(N=1500, k=20, T=1, H=16),                # more heads than XCDs (head-major workgroup order)
+    W.CONFIGS["llama8b_32k"].scaled(N=900, k=11, T=1, H=6, B=3),             # heads not a power of two, several streams
 ]
 
 
