@@ -27,7 +27,7 @@ INT8_MFMA_PEAK_TOPS = 5000.0      # the figure the co-activation target is quote
 FP4_MFMA_PEAK_TOPS = 10100.0      # dense peak of the 4-bit matrix-core form the build runs on
 # HBM bytes per score_kernel launch from FETCH_SIZE / WRITE_SIZE counter runs, calibrated on plain copies
 # (profiles/score_kernel_long_128k_hbm_traffic.txt).  Valid for the kernel as profiled; None for other workloads.
-SCORE_KERNEL_HBM_TRAFFIC = {"long_128k": 33892000}
+SCORE_KERNEL_HBM_TRAFFIC = {"long_128k": 33878000}
 
 
 def main():
