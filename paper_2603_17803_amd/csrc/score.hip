@@ -91,8 +91,7 @@ __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ ro
     const int nout = row_ids ? M : N;
     const int32_t* ids = row_ids ? row_ids + (size_t)h * M : nullptr;
     float* o = out + ((size_t)b * H + h) * nout;
-    // `iters` row groups per workgroup, a grid width apart: fewer, longer-lived workgroups measured
-    // a few percent faster on long sweeps
+    // `iters` row groups per workgroup, a grid width apart (the launch passes 1; see there)
 #pragma unroll 1
     for (int it = 0; it < iters; ++it) {
     const int row0 = (bx + it * gx) * RPB + wave * UNROLL * RPW + grp;
@@ -151,7 +150,7 @@ void launch_one(hipStream_t st, const swarm_keys* keys, const void* q, int B, fl
     constexpr int UNROLL = (NCH == 2 || LPR >= 16) ? 4 : 8;
     constexpr int RPB = 4 * UNROLL * (64 / LPR);
     const int groups = ((row_ids ? M : keys->N) + RPB - 1) / RPB;
-    const int iters = ((long)groups * keys->H * B >= 2048) ? 2 : 1;
+    const int iters = 1;    // row groups per workgroup: two of them were a few percent faster with the head-slowest order, one is with heads fastest
     const int gxn = (groups + iters - 1) / iters;
     if ((keys->H & (keys->H - 1)) == 0) {                   // power of two: heads fastest over the workgroup id
         hipLaunchKernelGGL((score_kernel<LPR, NCH, UNROLL, PAGE, true>), dim3(gxn * keys->H, 1, B), dim3(256), 0, st,
