@@ -328,7 +328,8 @@ swarm_status swarm_graph_destroy(swarm_graph* graph);
  * quoted next to the nominal peak a roofline is priced against.  Runs `reps` launches on the
  * context's stream, waits for them and returns the average rate in *out (host).
  *   SWARM_CAL_HBM_READ   streams `bytes` from buf with 16-byte loads           -> GB/s
- *   SWARM_CAL_HBM_WRITE  overwrites `bytes` of buf with 16-byte stores         -> GB/s
+ *   SWARM_CAL_HBM_WRITE  overwrites `bytes` of buf with 16-byte stores, one contiguous
+ *                        4 KiB per workgroup in address order                   -> GB/s
  *   SWARM_CAL_MFMA_I8    register-resident loop of v_mfma_i32_32x32x32_i8, 16
  *                        independent accumulators per wave; buf >= 4 bytes     -> TOP/s
  *   SWARM_CAL_MFMA_FP4   the same with the 4-bit form of v_mfma_f32_32x32x64_f8f6f4, the
