@@ -19,6 +19,7 @@
 namespace {
 
 using waveops::low_lanes_min;
+using waveops::lane_group_min;
 using waveops::wave_excl_scan;
 
 constexpr uint32_t INF32 = 0xffffffffu;
@@ -34,10 +35,14 @@ struct MapArgs {
 // holds (ssd << 24) | position-in-bucket for every routed item and INF32 for unroutable ones;
 // cnt is the bucket length of SSD `lane`.
 //
-// Items are staged 32 at a time, one per lane (lanes 0..31), and handed to the dependent chain by
-// v_readlane.  Per item the chain is: candidate select, DPP min over the SSD lanes, compare, add.
-// The SSD lane that wins item j sets bit j of its `won` word; bucket positions come from those
-// words afterwards, off the chain.
+// Items are staged 32 at a time, one per lane (lanes 0..31).  A single wave issues one instruction at a
+// time, so a link of the chain costs its instruction count, not only its dependent path; what can be done
+// per batch instead of per link is: the candidate masks are transposed once (SSD lane d gets the word whose
+// bit j says "not a candidate of item j", D ballots per batch), so a link needs one signed bit-field extract
+// for its mask, one v_readlane for its weight, and item numbers are literals (the batch is unrolled in
+// groups of 8 behind uniform branches).  Per link then: extract, or, DPP min over the SSD lanes, compare,
+// add, select, and two operations that set bit j of the winner's `won` word; bucket positions come from
+// those words afterwards, off the chain.
 template <int STEPS>
 __device__ __forceinline__ void greedy_chain_packed(uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
                                                     const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign,
@@ -55,24 +60,58 @@ __device__ __forceinline__ void greedy_chain_packed(uint32_t m, int lane, const 
         uint32_t won = 0;
         // Slots past n hold an empty mask: every lane then "wins" with weight 0, which changes nothing,
         // so the unrolled groups of 8 need no per-item bound.
-        for (uint32_t q = 0; q < n; q += 8) {
+        if constexpr (STEPS <= 4) {
+            uint32_t cand_t = 0;                               // bit j: this SSD lane is a candidate of item j
 #pragma unroll
-            for (uint32_t u = 0; u < 8; ++u) {
-                const uint32_t j = q + u;
-                const uint32_t s_lo = (uint32_t)__builtin_amdgcn_readlane((int)mlo, (int)j);
-                const uint32_t s_w6 = (uint32_t)__builtin_amdgcn_readlane((int)w6, (int)j);
-                uint32_t bits = s_lo;
-                if (STEPS > 5) {
-                    const uint32_t s_hi = (uint32_t)__builtin_amdgcn_readlane((int)mhi, (int)j);
-                    bits = lane >= 32 ? s_hi : s_lo;
+            for (int d = 0; d < (1 << STEPS); d += 4) {        // masks hold no bits at or beyond D
+                const uint32_t b0 = (uint32_t)__ballot((mlo >> d) & 1u), b1 = (uint32_t)__ballot((mlo >> (d + 1)) & 1u);
+                const uint32_t b2 = (uint32_t)__ballot((mlo >> (d + 2)) & 1u), b3 = (uint32_t)__ballot((mlo >> (d + 3)) & 1u);
+                // lane d + i takes ballot i.  Literal lane numbers: no lane-select hazard; the wait covers "a vector
+                // compare wrote the scalar register the next vector instruction reads" (2 wait states), which the
+                // compiler cannot see into the statement to provide.
+                asm("s_nop 1\n\tv_writelane_b32 %0, %1, %5\n\tv_writelane_b32 %0, %2, %6\n\tv_writelane_b32 %0, %3, %7\n\tv_writelane_b32 %0, %4, %8"
+                    : "+v"(cand_t)
+                    : "s"(b0), "s"(b1), "s"(b2), "s"(b3), "n"(d), "n"(d + 1), "n"(d + 2), "n"(d + 3));
+            }
+            const int32_t not_cand_t = (int32_t)~cand_t;
+#pragma unroll
+            for (uint32_t q = 0; q < 32; q += 8) {
+                if (q < n) {
+#pragma unroll
+                    for (uint32_t u = 0; u < 8; ++u) {
+                        const uint32_t j = q + u;
+                        const uint32_t s_w6 = (uint32_t)__builtin_amdgcn_readlane((int)w6, (int)j);
+                        const uint32_t not_cand = (uint32_t)((int32_t)((uint32_t)not_cand_t << (31u - j)) >> 31);   // 0 or all ones
+                        uint32_t bumped = keybase + s_w6;                       // off the dependent path
+                        asm volatile("" : "+v"(bumped));                        // kept as a sum to select, not folded into select-then-add
+                        const uint32_t key = keybase | not_cand;
+                        const uint32_t best = lane_group_min<STEPS>(key);
+                        const bool i_win = key == best;              // the winning SSD lane (every lane for an empty mask)
+                        keybase = i_win ? bumped : keybase;
+                        won |= (uint32_t)i_win << j;
+                    }
                 }
-                const uint32_t not_cand = ((bits >> lane5) & 1u) - 1u;      // 0 for a candidate SSD lane, all ones otherwise
-                const uint32_t bumped = keybase + s_w6;                     // off the dependent path
-                const uint32_t key = keybase | not_cand;
-                const uint32_t best = low_lanes_min<STEPS>(key);
-                const bool i_win = key == best;                  // the winning SSD lane (every lane for an empty mask)
-                keybase = i_win ? bumped : keybase;
-                won |= i_win ? (1u << j) : 0u;
+            }
+        } else {
+            for (uint32_t q = 0; q < n; q += 8) {
+#pragma unroll
+                for (uint32_t u = 0; u < 8; ++u) {
+                    const uint32_t j = q + u;
+                    const uint32_t s_lo = (uint32_t)__builtin_amdgcn_readlane((int)mlo, (int)j);
+                    const uint32_t s_w6 = (uint32_t)__builtin_amdgcn_readlane((int)w6, (int)j);
+                    uint32_t bits = s_lo;
+                    if (STEPS > 5) {
+                        const uint32_t s_hi = (uint32_t)__builtin_amdgcn_readlane((int)mhi, (int)j);
+                        bits = lane >= 32 ? s_hi : s_lo;
+                    }
+                    const uint32_t not_cand = ((bits >> lane5) & 1u) - 1u;      // 0 for a candidate SSD lane, all ones otherwise
+                    const uint32_t bumped = keybase + s_w6;                     // off the dependent path
+                    const uint32_t key = keybase | not_cand;
+                    const uint32_t best = low_lanes_min<STEPS>(key);
+                    const bool i_win = key == best;                  // the winning SSD lane (every lane for an empty mask)
+                    keybase = i_win ? bumped : keybase;
+                    won |= i_win ? (1u << j) : 0u;
+                }
             }
         }
         // bucket positions of this chunk's items, in item order

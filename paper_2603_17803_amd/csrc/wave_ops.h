@@ -46,6 +46,26 @@ __device__ __forceinline__ uint32_t dpp_min_u32(uint32_t v) {
     return min(v, o);
 }
 
+// The same exchange for patterns in which every lane has a source (quad_perm, the row mirrors, all rows and banks
+// enabled): "zero for a lane without source" never applies, and saying so leaves the instruction free to write a
+// register of its own instead of updating a copy of its input in place.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_min_u32_all(uint32_t v) {
+    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+    return min(v, o);
+}
+
+// Minimum over aligned groups of 2^STEPS lanes (STEPS <= 4), valid in every lane of a group.
+template <int STEPS>
+__device__ __forceinline__ uint32_t lane_group_min(uint32_t v) {
+    static_assert(STEPS >= 2 && STEPS <= 4, "inside a row of 16 lanes");
+    v = dpp_min_u32_all<0xB1>(v);                   // quad_perm [1,0,3,2]
+    v = dpp_min_u32_all<0x4E>(v);                   // quad_perm [2,3,0,1]
+    if (STEPS >= 3) v = dpp_min_u32_all<0x141>(v);  // row_half_mirror
+    if (STEPS >= 4) v = dpp_min_u32_all<0x140>(v);  // row_mirror
+    return v;
+}
+
 // Minimum over the first 2^STEPS lanes, valid in every one of them (STEPS <= 4 stays inside a row of
 // 16 lanes and is pure DPP; 5 and 6 add two cross-row shuffles).  Lanes that do not take part must
 // hold 0xffffffff.
