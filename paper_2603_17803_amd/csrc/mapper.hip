@@ -42,7 +42,8 @@ struct MapArgs {
 // for its mask, one v_readlane for its weight, and item numbers are literals (the batch is unrolled in
 // groups of 8 behind uniform branches).  Per link then: extract, or, DPP min over the SSD lanes, compare,
 // add, select, and two operations that set bit j of the winner's `won` word; bucket positions come from
-// those words afterwards, off the chain.
+// those words afterwards, off the chain.  The dependent path of a link matters as much as its length
+// (every DPP step waits for its predecessor), hence the prepared keys below.
 template <int STEPS>
 __device__ __forceinline__ void greedy_chain_packed(uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
                                                     const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign,
@@ -77,17 +78,27 @@ __device__ __forceinline__ void greedy_chain_packed(uint32_t m, int lane, const 
 #pragma unroll
             for (uint32_t q = 0; q < 32; q += 8) {
                 if (q < n) {
+                    // The key of the next link is prepared for both outcomes of this one (the lane keeps its load or takes
+                    // the weight) while the minimum is on its way, so that only the minimum, the compare and one select
+                    // lie between two links.
+                    uint32_t key = keybase | (uint32_t)((int32_t)((uint32_t)not_cand_t << (31u - q)) >> 31);
 #pragma unroll
                     for (uint32_t u = 0; u < 8; ++u) {
                         const uint32_t j = q + u;
                         const uint32_t s_w6 = (uint32_t)__builtin_amdgcn_readlane((int)w6, (int)j);
-                        const uint32_t not_cand = (uint32_t)((int32_t)((uint32_t)not_cand_t << (31u - j)) >> 31);   // 0 or all ones
-                        uint32_t bumped = keybase + s_w6;                       // off the dependent path
+                        uint32_t bumped = keybase + s_w6;
                         asm volatile("" : "+v"(bumped));                        // kept as a sum to select, not folded into select-then-add
-                        const uint32_t key = keybase | not_cand;
+                        uint32_t key_stay = 0, key_bump = 0;
+                        if (u < 7) {
+                            const uint32_t nc_next = (uint32_t)((int32_t)((uint32_t)not_cand_t << (31u - (j + 1))) >> 31);   // 0 or all ones
+                            key_stay = keybase | nc_next;
+                            key_bump = bumped | nc_next;
+                            asm volatile("" : "+v"(key_stay), "+v"(key_bump));
+                        }
                         const uint32_t best = lane_group_min<STEPS>(key);
                         const bool i_win = key == best;              // the winning SSD lane (every lane for an empty mask)
                         keybase = i_win ? bumped : keybase;
+                        if (u < 7) key = i_win ? key_bump : key_stay;
                         won |= (uint32_t)i_win << j;
                     }
                 }
