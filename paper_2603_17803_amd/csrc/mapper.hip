@@ -56,7 +56,7 @@ __device__ __forceinline__ void greedy_chain_packed(uint32_t m, int lane, const 
             it = order[base + lane];
             mlo = mask_lo[it];
             mhi = mask_hi[it];
-            w6 = (mlo | mhi) ? (wgt[it] << 6) : 0u;         // an unroutable item adds no load
+            w6 = (wgt[it] << 6) & (0u - (uint32_t)((mlo | mhi) != 0u));   // an unroutable item adds no load (read with the masks, not after them)
         }
         uint32_t won = 0;
         // Slots past n hold an empty mask: every lane then "wins" with weight 0, which changes nothing,
