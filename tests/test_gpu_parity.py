@@ -372,6 +372,28 @@ def test_map_random_ssd_families_sweep(sw):
         run_map(sw, sel, H, N, e2c, Nc, rep, D, weight)
 
 
+@pytest.mark.parametrize("D", [2, 4, 7, 8, 13, 16])
+def test_map_list_lengths_around_the_chain_batches(sw, D):
+    """The chain takes its items in batches of 32 and links in groups of 8: lists of every length from 1 to 70 and
+    around 96 and 128 (one entry = one cluster here, so the list length is the group's length), two to four candidates
+    per item, weights including 0."""
+    N, R = 512, min(D, 4)
+    rng = np.random.default_rng(40 + D)
+    rep = np.full((N, R), -1, np.int32)
+    for c in range(N):
+        rf = int(rng.integers(min(2, R), R + 1))
+        rep[c, :rf] = rng.permutation(D)[:rf]
+    e2c = np.arange(N, dtype=np.int32)[None]
+    weight = rng.integers(0, 9, size=N).astype(np.int32)
+    lengths = list(range(1, 71)) + [95, 96, 97, 127, 128, 129, 255, 256]
+    sel = np.full((len(lengths), 256), -1, np.int32)
+    for g, m in enumerate(lengths):
+        sel[g, :m] = np.sort(rng.permutation(N)[:m])
+    run_map(sw, sel, 1, N, e2c, N, rep, D, weight)
+    run_map(sw, sel, 1, N, e2c, N, rep, D, None)
+    assert sw.device_status() == 0
+
+
 def test_map_identity_clusters_is_entry_level_scheduling(sw):
     N, D, R = 4096, 8, 3
     cfg = W.CONFIGS["long_128k"].scaled(N=N, Nc=N, M=N, H=1)
