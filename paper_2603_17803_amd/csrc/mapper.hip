@@ -427,19 +427,32 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     // per item: candidate SSD mask, weight, replication factor -- by wave 0 alone for a short list, by every thread
     // for a long one (which also gathers, per SSD, the union of the candidate masks that contain it)
     uint32_t rf_min = INF32, rf_max = 0;
-    auto item = [&](uint32_t i) __attribute__((always_inline)) {
+    // TAB is a compile-time copy of stage_tab (a run-time choice between the LDS and the memory copy of a table
+    // makes its look-ups flat loads); the replica slots are read four at a time, all in flight together (the index
+    // is clamped: a slot read twice sets the same bit twice).
+    auto item = [&](uint32_t i, auto tab_tag) __attribute__((always_inline)) {
+        constexpr bool TAB = decltype(tab_tag)::value;
         const uint32_t c = list[i];
         const int64_t gc = cbase + c;
         uint64_t mask = 0;
-        for (int r = 0; r < a.R; ++r) {
-            const int32_t dsk = stage_tab ? s_rep[c * a.R + r] : a.replicas[gc * a.R + r];
-            if (dsk >= a.D) flags |= SWARM_DEV_BAD_SSD;
-            else if (dsk >= 0) mask |= 1ull << dsk;
+        const int R = a.R;
+        for (int r0 = 0; r0 < R; r0 += 4) {
+            int32_t dsk[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = min(r0 + u, R - 1);
+                dsk[u] = TAB ? s_rep[c * R + r] : a.replicas[gc * R + r];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (dsk[u] >= a.D) flags |= SWARM_DEV_BAD_SSD;
+                else if (dsk[u] >= 0) mask |= 1ull << dsk[u];
+            }
         }
         if (mask == 0) flags |= SWARM_DEV_BAD_SSD;
         mask_lo[i] = (uint32_t)mask;
         mask_hi[i] = (uint32_t)(mask >> 32);
-        const int32_t wraw = stage_tab ? s_wgt[c] : (a.weight ? a.weight[gc] : 1);
+        const int32_t wraw = TAB ? s_wgt[c] : (a.weight ? a.weight[gc] : 1);
         const uint32_t wv = (uint32_t)max(wraw, 0);
         wgt[i] = wv;
         wsum = min(wsum + min(wv, 1u << 26), 1u << 26);       // saturating: only "below 2^26" matters
@@ -462,7 +475,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         __syncthreads();
         const uint32_t mm = off[1];
         for (uint32_t i = tid; i < mm; i += NT) {
-            uint64_t bits = item(i);
+            uint64_t bits = stage_tab ? item(i, std::true_type{}) : item(i, std::false_type{});
             const uint32_t lo = (uint32_t)bits, hi = (uint32_t)(bits >> 32);
             while (bits) {
                 const int d = __ffsll((unsigned long long)bits) - 1;
@@ -485,7 +498,8 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         rf_max = off[3];
         wsum = min(off[4], 1u << 26);
     } else {
-        for (uint32_t i = lane; i < m; i += 64) (void)item(i);
+        if (stage_tab) { for (uint32_t i = lane; i < m; i += 64) (void)item(i, std::true_type{}); }
+        else { for (uint32_t i = lane; i < m; i += 64) (void)item(i, std::false_type{}); }
         reduce_wave();
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
