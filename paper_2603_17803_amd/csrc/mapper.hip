@@ -129,11 +129,26 @@ __device__ __forceinline__ void greedy_chain_packed(uint32_t m, int lane, const 
         const bool routable = (mlo | mhi) != 0u;
         const uint32_t valid = (uint32_t)__ballot(routable);      // lanes >= 32 stage nothing, so this is a 32-bit item mask
         uint32_t my_assign = INF32;
-        for (int dsk = 0; dsk < D; ++dsk) {
-            const uint32_t w_d = (uint32_t)__builtin_amdgcn_readlane((int)won, dsk);
-            const uint32_t c_d = (uint32_t)__builtin_amdgcn_readlane((int)cnt, dsk);
-            if (routable && lane < 32 && ((w_d >> lane) & 1u))
-                my_assign = ((uint32_t)dsk << 24) | (c_d + (uint32_t)__popc(w_d & ((1u << lane) - 1u) & valid));
+        if constexpr (STEPS <= 4) {
+            // item lane j: its SSD is the lane whose `won` word has bit j (for a routable item exactly one, below D);
+            // that lane's word and bucket length then come by one lane gather each
+            const uint32_t lanebit = 1u << lane5;
+            uint32_t dj = 0;
+#pragma unroll
+            for (int d = 1; d < (1 << STEPS); ++d) {
+                const uint32_t w_d = (uint32_t)__builtin_amdgcn_readlane((int)won, d);
+                dj = (w_d & lanebit) ? (uint32_t)d : dj;
+            }
+            const uint32_t w_sel = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(dj << 2), (int)won);
+            const uint32_t c_sel = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(dj << 2), (int)cnt);
+            if (routable && lane < 32) my_assign = (dj << 24) | (c_sel + (uint32_t)__popc(w_sel & (lanebit - 1u) & valid));
+        } else {
+            for (int dsk = 0; dsk < D; ++dsk) {
+                const uint32_t w_d = (uint32_t)__builtin_amdgcn_readlane((int)won, dsk);
+                const uint32_t c_d = (uint32_t)__builtin_amdgcn_readlane((int)cnt, dsk);
+                if (routable && lane < 32 && ((w_d >> lane) & 1u))
+                    my_assign = ((uint32_t)dsk << 24) | (c_d + (uint32_t)__popc(w_d & ((1u << lane) - 1u) & valid));
+            }
         }
         if ((uint32_t)lane < n) assign[it] = my_assign;
         cnt += __popc(won & valid);
