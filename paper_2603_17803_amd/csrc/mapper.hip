@@ -459,9 +459,9 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
                 dsk[u] = TAB ? s_rep[c * R + r] : a.replicas[gc * R + r];
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (dsk[u] >= a.D) flags |= SWARM_DEV_BAD_SSD;
-                else if (dsk[u] >= 0) mask |= 1ull << dsk[u];
+            for (int u = 0; u < 4; ++u) {                         // selects, not branches: one basic block for the four slots
+                flags |= (dsk[u] >= a.D) ? SWARM_DEV_BAD_SSD : 0u;
+                mask |= ((uint32_t)dsk[u] < (uint32_t)a.D) ? (1ull << (dsk[u] & 63)) : 0ull;      // negative: an unused slot
             }
         }
         if (mask == 0) flags |= SWARM_DEV_BAD_SSD;
