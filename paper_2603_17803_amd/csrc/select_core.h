@@ -24,8 +24,6 @@
 namespace selcore {
 
 using waveops::wave_incl_scan;
-using waveops::wave_max;
-using waveops::wave_min;
 
 constexpr int NT = 1024;        // threads per selecting block
 constexpr int NW = NT / 64;     // waves
@@ -36,7 +34,8 @@ struct Smem {
     uint32_t hist[NB];
     uint32_t cand[CMAX];
     uint32_t wave_a[NW], wave_b[NW];
-    float wave_hi[NW], wave_lo[NW];
+    __attribute__((aligned(16))) uint32_t wave_kmax[NW];
+    __attribute__((aligned(16))) uint32_t wave_kmin[NW];
     uint32_t cand_count, bstar, above, thr_key, thr_need;
     uint32_t digit, digit_above;
 };
@@ -90,25 +89,34 @@ __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int base = tid * IPT;
 
-    // row extrema of the binning value
-    float hi = -3.0e38f, lo = 3.0e38f;
+    // Row extrema of the binning value.  bin_value is monotone in the key, so they are the binning values of the
+    // largest and the smallest key: integer max / min per score (slots at or beyond N hold key 0, which cannot raise the
+    // maximum and is kept out of the minimum), two conversions at the end.
+    uint32_t kmax = 0u, kmin = 0xffffffffu;
 #pragma unroll
     for (int e = 0; e < IPT; ++e) {
-        if (base + e < N) {
-            const float v = bin_value(key[e]);
-            hi = fmaxf(hi, v);
-            lo = fminf(lo, v);
-        }
+        kmax = max(kmax, key[e]);
+        kmin = min(kmin, (base + e < N) ? key[e] : 0xffffffffu);
     }
-    hi = wave_max(hi);
-    lo = wave_min(lo);
-    if (lane == 0) { sm.wave_hi[wave] = hi; sm.wave_lo[wave] = lo; }
+    kmax = ~waveops::wave_min_u32(~kmax);
+    kmin = waveops::wave_min_u32(kmin);
+    if (lane == 0) { sm.wave_kmax[wave] = kmax; sm.wave_kmin[wave] = kmin; }
     sm.hist[tid] = 0;
     sm.hist[tid + NT] = 0;
     if (tid == 0) { sm.cand_count = 0; sm.thr_key = 0; sm.thr_need = 0xffffffffu; }
     __syncthreads();
+    {
+        const uint4* pmax = reinterpret_cast<const uint4*>(sm.wave_kmax);
+        const uint4* pmin = reinterpret_cast<const uint4*>(sm.wave_kmin);
 #pragma unroll
-    for (int w = 0; w < NW; ++w) { hi = fmaxf(hi, sm.wave_hi[w]); lo = fminf(lo, sm.wave_lo[w]); }
+        for (int w = 0; w < NW / 4; ++w) {
+            const uint4 a = pmax[w], b = pmin[w];
+            kmax = max(max(kmax, a.x), max(a.y, max(a.z, a.w)));
+            kmin = min(min(kmin, b.x), min(b.y, min(b.z, b.w)));
+        }
+    }
+    // an empty row (N = 0) leaves kmax < kmin: hi < lo, and the scale below becomes 0
+    const float hi = bin_value(kmax), lo = bin_value(kmin);
     const float range = hi - lo;
     const float scale = range > 0.f ? fminf((float)NB / range, 1.0e30f) : 0.f;
 
