@@ -64,20 +64,23 @@ __device__ __forceinline__ int bin_of(uint32_t key, float hi, float scale) {
 }
 
 
-// Exclusive block scan of two counters at once.
+// Exclusive block scan of two counters at once.  The 16 wave totals are scanned by every wave on its own (lane l reads
+// total l % 16, four DPP steps inside the row of 16 lanes) instead of being read and conditionally added one by one.
 __device__ __forceinline__ void block_excl_scan2(uint32_t a, uint32_t b, uint32_t& ea, uint32_t& eb, Smem& sm,
                                                  int lane, int wave) {
+    static_assert(NW == 16, "one wave total per lane of a DPP row");
     const uint32_t ia = wave_incl_scan(a), ib = wave_incl_scan(b);
     if (lane == 63) { sm.wave_a[wave] = ia; sm.wave_b[wave] = ib; }
     __syncthreads();
-    ea = ia - a;
-    eb = ib - b;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {                 // independent broadcast reads; earlier waves only
-        const uint32_t ta = sm.wave_a[w], tb = sm.wave_b[w];
-        ea += (w < wave) ? ta : 0u;
-        eb += (w < wave) ? tb : 0u;
-    }
+    uint32_t ta = sm.wave_a[lane & 15], tb = sm.wave_b[lane & 15];
+    ta += waveops::dpp_or_zero<0x111, 0xF>(ta);  tb += waveops::dpp_or_zero<0x111, 0xF>(tb);     // row_shr:1
+    ta += waveops::dpp_or_zero<0x112, 0xF>(ta);  tb += waveops::dpp_or_zero<0x112, 0xF>(tb);     // row_shr:2
+    ta += waveops::dpp_or_zero<0x114, 0xF>(ta);  tb += waveops::dpp_or_zero<0x114, 0xF>(tb);     // row_shr:4
+    ta += waveops::dpp_or_zero<0x118, 0xF>(ta);  tb += waveops::dpp_or_zero<0x118, 0xF>(tb);     // row_shr:8: totals of waves 0..l
+    const int prev = wave > 0 ? wave - 1 : 0;
+    const uint32_t pa = (uint32_t)__builtin_amdgcn_readlane((int)ta, prev), pb = (uint32_t)__builtin_amdgcn_readlane((int)tb, prev);
+    ea = ia - a + (wave > 0 ? pa : 0u);
+    eb = ib - b + (wave > 0 ? pb : 0u);
 }
 
 // key[e] is the key of index tid*IPT + e; slots at or beyond N must hold key 0.
