@@ -27,6 +27,7 @@ def lib():
         L.oracle_trace.restype = C.c_int
         L.oracle_coact_dense.restype = C.c_int
         L.oracle_coact_update.restype = C.c_int
+        L.oracle_coact_rows.restype = C.c_int
         L.oracle_map.restype = C.c_int
         L.oracle_density.restype = C.c_int
         L.oracle_score_rows.restype = C.c_int
@@ -123,6 +124,17 @@ def coact_update(idx: np.ndarray, N: int, Cm: np.ndarray | None = None, decay_q1
     if rc:
         raise OracleError("oracle_coact_update", rc)
     return Cm
+
+
+def coact_rows(idx: np.ndarray, N: int, h: int, r0: int, r1: int, nthreads: int = 1) -> np.ndarray:
+    """Rows [r0, r1) of head h's co-activation counts, from zero: idx int32 [rows][H][k] -> int32 [r1-r0][N]."""
+    idx = _c(idx, np.int32)
+    rows, H, k = idx.shape
+    out = np.empty((r1 - r0, N), np.int32)
+    rc = lib().oracle_coact_rows(_p(idx), C.c_int64(rows), H, k, N, h, r0, r1, _p(out), nthreads)
+    if rc:
+        raise OracleError("oracle_coact_rows", rc)
+    return out
 
 
 def density(Cm: np.ndarray, tau: float, flags: int = 0, totals: np.ndarray | None = None, nthreads: int = 1):

@@ -238,6 +238,38 @@ int oracle_coact_update(const int32_t* idx, int64_t rows, int H, int k, int N, i
 }
 
 // ---------------------------------------------------------------------------------------
+// A block of rows of the co-activation counts of one head (Section 5.1, Step 1, the same definition as
+// above restricted to rows i in [r0, r1)): out[i - r0][j] = number of trace rows of head h that hold both
+// i and j.  For matrices too large to keep whole on the host (65536 x 65536 counts are 16 GiB): the
+// caller walks the matrix block by block.  idx[rows][H][k]; out[(r1 - r0)][N], overwritten.
+// Returns -2 on a bad index, -3 on a repeated index in a row.
+// ---------------------------------------------------------------------------------------
+int oracle_coact_rows(const int32_t* idx, int64_t rows, int H, int k, int N, int h, int r0, int r1, int32_t* out,
+                      int nthreads) {
+    if (!idx || !out || rows < 0 || H < 1 || k < 1 || N < 1 || k > N || h < 0 || h >= H || r0 < 0 || r1 > N || r0 >= r1) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        std::vector<int32_t> v(idx + (r * H + h) * k, idx + (r * H + h + 1) * k);
+        std::sort(v.begin(), v.end());
+        if (v.front() < 0 || v.back() >= N) return -2;
+        if (std::adjacent_find(v.begin(), v.end()) != v.end()) return -3;
+    }
+    std::memset(out, 0, sizeof(int32_t) * (size_t)(r1 - r0) * N);
+    // a row of the block only depends on the trace rows that contain it: split the block's rows over workers
+    parallel_for(r1 - r0, nthreads, [&](int64_t lo, int64_t hi) {
+        for (int64_t r = 0; r < rows; ++r) {
+            const int32_t* sel = idx + (r * H + h) * k;
+            for (int a = 0; a < k; ++a) {
+                const int64_t i = (int64_t)sel[a] - r0;
+                if (i < lo || i >= hi) continue;
+                int32_t* crow = out + i * N;
+                for (int b = 0; b < k; ++b) ++crow[sel[b]];
+            }
+        }
+    });
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------------
 // Request mapping (Section 6.1: merge of the activated clusters with the DRAM-resident ones
 // filtered out, then decoupled entry-bucket scheduling).  Per group g (head = g % H):
 //   1. clusters = { e2c[head][e] : e in sel[g] } minus those whose bit is set in `resident`;

@@ -46,6 +46,29 @@ def test_dense_definition_equals_integer_matmul_and_pair_form():
     assert np.array_equal(Cu, oracle.coact_update(sel, 50, nthreads=1))
 
 
+def test_row_blocks_of_the_counts():
+    """Row blocks of C (for matrices too large to hold whole): the hand fixture's rows, numpy's integer matmul on
+    the block's columns of the trace, ragged block edges, every thread count, and the activation counts on the
+    block's diagonal."""
+    g = json.load(open(os.path.join(GOLD, "coact_hand_case.json")))
+    sel = np.array(g["selections"], np.int32)[:, None, :]
+    assert oracle.coact_rows(sel, g["N"], 0, 1, 3).tolist() == g["C"][1:3]
+    rows, H, k, N = 41, 3, 7, 53
+    sel = W.random_selections(rows, H, k, N, seed=11)
+    A = oracle.trace(sel, N).astype(np.int64)
+    for h in range(H):
+        full = A[h].T @ A[h]
+        for r0, r1, nt in ((0, N, 1), (0, 1, 2), (5, 29, 3), (29, N, 8), (N - 1, N, 4)):
+            blk = oracle.coact_rows(sel, N, h, r0, r1, nthreads=nt)
+            assert np.array_equal(blk, full[r0:r1])
+            counts = np.bincount(sel[:, h].ravel(), minlength=N)
+            assert np.array_equal(blk[np.arange(r1 - r0), np.arange(r0, r1)], counts[r0:r1])
+    with pytest.raises(oracle.OracleError):
+        oracle.coact_rows(sel, N, H, 0, 4)                           # no such head
+    with pytest.raises(oracle.OracleError):
+        oracle.coact_rows(np.array([[[0, 0]]], np.int32), 4, 0, 0, 4)   # repeated entry
+
+
 def test_coact_invariants():
     rows, H, k, N = 64, 2, 16, 200
     sel = W.random_selections(rows, H, k, N, seed=7)
