@@ -87,6 +87,9 @@ swarm_status swarm_destroy(swarm_ctx* ctx);
 /* Text of the last error on this context (or of the last failed swarm_create when ctx is NULL).
  * Valid until the next call on the context.  */
 const char* swarm_last_error(const swarm_ctx* ctx);
+/* Hash of the sources this library was built from (set by the build script; "unknown" otherwise), so that
+ * a binary left behind by an older tree can be told from a current one.  Static storage. */
+const char* swarm_source_hash(void);
 /* Synchronises the stream, reads and clears the sticky device flags.  Returns SWARM_OK when no
  * flag was set, SWARM_EDATA otherwise; *flags (nullable, host) receives the SWARM_DEV_* bits. */
 swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags);

@@ -19,7 +19,7 @@ SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
 SWARM_DEV_BAD_OFFSETS, SWARM_DEV_OVERFLOW = 32, 64
 
-EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_device_status", "swarm_score", "swarm_score_select",
+EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_source_hash", "swarm_device_status", "swarm_score", "swarm_score_select",
            "swarm_coact_accumulate", "swarm_coact_build_density", "swarm_map_requests", "swarm_coact_density", "swarm_window_assign", "swarm_score_select_indexed", "swarm_expand_clusters",
            "swarm_submission_order", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
@@ -52,6 +52,8 @@ def load() -> C.CDLL:
     L.swarm_destroy.argtypes = [vp]
     L.swarm_last_error.argtypes = [vp]
     L.swarm_last_error.restype = C.c_char_p
+    L.swarm_source_hash.argtypes = []
+    L.swarm_source_hash.restype = C.c_char_p
     L.swarm_device_status.argtypes = [vp, C.POINTER(u32)]
     L.swarm_score_select.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, i32, vp, vp]
     L.swarm_score.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, vp]
@@ -70,7 +72,7 @@ def load() -> C.CDLL:
     L.swarm_graph_launch.argtypes = [vp, vp]
     L.swarm_graph_destroy.argtypes = [vp]
     for name in EXPORTS:
-        if name != "swarm_last_error":
+        if name not in ("swarm_last_error", "swarm_source_hash"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -92,6 +94,15 @@ def swarm_destroy(ctx: int) -> None:
 
 def swarm_last_error(ctx: int) -> str:
     return load().swarm_last_error(C.c_void_p(ctx)).decode()
+
+
+def swarm_source_hash() -> str:
+    return load().swarm_source_hash().decode()
+
+
+def library_is_current() -> bool:
+    """True when the loaded library was built from the sources now on disk (its compiled-in hash matches)."""
+    return swarm_source_hash() == _build.source_hash()
 
 
 def swarm_device_status(ctx: int) -> Tuple[int, int]:

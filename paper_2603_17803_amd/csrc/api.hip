@@ -101,6 +101,11 @@ swarm_status swarm_destroy(swarm_ctx* ctx) {
 
 const char* swarm_last_error(const swarm_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
 
+#ifndef SWARM_SOURCE_HASH
+#define SWARM_SOURCE_HASH "unknown"
+#endif
+const char* swarm_source_hash(void) { return SWARM_SOURCE_HASH; }
+
 swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags) {
     SWARM_ENTER(ctx);
     if (ctx->capturing) SWARM_REJECT(ctx, "device_status: not while recording");

@@ -28,6 +28,13 @@ def test_library_exports_every_declared_symbol():
         assert ctypes.cast(getattr(lib, name), ctypes.c_void_p).value
 
 
+def test_library_was_built_from_the_sources_on_disk():
+    """The library is git-ignored but travels with the tree: its compiled-in source hash must be the hash of
+    csrc/ and include/swarm.h as they are now, or the GPU tests would exercise an older binary."""
+    binding.load()
+    assert binding.library_is_current(), "libswarm.so is older than its sources: run __graft_entry__.build()"
+
+
 def test_null_context_is_rejected_without_touching_a_device():
     lib = binding.load()
     assert lib.swarm_destroy(None) == binding.SWARM_EINVAL

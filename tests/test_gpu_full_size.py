@@ -1,13 +1,13 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch shapes bench.py uses.
 
-At these sizes the oracle cannot produce every output in seconds, so each stage is checked on
-sampled outputs the oracle computes one by one, plus properties that hold at any size:
+Per stage:
   scores     : sampled decode steps against the oracle, within the score tolerance;
   selections : the oracle's select on the GPU's own scores for the sampled steps, bit-exact; every
                step: k distinct ascending indices;
-  C          : symmetric; diagonal = activation counts (independent histogram of the selections);
-               row sums = k * diagonal; grand total = rows * k^2; sampled entries against the count
-               of steps that hold both entries, bit-exact;
+  C          : every element against the oracle's counts from the GPU's selections, bit-exact (the whole
+               matrix at once up to 8 x 8192^2; 65536^2 in blocks of 4096 rows, which the oracle builds
+               one at a time); also symmetric, diagonal = activation counts (independent histogram of
+               the selections), row sums = k * diagonal, grand total = rows * k^2;
   queues     : sampled groups against the oracle, bit-exact.
 """
 import numpy as np
@@ -99,6 +99,19 @@ def run_full(sw, cfg, sample_steps, rng):
         got = c[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()].cpu().numpy()
         want = np.array([int((member[int(a)] & member[int(b)]).sum()) for a, b in zip(ii, jj)])
         assert np.array_equal(got, want)
+    # every element against the oracle (Section 5.1 Step 1's counts from the same selections)
+    if H * N * N * 4 <= (4 << 30):
+        C_ref = oracle.coact_update(idx, N, nthreads=16)
+        assert np.array_equal(Cm.cpu().numpy(), C_ref)
+        del C_ref
+    else:
+        BLK = 4096                                            # 1 GiB of counts per block at N = 65536
+        for h in range(H):
+            for r0 in range(0, N, BLK):
+                r1 = min(N, r0 + BLK)
+                ref = oracle.coact_rows(idx, N, h, r0, r1, nthreads=16)
+                assert np.array_equal(Cm[h, r0:r1].cpu().numpy(), ref), (h, r0)
+                del ref
     # the whole matrix once more by the independent route (AND + popcount on the bit trace), compared on the device
     C2 = torch.empty_like(Cm)
     sw.coact_accumulate(idx_all, N, C2, decay_q16=0, flags=2)
@@ -243,10 +256,13 @@ def test_drifting_batch_decayed_windows_scaled(sw):
     assert sw.device_status() == 0
 
 
-def test_drifting_batch_full_size_window(sw):
-    """The drifting batch at its full shape (8 heads x 2048 pages, 64 streams x 4 query heads per KV head, k = 128):
-    one whole decay window of 256 steps (16384 trace rows) and a decayed second window of 64 steps.  Scores run on
-    the matrix-core scorer; sampled steps against the oracle, C of both windows against the oracle in full."""
+def test_drifting_batch_full_size_across_phase_changes(sw):
+    """The drifting batch at its full shape (8 heads x 2048 pages, 64 streams x 4 query heads per KV head, k = 128)
+    over its first 2176 decode steps: a half window of 128 steps, then eight decayed windows of 256 steps (16384
+    trace rows each).  The windows [896, 1152) and [1920, 2176) straddle the changes of the topic mixture at steps
+    1024 and 2048, and eight consecutive decays bring the counts towards their steady state.  Scores run on the
+    matrix-core scorer; sampled steps (among them the last step of a phase and the first of the next) against
+    the oracle; C after every window against the oracle in full."""
     cfg = W.CONFIGS["drift_batch"]
     H, N, B, k = cfg.H, cfg.N, cfg.B, cfg.k
     K = W.keys(cfg)
@@ -255,13 +271,17 @@ def test_drifting_batch_full_size_window(sw):
     e2c_d, w_d, rep_d = dev(e2c), dev(weight), dev(rep)
     Cd = torch.zeros((H, N, N), dtype=torch.int32, device="cuda")
     Cref = np.zeros((H, N, N), np.int32)
-    t0 = 0
-    for steps, decay in ((cfg.decay_window, 65536), (64, cfg.decay_q16)):
-        qs = W.queries(cfg, t0, t0 + steps)
+    windows = [(0, 128, 65536)] + [(128 + 256 * w, 128 + 256 * (w + 1), cfg.decay_q16) for w in range(8)]
+    assert any(a < cfg.phase_len < b for a, b, _ in windows) and any(a < 2 * cfg.phase_len < b for a, b, _ in windows)
+    sampled = {0, 127, 128, cfg.phase_len - 1, cfg.phase_len, 1500, 2 * cfg.phase_len - 1, 2 * cfg.phase_len, 2175}
+    distinct = []
+    for t0, t1, decay in windows:
+        steps = t1 - t0
+        qs = W.queries(cfg, t0, t1)
         idx_win = torch.empty((steps * B, H, k), dtype=torch.int32, device="cuda")
         for t in range(steps):
             out_idx = idx_win[t * B:(t + 1) * B]
-            want = t in (0, steps // 2, steps - 1)
+            want = (t0 + t) in sampled
             _, sc = sw.score_select("page", Kd, dev(qs[t]), k, G=cfg.G, out_idx=out_idx, want_scores=want)
             sel = out_idx.permute(1, 0, 2).reshape(H, B * k).contiguous()          # the 64 streams of a step merged per head
             got = sw.map_requests(sel, H, N, e2c_d, cfg.Nc, rep_d, cfg.D, w_d)
@@ -274,8 +294,10 @@ def test_drifting_batch_full_size_window(sw):
                 ref = oracle.map_requests(sel.cpu().numpy(), H, N, e2c, cfg.Nc, rep, cfg.D, weight, nthreads=16)
                 for g_, r_ in zip(got, ref):
                     assert np.array_equal(g_.cpu().numpy(), r_)
+                distinct.append(int(ref[0][:, -1].max()))
         sw.coact_accumulate(idx_win, N, Cd, decay_q16=decay)
         oracle.coact_update(idx_win.cpu().numpy(), N, Cref, decay, nthreads=16)
-        assert np.array_equal(Cd.cpu().numpy(), Cref)
-        t0 += steps
+        assert np.array_equal(Cd.cpu().numpy(), Cref), (t0, t1)
+    assert np.array_equal(Cref, np.transpose(Cref, (0, 2, 1)))
+    assert max(distinct) > 96                      # the merged selections are long lists (the mapper's split into SSD families)
     assert sw.device_status() == 0

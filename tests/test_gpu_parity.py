@@ -54,16 +54,20 @@ def check_scores(kind, K, q, G, got):
     return ref32, ref64, tol
 
 
-def check_tie_aware(got_idx, ref64, tol, k):
-    """Stage 5 for one row."""
+def check_tie_aware(got_idx, ref64, tol, k, got_scores):
+    """Stage 5 for one row.  The sets must be identical wherever the gap between the k-th and the (k+1)-th
+    oracle score exceeds the tolerance.  Two scores can each move by their own error, so that rule is sound
+    when this row's observed error is at most half the tolerance (it is: fp32 accumulation errs far less than
+    1e-3 relative); should a row ever err more, the sound bound 2 x (observed error) takes its place."""
     order = np.sort(ref64)[::-1]
     kth, nxt = order[k - 1], (order[k] if k < ref64.size else -np.inf)
     t = tol.max()
+    eps = float(np.max(np.abs(got_scores.astype(np.float64) - ref64)))
     sel = np.zeros(ref64.size, bool)
     sel[got_idx] = True
     assert sel[ref64 > kth + t].all()
     assert (ref64[got_idx] >= kth - t).all()
-    if kth - nxt > 2 * t:
+    if kth - nxt > (t if 2 * eps <= t else 2 * eps):
         assert np.array_equal(np.flatnonzero(ref64 >= kth), got_idx)
 
 
@@ -113,7 +117,7 @@ def test_score_and_select_stages(sw, cfg):
         # stage 5: tie-aware end to end
         for b in range(cfg.B):
             for h in range(cfg.H):
-                check_tie_aware(idx[b, h], ref64[b, h], tol[b, h], cfg.k)
+                check_tie_aware(idx[b, h], ref64[b, h], tol[b, h], cfg.k, sc[b, h])
         assert (np.diff(idx, axis=-1) > 0).all()
 
 
@@ -143,7 +147,10 @@ def test_select_ties_special_values(sw):
         idx, sc = sw.score_select("token", Kd, qd, k, want_scores=True)
         sc = sc.cpu().numpy()
         got = idx.cpu().numpy()[0, 0]
-        assert np.array_equal(sc[0, 0], vals, equal_nan=True)          # numerically equal (a -0 may come back as +0)
+        # numerically equal, not bit-equal: the paper says nothing about signed zeros, the reading taken for the
+        # selection is IEEE's (-0 equals +0, and the oracle's own fp64 sum returns +0), so a -0 that comes back
+        # as +0 is the same score
+        assert np.array_equal(sc[0, 0], vals, equal_nan=True)
         assert got.tolist() == oracle.select(vals[None], k)[0].tolist(), (vals[:8], k)
         assert got.tolist() == oracle.select(sc[0], k)[0].tolist()
 
