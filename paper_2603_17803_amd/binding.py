@@ -19,7 +19,7 @@ SWARM_CHECK_IDX = 1
 SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SWARM_DEV_DUP_ENTRY = 1, 2, 4, 8, 16
 SWARM_DEV_BAD_OFFSETS, SWARM_DEV_OVERFLOW = 32, 64
 
-EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_source_hash", "swarm_device_status", "swarm_score", "swarm_score_select",
+EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_source_hash", "swarm_device_status", "swarm_score", "swarm_score_select", "swarm_score_select_static",
            "swarm_coact_accumulate", "swarm_coact_build_density", "swarm_map_requests", "swarm_coact_density", "swarm_window_assign", "swarm_score_select_indexed", "swarm_expand_clusters",
            "swarm_submission_order", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
@@ -56,6 +56,7 @@ def load() -> C.CDLL:
     L.swarm_source_hash.restype = C.c_char_p
     L.swarm_device_status.argtypes = [vp, C.POINTER(u32)]
     L.swarm_score_select.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, i32, vp, vp]
+    L.swarm_score_select_static.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, i32, vp]
     L.swarm_score.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, vp]
     L.swarm_coact_accumulate.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, u32]
     L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
@@ -116,6 +117,12 @@ def swarm_score_select(ctx: int, kind: int, data: int, H: int, N: int, d: int, G
     ks = swarm_keys(kind, data, H, N, d, G)
     return load().swarm_score_select(C.c_void_p(ctx), C.byref(ks), C.c_void_p(q), B, k, C.c_void_p(out_idx),
                                      C.c_void_p(out_scores))
+
+
+def swarm_score_select_static(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q: int, B: int, k: int,
+                              out_idx: int) -> int:
+    ks = swarm_keys(kind, data, H, N, d, G)
+    return load().swarm_score_select_static(C.c_void_p(ctx), C.byref(ks), C.c_void_p(q), B, k, C.c_void_p(out_idx))
 
 
 def swarm_score(ctx: int, kind: int, data: int, H: int, N: int, d: int, G: int, q: int, B: int, out_scores: int) -> int:

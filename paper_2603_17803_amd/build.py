@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswarm.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "score.hip", "select.hip", "coact.hip", "mapper.hip", "density.hip", "window.hip", "retrieval.hip",
-           "calib.hip"]
+           "calib.hip", "noalloc.hip"]
 HEADERS = ["common.h", "wave_ops.h", "select_core.h"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

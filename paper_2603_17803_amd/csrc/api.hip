@@ -72,6 +72,11 @@ swarm_status swarm_create(swarm_ctx** out, int device, void* hip_stream) {
     }
     ctx->device = device;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
+    if (swarm_static_scratch_init(ctx) != SWARM_OK) {
+        snprintf(g_create_err, sizeof g_create_err, "%s", ctx->err);
+        delete ctx;
+        return SWARM_EHIP;
+    }
     e = hipMalloc(reinterpret_cast<void**>(&ctx->dev_flags), 256);
     if (e == hipSuccess) e = hipMemsetAsync(ctx->dev_flags, 0, 256, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
@@ -124,7 +129,9 @@ swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags) {
     return SWARM_OK;
 }
 
-static swarm_status check_score_args(swarm_ctx* ctx, const char* fn, const swarm_keys* keys, const void* q, int32_t B) {
+}  // extern "C"
+
+swarm_status swarm_check_score_args(swarm_ctx* ctx, const char* fn, const swarm_keys* keys, const void* q, int32_t B) {
     if (!keys || !keys->data || !q) SWARM_REJECT(ctx, "%s: NULL keys, data or q", fn);
     if (keys->kind != SWARM_KEYS_TOKEN && keys->kind != SWARM_KEYS_PAGE_MINMAX)
         SWARM_REJECT(ctx, "%s: unknown key kind %d", fn, keys->kind);
@@ -139,9 +146,11 @@ static swarm_status check_score_args(swarm_ctx* ctx, const char* fn, const swarm
     return SWARM_OK;
 }
 
+extern "C" {
+
 swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, float* out_scores) {
     SWARM_ENTER(ctx);
-    swarm_status st = check_score_args(ctx, "score", keys, q, B);
+    swarm_status st = swarm_check_score_args(ctx, "score", keys, q, B);
     if (st != SWARM_OK) return st;
     if (!out_scores || (reinterpret_cast<uintptr_t>(out_scores) & 3)) SWARM_REJECT(ctx, "score: NULL or misaligned out_scores");
     return launch_score(ctx, keys, q, B, out_scores);
@@ -150,7 +159,7 @@ swarm_status swarm_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, 
 swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, int32_t k,
                                 int32_t* out_idx, float* out_scores) {
     SWARM_ENTER(ctx);
-    swarm_status st = check_score_args(ctx, "score_select", keys, q, B);
+    swarm_status st = swarm_check_score_args(ctx, "score_select", keys, q, B);
     if (st != SWARM_OK) return st;
     if (!out_idx) SWARM_REJECT(ctx, "score_select: NULL out_idx");
     if (k < 1 || k > keys->N) SWARM_REJECT(ctx, "score_select: k=%d outside [1,N=%d]", k, keys->N);
@@ -171,7 +180,7 @@ swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const vo
 swarm_status swarm_score_select_indexed(swarm_ctx* ctx, const swarm_keys* keys, const int32_t* row_ids, int32_t M, const void* q,
                                         int32_t B, int32_t k, int32_t* out_idx, float* out_scores) {
     SWARM_ENTER(ctx);
-    swarm_status st = check_score_args(ctx, "score_select_indexed", keys, q, B);
+    swarm_status st = swarm_check_score_args(ctx, "score_select_indexed", keys, q, B);
     if (st != SWARM_OK) return st;
     if (!row_ids || !out_idx) SWARM_REJECT(ctx, "score_select_indexed: NULL row_ids or out_idx");
     if (M < 1) SWARM_REJECT(ctx, "score_select_indexed: M=%d must be >= 1", M);
@@ -350,7 +359,7 @@ swarm_status swarm_step(swarm_ctx* ctx, const swarm_keys* keys, const void* q, i
                         const int32_t* weight, const uint32_t* resident, int32_t* q_off, int32_t* q_cluster,
                         int32_t* q_load, int32_t cap) {
     SWARM_ENTER(ctx);
-    swarm_status st = check_score_args(ctx, "step", keys, q, 1);
+    swarm_status st = swarm_check_score_args(ctx, "step", keys, q, 1);
     if (st != SWARM_OK) return st;
     if (!out_idx) SWARM_REJECT(ctx, "step: NULL out_idx");
     if (k < 1 || k > keys->N) SWARM_REJECT(ctx, "step: k=%d outside [1,N=%d]", k, keys->N);

@@ -801,9 +801,10 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
     hipStream_t st = ctx->stream;
     if (sliced) {
         int M = 0, stride = 0;
-        const swarm_status rc = launch_select_slices(ctx, scores, H, N, k, &M, &stride);
+        int32_t* cand = nullptr;
+        const swarm_status rc = launch_select_slices(ctx, scores, H, N, k, &M, &stride, &cand);
         if (rc != SWARM_OK) return rc;
-#define SWARM_MERGEMAP(IPT) hipLaunchKernelGGL((select_map_kernel<IPT, true>), grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off, ctx->cand, stride, M)
+#define SWARM_MERGEMAP(IPT) hipLaunchKernelGGL((select_map_kernel<IPT, true>), grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off, cand, stride, M)
         if (M <= 4 * NT) SWARM_MERGEMAP(4);
         else if (M <= 8 * NT) SWARM_MERGEMAP(8);
         else if (M <= 16 * NT) SWARM_MERGEMAP(16);

@@ -303,8 +303,19 @@ void launch_batched(hipStream_t st, const swarm_keys* keys, const uint16_t* whi,
 
 }  // namespace
 
+static bool score_is_batched(const swarm_keys* keys, int B, bool listed) {
+    const int L = keys->kind == SWARM_KEYS_PAGE_MINMAX ? 2 * keys->d : keys->d;
+    return !listed && B >= SWARM_BATCHED_MIN_STREAMS && (L == 128 || L == 256) && keys->H <= 65535;
+}
+
+size_t score_weights_bytes(const swarm_keys* keys, int B) {
+    if (!score_is_batched(keys, B, false)) return 0;
+    const int L = keys->kind == SWARM_KEYS_PAGE_MINMAX ? 2 * keys->d : keys->d;
+    return 2 * (size_t)B * keys->H * L * sizeof(uint16_t);
+}
+
 swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores, const int32_t* row_ids,
-                          int M) {
+                          int M, const swarm_fixed_scratch* fixed) {
     if (((int64_t)(row_ids ? M : keys->N) / 16 + 1) * keys->H > 0x7fffffffll) {       // workgroups along x: at least 16 rows each
         snprintf(ctx->err, sizeof(ctx->err), "score: N=%d x H=%d is more than one launch can cover", keys->N, keys->H);
         return SWARM_EINVAL;
@@ -317,12 +328,23 @@ swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q,
     const int L = page ? 2 * keys->d : keys->d;
     const int CH = L / 8;
     // many streams: matrix-core path (row lengths of 128 and 256 values, i.e. d = 128 or page rows of d = 64 / 128)
-    if (!row_ids && B >= SWARM_BATCHED_MIN_STREAMS && (L == 128 || L == 256) && keys->H <= 65535) {
+    if (score_is_batched(keys, B, row_ids != nullptr)) {
         const size_t wbytes = (size_t)B * keys->H * L * sizeof(uint16_t);
-        swarm_status st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->weights), &ctx->weights_bytes, 2 * wbytes);
-        if (st != SWARM_OK) return st;
-        uint16_t* whi = ctx->weights;
-        uint16_t* wlo = ctx->weights + (size_t)B * keys->H * L;
+        swarm_status st = SWARM_OK;
+        uint16_t* whi = nullptr;
+        if (fixed) {
+            if (2 * wbytes > fixed->weights_bytes) {
+                snprintf(ctx->err, sizeof(ctx->err), "score: the folded weights need %zu bytes, the fixed scratch has %zu", 2 * wbytes,
+                         fixed->weights_bytes);
+                return SWARM_EINVAL;
+            }
+            whi = fixed->weights;
+        } else {
+            st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->weights), &ctx->weights_bytes, 2 * wbytes);
+            if (st != SWARM_OK) return st;
+            whi = ctx->weights;
+        }
+        uint16_t* wlo = whi + (size_t)B * keys->H * L;
         const int64_t total = (int64_t)B * keys->H * L;
         const unsigned blocks = (unsigned)((total + 255) / 256);
         if (page)

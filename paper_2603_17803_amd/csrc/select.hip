@@ -150,32 +150,54 @@ bool select_uses_slices(int64_t rows, int N, int k) {
     return M <= N / 2 && M <= 64 * selcore::NT;
 }
 
-// First stage of the sliced selection: the slices' winners of every row into ctx->cand ([rows][*stride], *M of them per row).
-swarm_status launch_select_slices(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int* M_out, int* stride_out) {
+size_t select_cand_bytes(int64_t rows, int N, int k) {
+    if (!select_uses_slices(rows, N, k)) return 0;
+    const int64_t P = (N + SLICE - 1) / SLICE;
+    return sizeof(int32_t) * (size_t)rows * (size_t)(P * (k < SLICE ? k : SLICE));
+}
+
+// First stage of the sliced selection: the slices' winners of every row into *cand_out ([rows][*stride], *M of them per
+// row), which is the context's scratch (grown on demand) or the fixed scratch when one is given.
+swarm_status launch_select_slices(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int* M_out, int* stride_out,
+                                  int32_t** cand_out, const swarm_fixed_scratch* fixed) {
     const int P = (N + SLICE - 1) / SLICE;
     const int per = k < SLICE ? k : SLICE;
     const int last = N - (P - 1) * SLICE;
     *M_out = (P - 1) * per + (k < last ? k : last);
     *stride_out = P * per;
-    swarm_status rc = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->cand), &ctx->cand_bytes, sizeof(int32_t) * (size_t)rows * *stride_out);
-    if (rc != SWARM_OK) return rc;
-    hipLaunchKernelGGL(topk_slice_kernel, dim3((unsigned)P, (unsigned)rows), dim3(selcore::NT), 0, ctx->stream, scores, N, k, ctx->cand,
+    const size_t need = sizeof(int32_t) * (size_t)rows * *stride_out;
+    int32_t* cand = nullptr;
+    if (fixed) {
+        if (need > fixed->cand_bytes) {
+            snprintf(ctx->err, sizeof(ctx->err), "select: the slices' winners need %zu bytes, the fixed scratch has %zu", need, fixed->cand_bytes);
+            return SWARM_EINVAL;
+        }
+        cand = fixed->cand;
+    } else {
+        const swarm_status rc = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->cand), &ctx->cand_bytes, need);
+        if (rc != SWARM_OK) return rc;
+        cand = ctx->cand;
+    }
+    *cand_out = cand;
+    hipLaunchKernelGGL(topk_slice_kernel, dim3((unsigned)P, (unsigned)rows), dim3(selcore::NT), 0, ctx->stream, scores, N, k, cand,
                        *stride_out);
     return swarm_check_launch(ctx, "topk_slice_kernel");
 }
 
-swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx) {
+swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx,
+                           const swarm_fixed_scratch* fixed) {
     const dim3 grid((unsigned)rows), block(selcore::NT);
     hipStream_t st = ctx->stream;
     if (select_uses_slices(rows, N, k)) {
         int M = 0, stride = 0;
-        const swarm_status rc = launch_select_slices(ctx, scores, rows, N, k, &M, &stride);
+        int32_t* cand = nullptr;
+        const swarm_status rc = launch_select_slices(ctx, scores, rows, N, k, &M, &stride, &cand, fixed);
         if (rc != SWARM_OK) return rc;
-        if (M <= 4 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<4>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
-        else if (M <= 8 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<8>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
-        else if (M <= 16 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<16>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
-        else if (M <= 32 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<32>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
-        else hipLaunchKernelGGL(topk_merge_kernel<64>, grid, block, 0, st, scores, N, k, ctx->cand, stride, M, out_idx);
+        if (M <= 4 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<4>, grid, block, 0, st, scores, N, k, cand, stride, M, out_idx);
+        else if (M <= 8 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<8>, grid, block, 0, st, scores, N, k, cand, stride, M, out_idx);
+        else if (M <= 16 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<16>, grid, block, 0, st, scores, N, k, cand, stride, M, out_idx);
+        else if (M <= 32 * selcore::NT) hipLaunchKernelGGL(topk_merge_kernel<32>, grid, block, 0, st, scores, N, k, cand, stride, M, out_idx);
+        else hipLaunchKernelGGL(topk_merge_kernel<64>, grid, block, 0, st, scores, N, k, cand, stride, M, out_idx);
         return swarm_check_launch(ctx, "topk_merge_kernel");
     }
     if (N <= 4 * selcore::NT) hipLaunchKernelGGL(topk_select_kernel<4>, grid, block, 0, st, scores, N, k, out_idx);
