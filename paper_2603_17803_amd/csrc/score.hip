@@ -9,6 +9,8 @@
 // The sweep is bound by HBM bandwidth: each lane issues UNROLL independent 16-byte loads, a
 // group of LPR lanes covers one row, a wave covers 64/LPR consecutive rows per load (1 KiB
 // contiguous), and the per-row partial sums are combined with a lane butterfly.
+#include <type_traits>
+
 #include "common.h"
 
 namespace {
@@ -55,7 +57,7 @@ __device__ __forceinline__ void load_weights(const uint16_t* __restrict__ qbh, i
 // rows in flight per lane.  CH = 16-byte chunks per row.
 template <int LPR, int NCH, int UNROLL, bool PAGE, bool HM>
 __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ rows, const uint16_t* __restrict__ q,
-                                                    float* __restrict__ out, int N, int H, int hshift, int G, int d, int CH, int iters,
+                                                    float* __restrict__ out, int N, int H, int hshift, int G, int d, int CH,
                                                     const int32_t* __restrict__ row_ids, int M, uint32_t* __restrict__ dev_flags) {
     constexpr int RPW = 64 / LPR;
     constexpr int RPB = 4 * UNROLL * RPW;
@@ -67,23 +69,9 @@ __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ ro
     // division in its other arm made the kernel's start 0.3 us slower.)
     const int b = blockIdx.z;
     const int h = HM ? (int)(blockIdx.x & (H - 1)) : (int)blockIdx.y;
-    const int bx = HM ? (int)(blockIdx.x >> hshift) : (int)blockIdx.x, gx = HM ? (int)(gridDim.x >> hshift) : (int)gridDim.x;
+    const int bx = HM ? (int)(blockIdx.x >> hshift) : (int)blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % LPR, grp = lane / LPR;
-
-    const uint16_t* qbh = q + ((size_t)b * H + h) * (size_t)G * d;
-    float w[NCH][8];
-    bool chunk_ok[NCH];
-#pragma unroll
-    for (int m = 0; m < NCH; ++m) {
-        const int chunk = sub + m * LPR;
-        chunk_ok[m] = chunk < CH;
-        if (chunk_ok[m]) load_weights<PAGE>(qbh, G, d, chunk, w[m]);
-        else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) w[m][e] = 0.f;
-        }
-    }
 
     // With a row list (medoid index, Section 5.2 Tier 1) output row n is the score of entry row_ids[h][n];
     // an id outside [0,N) scores 0 and is flagged.
@@ -91,26 +79,58 @@ __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ ro
     const int nout = row_ids ? M : N;
     const int32_t* ids = row_ids ? row_ids + (size_t)h * M : nullptr;
     float* o = out + ((size_t)b * H + h) * nout;
-    // `iters` row groups per workgroup, a grid width apart (the launch passes 1; see there)
-#pragma unroll 1
-    for (int it = 0; it < iters; ++it) {
-    const int row0 = (bx + it * gx) * RPB + wave * UNROLL * RPW + grp;
-    u32x4 x[UNROLL][NCH];
+    bool chunk_ok[NCH];
+#pragma unroll
+    for (int m = 0; m < NCH; ++m) chunk_ok[m] = sub + m * LPR < CH;
+
+    // The key rows first: their loads depend on nothing but the workgroup's position, and they are the long trip
+    // (memory).  The query is fetched and folded into the weights while they are in flight; loading the query first
+    // put one cache round trip in front of every workgroup's first memory request.
+    // Every lane loads from a valid address (row and chunk clamped) and what it must not use is zeroed afterwards:
+    // no divergent branch sits between the loads, so all of them are in flight together.
+    const int row0 = bx * RPB + wave * UNROLL * RPW + grp;
+    int src[UNROLL];
+    bool use[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-        const int n = row0 + u * RPW;
-        int src = n;
-        bool ok = n < nout;
-        if (ids && ok) {
-            src = ids[n];
-            if (src < 0 || src >= N) { ok = false; atomicOr(dev_flags, SWARM_DEV_BAD_ENTRY); }
-        }
+        src[u] = min(row0 + u * RPW, nout - 1);
+        use[u] = true;
+    }
+    if (ids) {
 #pragma unroll
-        for (int m = 0; m < NCH; ++m) {
-            if (ok && chunk_ok[m]) x[u][m] = __builtin_nontemporal_load(base + (size_t)src * CH + sub + m * LPR);
-            else x[u][m] = u32x4{0, 0, 0, 0};
+        for (int u = 0; u < UNROLL; ++u) src[u] = ids[src[u]];
+        bool bad = false;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            use[u] = (uint32_t)src[u] < (uint32_t)N;
+            bad |= !use[u] && row0 + u * RPW < nout;
+            src[u] = use[u] ? src[u] : 0;
+        }
+        if (bad) atomicOr(dev_flags, SWARM_DEV_BAD_ENTRY);
+    }
+    u32x4 x[UNROLL][NCH];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+        for (int m = 0; m < NCH; ++m)
+            x[u][m] = __builtin_nontemporal_load(base + (size_t)src[u] * CH + min(sub + m * LPR, CH - 1));
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+        for (int m = 0; m < NCH; ++m)
+            if (!(use[u] && chunk_ok[m])) x[u][m] = u32x4{0, 0, 0, 0};
+
+    const uint16_t* qbh = q + ((size_t)b * H + h) * (size_t)G * d;
+    float w[NCH][8];
+#pragma unroll
+    for (int m = 0; m < NCH; ++m) {
+        if (chunk_ok[m]) load_weights<PAGE>(qbh, G, d, sub + m * LPR, w[m]);
+        else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) w[m][e] = 0.f;
         }
     }
+
     float p[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -140,32 +160,108 @@ __global__ __launch_bounds__(256) void score_kernel(const u32x4* __restrict__ ro
             }
         }
     }
-    }
 }
 
+
+// Lean form of the sweep for the shapes the decode path runs on: one query head per KV head (G = 1), a row of
+// exactly LPR chunks, a power-of-two number of heads (heads fastest over the workgroup id, as above), no row list.
+// The sweep moves 16 KiB per workgroup and every one of the 2048 workgroups of a 33.5 MB launch runs its code once:
+// measured on one device, the launch takes 7.3 us with 430 instructions per wave, 6.7 us with 254 and 6.5 us with
+// 125 -- what a wave executes around its four loads is time the memory system waits for its next request.  Hence:
+// compile-time row length, one address per wave with literal offsets for the other rows, and a reduction that
+// halves the values a lane carries while it halves the lanes (two exchange steps bring a lane's four partial sums
+// down to one, which then needs one add per remaining lane stride: 6 exchanges instead of 20).
+template <int LPR, bool PAGE>
+__global__ __launch_bounds__(256) void score_lean_kernel(const u32x4* __restrict__ rows, const uint16_t* __restrict__ q,
+                                                         float* __restrict__ out, int N, int H, int hshift) {
+    constexpr int RPW = 64 / LPR, UNROLL = 4, RPB = 4 * UNROLL * RPW, CH = LPR;
+    constexpr int D = PAGE ? CH * 4 : CH * 8;                 // head dimension
+    static_assert(LPR >= 8 && LPR <= 32, "");
+    const int b = blockIdx.z;
+    const int h = (int)(blockIdx.x & (H - 1)), bx = (int)(blockIdx.x >> hshift);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane % LPR, grp = lane / LPR;
+    const int row0 = bx * RPB + wave * UNROLL * RPW + grp;
+    const u32x4* base = rows + (size_t)h * N * CH;
+
+    u32x4 x[UNROLL];
+    if ((bx + 1) * RPB <= N) {                                // the whole workgroup inside the head: one address, literal offsets
+        const u32x4* p0 = base + (size_t)row0 * CH + sub;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) x[u] = __builtin_nontemporal_load(p0 + u * RPW * CH);
+    } else {                                                  // the head's last workgroup: rows clamped, stores masked below
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) x[u] = __builtin_nontemporal_load(base + (size_t)min(row0 + u * RPW, N - 1) * CH + sub);
+    }
+
+    // weights of this lane's chunk, fetched while the rows are in flight
+    float w[8];
+    {
+        const bool max_half = PAGE && sub >= LPR / 2;
+        const int c0 = (PAGE ? sub % (LPR / 2) : sub) * 8;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(q + ((size_t)b * H + h) * D + c0);
+        const float f[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y), bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = PAGE ? (max_half ? fmaxf(f[e], 0.f) : fminf(f[e], 0.f)) : f[e];
+    }
+    float p[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) p[u] = dot8(x[u], w);
+
+    // lanes exchange with the partner one lane away and keep rows {0,1} (even lane) or {2,3} (odd lane), then two lanes
+    // away and keep one row; the lanes of a row's group that agree in their two low bits then add up
+    auto dpp = [](float v, auto ctrl) __attribute__((always_inline)) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xF, 0xF, true));
+    };
+    const bool b0 = lane & 1, b1 = lane & 2;
+    float k0 = b0 ? p[2] : p[0], k1 = b0 ? p[3] : p[1];
+    const float s0 = b0 ? p[0] : p[2], s1 = b0 ? p[1] : p[3];
+    k0 += dpp(s0, std::integral_constant<int, 0xB1>{});       // quad_perm [1,0,3,2]
+    k1 += dpp(s1, std::integral_constant<int, 0xB1>{});
+    float v = b1 ? k1 : k0;
+    const float sv = b1 ? k0 : k1;
+    v += dpp(sv, std::integral_constant<int, 0x4E>{});        // quad_perm [2,3,0,1]
+    v += dpp(v, std::integral_constant<int, 0x124>{});        // row_ror:4  (rotation inside a row of 16 lanes)
+    if (LPR >= 16) v += dpp(v, std::integral_constant<int, 0x128>{});   // row_ror:8
+    if (LPR >= 32) v += __shfl_xor(v, 16, 64);
+    // lane (b0, b1) of a group now holds row 2 b0 + b1 of its group's four rows
+    const int n = row0 + (2 * (int)b0 + (int)(b1 ? 1 : 0)) * RPW;
+    if (sub < UNROLL && n < N) out[((size_t)b * H + h) * N + n] = v;
+}
 
 template <int LPR, int NCH, bool PAGE>
 void launch_one(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int CH, const int32_t* row_ids,
                 int M, uint32_t* dev_flags) {
     constexpr int UNROLL = (NCH == 2 || LPR >= 16) ? 4 : 8;
     constexpr int RPB = 4 * UNROLL * (64 / LPR);
-    const int groups = ((row_ids ? M : keys->N) + RPB - 1) / RPB;
-    const int iters = 1;    // row groups per workgroup: two of them were a few percent faster with the head-slowest order, one is with heads fastest
-    const int gxn = (groups + iters - 1) / iters;
+    const int gxn = ((row_ids ? M : keys->N) + RPB - 1) / RPB;      // one row group per workgroup
     if ((keys->H & (keys->H - 1)) == 0) {                   // power of two: heads fastest over the workgroup id
         hipLaunchKernelGGL((score_kernel<LPR, NCH, UNROLL, PAGE, true>), dim3(gxn * keys->H, 1, B), dim3(256), 0, st,
                            static_cast<const u32x4*>(keys->data), static_cast<const uint16_t*>(q), scores, keys->N, keys->H,
-                           __builtin_ctz(keys->H), keys->G, keys->d, CH, iters, row_ids, M, dev_flags);
+                           __builtin_ctz(keys->H), keys->G, keys->d, CH, row_ids, M, dev_flags);
     } else {
         hipLaunchKernelGGL((score_kernel<LPR, NCH, UNROLL, PAGE, false>), dim3(gxn, keys->H, B), dim3(256), 0, st,
                            static_cast<const u32x4*>(keys->data), static_cast<const uint16_t*>(q), scores, keys->N, keys->H,
-                           0, keys->G, keys->d, CH, iters, row_ids, M, dev_flags);
+                           0, keys->G, keys->d, CH, row_ids, M, dev_flags);
     }
+}
+
+template <int LPR, bool PAGE>
+void launch_lean(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores) {
+    constexpr int RPB = 4 * 4 * (64 / LPR);
+    const int gxn = (keys->N + RPB - 1) / RPB;
+    hipLaunchKernelGGL((score_lean_kernel<LPR, PAGE>), dim3(gxn * keys->H, 1, B), dim3(256), 0, st, static_cast<const u32x4*>(keys->data),
+                       static_cast<const uint16_t*>(q), scores, keys->N, keys->H, __builtin_ctz(keys->H));
 }
 
 template <bool PAGE>
 void dispatch(hipStream_t st, const swarm_keys* keys, const void* q, int B, float* scores, int CH, const int32_t* row_ids, int M,
               uint32_t* dev_flags) {
+    if (!row_ids && keys->G == 1 && (keys->H & (keys->H - 1)) == 0) {      // the decode path's shapes: the lean kernel
+        if (CH == 32) return launch_lean<32, PAGE>(st, keys, q, B, scores);
+        if (CH == 16) return launch_lean<16, PAGE>(st, keys, q, B, scores);
+        if (CH == 8) return launch_lean<8, PAGE>(st, keys, q, B, scores);
+    }
     if (CH > 64) return launch_one<64, 2, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
     if (CH > 32) return launch_one<64, 1, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
     if (CH > 16) return launch_one<32, 1, PAGE>(st, keys, q, B, scores, CH, row_ids, M, dev_flags);
