@@ -119,15 +119,15 @@ swarm_status swarm_score_select(swarm_ctx* ctx, const swarm_keys* keys, const vo
 /*
  * swarm_score_select for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same kernels and same results as swarm_score_select with
- * out_scores = NULL, but the scratch (fp32 scores [B][H][N], the winners of the sliced selection of long
- * rows, the folded weights of the many-stream scorer) lives in one static device array of
+ * out_scores = NULL, but the scratch (fp32 scores [B][H][N] and the winners of the sliced selection of long
+ * rows) lives in one static device array of
  * SWARM_STATIC_SCRATCH_BYTES per GPU, which the library holds from load until the process ends.  The call
  * allocates and frees nothing, on the device or through any library.
  * Every call on a GPU shares that GPU's array, on whatever context or stream: calls that overlap in time on
  * one GPU race (calls on one stream are ordered and safe).  The array keeps the last call's contents; nothing
  * needs clearing, every byte a kernel reads is written earlier in the same call.
  * Errors: those of swarm_score_select; SWARM_EINVAL when the shapes need more than the static scratch
- * (4*B*H*N bytes of scores, rounded up to 256, plus the winners and weights where used).
+ * (4*B*H*N bytes of scores, rounded up to 256, plus the slices' winners where used).
  */
 #define SWARM_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
 swarm_status swarm_score_select_static(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t B, int32_t k,

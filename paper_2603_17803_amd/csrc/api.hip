@@ -96,7 +96,6 @@ swarm_status swarm_destroy(swarm_ctx* ctx) {
     if (ctx->trace) (void)hipFree(ctx->trace);
     if (ctx->cand) (void)hipFree(ctx->cand);
     if (ctx->totals) (void)hipFree(ctx->totals);
-    if (ctx->weights) (void)hipFree(ctx->weights);
     for (auto& t : ctx->tile_orders) (void)hipFree(t.second);
     for (void* p : ctx->retired) (void)hipFree(p);
     if (ctx->dev_flags) (void)hipFree(ctx->dev_flags);

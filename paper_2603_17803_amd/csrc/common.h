@@ -25,13 +25,11 @@ struct swarm_ctx {
     int32_t* cand = nullptr;       // winners of the slices of long rows (two-stage selection)
     size_t cand_bytes = 0;
     size_t scores_bytes = 0;
-    uint16_t* weights = nullptr;   // folded query weights of the batched scorer: bf16 hi then lo, each [B][H][L]
-    size_t weights_bytes = 0;
     void* trace = nullptr;         // binary trace as bits: uint4 [H][runs of 128 rows][Npad]
     size_t trace_bytes = 0;
     int64_t* totals = nullptr;     // per-head grand totals of C when the caller keeps none
     size_t totals_bytes = 0;
-    bool trace_lds_opt_in = false, syrk_lds_opt_in = false;   // large dynamic LDS enabled for this context's device
+    bool trace_lds_opt_in = false, syrk_lds_opt_in = false, batched_lds_opt_in = false;   // large dynamic LDS enabled for this context's device
     uint32_t* dev_flags = nullptr; // sticky SWARM_DEV_* bits (one word)
     void* static_scratch = nullptr; // this device's copy of the library's static scratch array (address resolved at create)
     std::vector<std::pair<int, int32_t*>> tile_orders;   // co-activation tile schedules, one per tile count, never rewritten
@@ -71,24 +69,21 @@ swarm_status swarm_check_score_args(swarm_ctx* ctx, const char* fn, const swarm_
 // Resolves this device's copy of the library's static scratch (called by swarm_create with the device current).
 swarm_status swarm_static_scratch_init(swarm_ctx* ctx);
 size_t select_cand_bytes(int64_t rows, int N, int k);           // scratch the sliced selection needs for its winners (0: not sliced)
-size_t score_weights_bytes(const swarm_keys* keys, int B);     // scratch the batched scorer needs for its folded weights (0: not batched)
 
 // Grows a scratch buffer to at least `bytes` (never shrinks).  Allocation synchronises the stream.
 swarm_status swarm_grow(swarm_ctx* ctx, void** buf, size_t* have, size_t bytes);
 
 // Fixed scratch handed to the launchers in place of the context's growing buffers (for the entry point that
-// may not allocate): the winners of the sliced selection and the folded weights of the batched scorer.
+// may not allocate): the winners of the sliced selection.
 struct swarm_fixed_scratch {
     int32_t* cand;
     size_t cand_bytes;
-    uint16_t* weights;
-    size_t weights_bytes;
 };
 
 // --- kernel launchers (each enqueues on ctx->stream and reports launch errors) ---------------
 constexpr int SWARM_BATCHED_MIN_STREAMS = 8;   // from this many streams on, scoring runs as a GEMM on the matrix cores
 swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores,
-                          const int32_t* row_ids = nullptr, int M = 0, const swarm_fixed_scratch* fixed = nullptr);
+                          const int32_t* row_ids = nullptr, int M = 0);
 swarm_status launch_select(swarm_ctx* ctx, const float* scores, int64_t rows, int N, int k, int32_t* out_idx,
                            const swarm_fixed_scratch* fixed = nullptr);
 bool select_uses_slices(int64_t rows, int N, int k);   // long rows, few of them: sliced two-stage selection

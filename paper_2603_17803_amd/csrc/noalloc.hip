@@ -1,7 +1,7 @@
 // Scoring + selection for callers that cannot allocate device memory (code under HIP graph capture, tight
 // serving loops, harnesses that forbid hipMalloc): the same kernels as swarm_score_select, with every piece
-// of scratch -- the fp32 scores, the winners of the sliced selection, the folded weights of the batched
-// scorer -- laid out in one file-scope device array of fixed size instead of the context's growing buffers.
+// of scratch -- the fp32 scores and the winners of the sliced selection -- laid out in one file-scope device
+// array of fixed size instead of the context's growing buffers.
 #include <mutex>
 
 #include "common.h"
@@ -53,17 +53,15 @@ extern "C" swarm_status swarm_score_select_static(swarm_ctx* ctx, const swarm_ke
     const int64_t rows = (int64_t)B * keys->H;
     const size_t scores_bytes = align256(sizeof(float) * (size_t)rows * keys->N);
     const size_t cand_bytes = align256(select_cand_bytes(rows, keys->N, k));
-    const size_t weights_bytes = align256(score_weights_bytes(keys, B));
-    const size_t need = scores_bytes + cand_bytes + weights_bytes;
+    const size_t need = scores_bytes + cand_bytes;
     if (need > SCRATCH_BYTES)
         SWARM_REJECT(ctx, "score_select_static: B=%d H=%d N=%d k=%d need %zu bytes of scratch, the static scratch holds %zu", B, keys->H,
                      keys->N, k, need, SCRATCH_BYTES);
     unsigned char* base = static_cast<unsigned char*>(ctx->static_scratch);
     float* scores = reinterpret_cast<float*>(base);
-    const swarm_fixed_scratch fixed{reinterpret_cast<int32_t*>(base + scores_bytes), cand_bytes,
-                                    reinterpret_cast<uint16_t*>(base + scores_bytes + cand_bytes), weights_bytes};
+    const swarm_fixed_scratch fixed{reinterpret_cast<int32_t*>(base + scores_bytes), cand_bytes};
     // every byte a kernel reads from the scratch is written by an earlier kernel of this call: nothing to clear
-    st = launch_score(ctx, keys, q, B, scores, nullptr, 0, &fixed);
+    st = launch_score(ctx, keys, q, B, scores);
     if (st != SWARM_OK) return st;
     return launch_select(ctx, scores, rows, keys->N, k, out_idx, &fixed);
 }

@@ -275,126 +275,137 @@ void dispatch(hipStream_t st, const swarm_keys* keys, const void* q, int B, floa
 
 // ---- many streams per call: the sweep becomes a small GEMM on the bf16 matrix cores -------------
 //
-// s[b][n] = sum_c w[b][c] * row[n][c] with w the (folded) query weights of stream b.  The weights
-// are sums of up to G bf16 values, so they are carried as a bf16 pair hi + lo (relative error
-// 2^-17, far inside the score tolerance) and every 16-wide k-step issues two MFMAs per tile.
-// Each wave owns 32 entries x up to 128 streams; entries are read from memory once per 128 streams.
-// The contraction index is free to be visited in any order as long as both operands agree: lane
-// half 0 walks the first half of the row, lane half 1 the second half, 8 values per k-step, so
-// every lane reads one contiguous run of its row.
+// s[b][n] = sum_g sum_c w_g[b][c] * row[n][c], w_g the weights of query head g of stream b: the query itself for
+// token keys, [min(q,0), max(q,0)] for page summaries.  Clamping a bf16 against zero leaves a bf16, so every
+// weight is exact and the G query heads of a group are G matrix-core products into one fp32 accumulator: no
+// folded fp32 weights, no split into a high and a low part, no separate launch to prepare them.
+// A workgroup owns 128 entries (32 per wave, read from memory once, straight into the A fragments) and one tile
+// of 32 streams; the weights of that tile are staged in LDS, clamped on the way (both clamped versions of a page
+// query are stored, the lane half picks its own).  The contraction index is free to be visited in any order as
+// long as both operands agree: lane half 0 walks the first half of the row, lane half 1 the second half, 8 values
+// per k-step, so every lane reads one contiguous run of its row -- and for page rows the first half is the min
+// summary, the second the max summary, so both halves of a k-step use the same 8 query channels.
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;      // NaN stays NaN
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+constexpr int SB_GT = 4;        // query heads of a group staged per pass
+
+// The negative ones of two packed bf16 values (min(q,0)); the other version, max(q,0), is what is left of the pair.
+// A NaN goes where its sign bit says, so a NaN query makes its scores NaN.
+__device__ __forceinline__ uint32_t negative_halves(uint32_t v) {
+    const uint32_t sign = (v >> 15) & 0x00010001u;
+    return v & ((sign << 16) - sign);                            // mask: 0xffff in every half whose sign bit is set
 }
 
-// whi/wlo: bf16 [B][H][L], L = d (token) or 2d (page: min-half weights, then max-half weights)
-template <bool PAGE>
-__global__ void fold_weights_kernel(const uint16_t* __restrict__ q, int G, int d, int L, int64_t total,
-                                    uint16_t* __restrict__ whi, uint16_t* __restrict__ wlo) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total) return;
-    const int c = (int)(i % L);
-    const int64_t bh = i / L;
-    const bool max_half = PAGE && c >= d;
-    const int ch = max_half ? c - d : c;
-    float w = 0.f;
-    for (int g = 0; g < G; ++g) {
-        float x = bf16_lo(q[(bh * G + g) * d + ch]);
-        if (PAGE) x = max_half ? fmaxf(x, 0.f) : fminf(x, 0.f);
-        w += x;
-    }
-    const uint32_t hi = f32_to_bf16_rne(w);
-    const float rest = w - bf16_lo(hi);
-    whi[i] = (uint16_t)hi;
-    wlo[i] = (uint16_t)f32_to_bf16_rne(rest);
-}
-
-constexpr int SB_TILES = 4;     // stream tiles of 32 per wave
-
-// grid (ceil(N / 128), H, ceil(B / 128)); 4 waves, wave w scores entries [128 x + 32 w, +32).
-// KSTEPS = L / 16 k-steps, each consuming 8 values from each half of the row.
-template <int KSTEPS>
-__global__ __launch_bounds__(256) void score_batched_kernel(const u32x4* __restrict__ rows, const u32x4* __restrict__ whi,
-                                                            const u32x4* __restrict__ wlo, float* __restrict__ out,
-                                                            int N, int H, int B) {
-    constexpr int CH = KSTEPS * 2;               // 16-byte chunks per row (and per weight vector)
+// grid (ceil(N / 128), H, ceil(B / 32)); 4 waves, wave w scores entries [128 x + 32 w, +32) for streams [32 z, +32).
+// KSTEPS = L / 16 k-steps, each consuming 8 values from each half of the row.  LDS: [SB_GT][NVER][32][WROW] chunks.
+template <int KSTEPS, bool PAGE>
+__global__ __launch_bounds__(256) void score_batched_kernel(const u32x4* __restrict__ rows, const u32x4* __restrict__ q,
+                                                            float* __restrict__ out, int N, int H, int B, int G) {
+    constexpr int CH = KSTEPS * 2;                         // 16-byte chunks per key row
+    constexpr int CHQ = PAGE ? KSTEPS : KSTEPS * 2;        // 16-byte chunks per query vector (d / 8)
+    constexpr int WROW = CHQ + 1;                          // padded: the 16 lanes an LDS read serves together fall into 16 bank groups
+    constexpr int NVER = PAGE ? 2 : 1;
+    extern __shared__ __attribute__((aligned(16))) u32x4 wt[];
     const int h = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r32 = lane & 31, hf = lane >> 5;
     const int n0 = blockIdx.x * 128 + wave * 32;
-    const int b0 = blockIdx.z * (32 * SB_TILES);
+    const int b0 = blockIdx.z * 32;
     const int n = min(n0 + r32, N - 1);                                     // clamped; stores are masked
     const u32x4* arow = rows + ((size_t)h * N + n) * CH + hf * KSTEPS;
 
-    u32x4 a[KSTEPS];
+    // The first pass's query chunks are requested before the key rows: they come from the cache and are clamped and
+    // parked in LDS while the rows are still on their way from memory.
+    constexpr int NPRE = SB_GT * 32 * CHQ / 256;          // staged chunks per thread and pass
+    auto fetch = [&](int g0, int gn, u32x4 (&qv)[NPRE]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) a[s] = __builtin_nontemporal_load(arow + s);
-
-    f32x16 acc[SB_TILES];
+        for (int i = 0; i < NPRE; ++i) {
+            const int u = threadIdx.x + i * 256;
+            const int c = u % CHQ, sb = (u / CHQ) & 31, g = min(u / (CHQ * 32), gn - 1);
+            const int b = min(b0 + sb, B - 1);
+            qv[i] = q[(((size_t)b * H + h) * G + g0 + g) * CHQ + c];
+        }
+    };
+    auto park = [&](int gn, const u32x4 (&qv)[NPRE]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int t = 0; t < SB_TILES; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-
-    // The weights of a 32-stream tile (hi and lo halves, CH 16-byte chunks per stream) are the same for the
-    // four waves: they are staged in LDS with coalesced loads, one tile at a time, instead of every wave
-    // gathering them from the L2 in 16-byte pieces.  Rows are padded by one chunk so that the 16 lanes a
-    // 16-byte LDS read serves together (16 streams, same chunk) fall into 16 different bank groups.
-    constexpr int WROW = CH + 1;
-    __shared__ u32x4 wtile[2][32 * WROW];
-    const int ntiles = min(SB_TILES, (B - b0 + 31) / 32);
-#pragma unroll
-    for (int t = 0; t < SB_TILES; ++t) {
-        if (t < ntiles) {
-            __syncthreads();
-            for (int u = threadIdx.x; u < 32 * CH; u += 256) {
-                const int sb = u / CH, c = u % CH;
-                const int b = min(b0 + t * 32 + sb, B - 1);
-                wtile[0][sb * WROW + c] = whi[((size_t)b * H + h) * CH + c];
-                wtile[1][sb * WROW + c] = wlo[((size_t)b * H + h) * CH + c];
-            }
-            __syncthreads();
-            const u32x4* wh = &wtile[0][r32 * WROW + hf * KSTEPS];
-            const u32x4* wl = &wtile[1][r32 * WROW + hf * KSTEPS];
-#pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) {
-                const u32x4 bh_ = wh[s], bl_ = wl[s];
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[s]), __builtin_bit_cast(bf16x8, bh_), acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[s]), __builtin_bit_cast(bf16x8, bl_), acc[t], 0, 0, 0);
+        for (int i = 0; i < NPRE; ++i) {
+            const int u = threadIdx.x + i * 256;
+            const int c = u % CHQ, sb = (u / CHQ) & 31, g = u / (CHQ * 32);
+            if (g < gn) {
+                u32x4* dst = wt + ((size_t)g * NVER * 32 + sb) * WROW + c;
+                const u32x4 v = qv[i];
+                if (PAGE) {
+                    const u32x4 neg = {negative_halves(v.x), negative_halves(v.y), negative_halves(v.z), negative_halves(v.w)};
+                    dst[0] = neg;                          // min(q, 0): weights of the min half
+                    dst[32 * WROW] = v ^ neg;              // max(q, 0): weights of the max half
+                } else {
+                    dst[0] = v;
+                }
             }
         }
+    };
+    u32x4 qv[NPRE];
+    fetch(0, min(SB_GT, G), qv);
+    u32x4 a[KSTEPS];
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) a[s] = arow[s];      // cached loads: a 128-byte line serves eight consecutive k-steps of a lane
+
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+    for (int g0 = 0; g0 < G; g0 += SB_GT) {
+        const int gn = min(SB_GT, G - g0);
+        if (g0) {
+            __syncthreads();                               // the previous pass's fragments have been read
+            fetch(g0, gn, qv);
+        }
+        park(gn, qv);
+        __syncthreads();
+        for (int g = 0; g < gn; ++g) {
+            const u32x4* wf = wt + ((size_t)(g * NVER + (PAGE ? hf : 0)) * 32 + r32) * WROW + (PAGE ? 0 : hf * KSTEPS);
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[s]), __builtin_bit_cast(bf16x8, wf[s]), acc, 0, 0, 0);
+        }
     }
-    // result tile: lane l, register r -> stream b0 + 32 t + l%32, entry n0 + 8*(r/4) + 4*(l/32) + r%4
+    // result tile: lane l, register r -> stream b0 + l%32, entry n0 + 8*(r/4) + 4*(l/32) + r%4
+    const int b = b0 + r32;
+    if (b < B) {
+        float* o = out + ((size_t)b * H + h) * N;
 #pragma unroll
-    for (int t = 0; t < SB_TILES; ++t) {
-        const int b = b0 + t * 32 + r32;
-        if (t < ntiles && b < B) {
-            float* o = out + ((size_t)b * H + h) * N;
+        for (int rq = 0; rq < 4; ++rq) {
+            const int nn = n0 + rq * 8 + hf * 4;
+            if (nn + 3 < N && ((reinterpret_cast<uintptr_t>(o + nn) & 15) == 0)) {
+                *reinterpret_cast<float4*>(o + nn) = make_float4(acc[rq * 4], acc[rq * 4 + 1], acc[rq * 4 + 2], acc[rq * 4 + 3]);
+            } else {
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const int nn = n0 + rq * 8 + hf * 4;
-                if (nn + 3 < N && ((reinterpret_cast<uintptr_t>(o + nn) & 15) == 0)) {
-                    *reinterpret_cast<float4*>(o + nn) = make_float4(acc[t][rq * 4], acc[t][rq * 4 + 1], acc[t][rq * 4 + 2], acc[t][rq * 4 + 3]);
-                } else {
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        if (nn + rr < N) o[nn + rr] = acc[t][rq * 4 + rr];
-                }
+                for (int rr = 0; rr < 4; ++rr)
+                    if (nn + rr < N) o[nn + rr] = acc[rq * 4 + rr];
             }
         }
     }
 }
 
-template <int KSTEPS>
-void launch_batched(hipStream_t st, const swarm_keys* keys, const uint16_t* whi, const uint16_t* wlo, int B, float* scores) {
-    dim3 grid((keys->N + 127) / 128, keys->H, (B + 32 * SB_TILES - 1) / (32 * SB_TILES));
-    hipLaunchKernelGGL((score_batched_kernel<KSTEPS>), grid, dim3(256), 0, st, static_cast<const u32x4*>(keys->data),
-                       reinterpret_cast<const u32x4*>(whi), reinterpret_cast<const u32x4*>(wlo), scores, keys->N, keys->H, B);
+template <int KSTEPS, bool PAGE>
+swarm_status launch_batched(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores) {
+    constexpr int CHQ = PAGE ? KSTEPS : KSTEPS * 2;
+    constexpr size_t LDS = (size_t)SB_GT * (PAGE ? 2 : 1) * 32 * (CHQ + 1) * 16;
+    if (LDS > 64 * 1024 && !ctx->batched_lds_opt_in) {     // per context: the attribute belongs to the device the context is bound to
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_batched_kernel<KSTEPS, PAGE>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+        if (e != hipSuccess) {
+            snprintf(ctx->err, sizeof(ctx->err), "score: cannot opt in to %zu bytes of LDS: %s", LDS, hipGetErrorString(e));
+            return SWARM_EHIP;
+        }
+        ctx->batched_lds_opt_in = true;
+    }
+    dim3 grid((keys->N + 127) / 128, keys->H, (B + 31) / 32);
+    hipLaunchKernelGGL((score_batched_kernel<KSTEPS, PAGE>), grid, dim3(256), LDS, ctx->stream, static_cast<const u32x4*>(keys->data),
+                       static_cast<const u32x4*>(q), scores, keys->N, keys->H, B, keys->G);
+    return swarm_check_launch(ctx, "score_batched_kernel");
 }
 
 }  // namespace
@@ -404,14 +415,8 @@ static bool score_is_batched(const swarm_keys* keys, int B, bool listed) {
     return !listed && B >= SWARM_BATCHED_MIN_STREAMS && (L == 128 || L == 256) && keys->H <= 65535;
 }
 
-size_t score_weights_bytes(const swarm_keys* keys, int B) {
-    if (!score_is_batched(keys, B, false)) return 0;
-    const int L = keys->kind == SWARM_KEYS_PAGE_MINMAX ? 2 * keys->d : keys->d;
-    return 2 * (size_t)B * keys->H * L * sizeof(uint16_t);
-}
-
 swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int B, float* scores, const int32_t* row_ids,
-                          int M, const swarm_fixed_scratch* fixed) {
+                          int M) {
     if (((int64_t)(row_ids ? M : keys->N) / 16 + 1) * keys->H > 0x7fffffffll) {       // workgroups along x: at least 16 rows each
         snprintf(ctx->err, sizeof(ctx->err), "score: N=%d x H=%d is more than one launch can cover", keys->N, keys->H);
         return SWARM_EINVAL;
@@ -424,36 +429,10 @@ swarm_status launch_score(swarm_ctx* ctx, const swarm_keys* keys, const void* q,
     const int L = page ? 2 * keys->d : keys->d;
     const int CH = L / 8;
     // many streams: matrix-core path (row lengths of 128 and 256 values, i.e. d = 128 or page rows of d = 64 / 128)
+    // many streams: matrix-core path (row lengths of 128 and 256 values, i.e. d = 128 or page rows of d = 64 / 128)
     if (score_is_batched(keys, B, row_ids != nullptr)) {
-        const size_t wbytes = (size_t)B * keys->H * L * sizeof(uint16_t);
-        swarm_status st = SWARM_OK;
-        uint16_t* whi = nullptr;
-        if (fixed) {
-            if (2 * wbytes > fixed->weights_bytes) {
-                snprintf(ctx->err, sizeof(ctx->err), "score: the folded weights need %zu bytes, the fixed scratch has %zu", 2 * wbytes,
-                         fixed->weights_bytes);
-                return SWARM_EINVAL;
-            }
-            whi = fixed->weights;
-        } else {
-            st = swarm_grow(ctx, reinterpret_cast<void**>(&ctx->weights), &ctx->weights_bytes, 2 * wbytes);
-            if (st != SWARM_OK) return st;
-            whi = ctx->weights;
-        }
-        uint16_t* wlo = whi + (size_t)B * keys->H * L;
-        const int64_t total = (int64_t)B * keys->H * L;
-        const unsigned blocks = (unsigned)((total + 255) / 256);
-        if (page)
-            hipLaunchKernelGGL(fold_weights_kernel<true>, dim3(blocks), dim3(256), 0, ctx->stream, static_cast<const uint16_t*>(q),
-                               keys->G, keys->d, L, total, whi, wlo);
-        else
-            hipLaunchKernelGGL(fold_weights_kernel<false>, dim3(blocks), dim3(256), 0, ctx->stream, static_cast<const uint16_t*>(q),
-                               keys->G, keys->d, L, total, whi, wlo);
-        st = swarm_check_launch(ctx, "fold_weights_kernel");
-        if (st != SWARM_OK) return st;
-        if (L == 256) launch_batched<16>(ctx->stream, keys, whi, wlo, B, scores);
-        else launch_batched<8>(ctx->stream, keys, whi, wlo, B, scores);
-        return swarm_check_launch(ctx, "score_batched_kernel");
+        if (page) return L == 256 ? launch_batched<16, true>(ctx, keys, q, B, scores) : launch_batched<8, true>(ctx, keys, q, B, scores);
+        return L == 256 ? launch_batched<16, false>(ctx, keys, q, B, scores) : launch_batched<8, false>(ctx, keys, q, B, scores);
     }
     if (page) dispatch<true>(ctx->stream, keys, q, B, scores, CH, row_ids, M, ctx->dev_flags);
     else dispatch<false>(ctx->stream, keys, q, B, scores, CH, row_ids, M, ctx->dev_flags);
