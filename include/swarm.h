@@ -275,6 +275,22 @@ swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t grou
                                 int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap);
 
 /*
+ * Request mapping of a batch of decode streams, straight from the selections (Section 6.1: the clusters activated
+ * at a step are merged before the buckets are filled; Fig. 9's caption shows two queries' clusters merged).
+ * Group (step, head) merges the entries idx[step][b][head][0..k) of all B streams b and is mapped exactly as
+ * swarm_map_requests maps a group holding those B*k entries: same queues, bit for bit.
+ *
+ * idx     device, int32 [steps][B][H][k]: the out_idx of `steps` consecutive swarm_score_select calls of B streams.
+ * outputs q_off [steps*H][D+1], q_cluster [steps*H][cap], q_load [steps*H][D]; everything else as in
+ *         swarm_map_requests (S there is B*k here; cap = min(B*k, Nc) always suffices).
+ * Errors: those of swarm_map_requests; SWARM_EINVAL for steps/B/k < 1, B*k > 2^24, H*k > 2^30, steps*H > 2^30.
+ */
+swarm_status swarm_map_requests_streams(swarm_ctx* ctx, const int32_t* idx, int64_t steps, int32_t B, int32_t H, int32_t k, int32_t N,
+                                        const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
+                                        const int32_t* weight, const uint32_t* resident,
+                                        int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap);
+
+/*
  * Medoid-indexed retrieval (Section 5.2, Tier 1: the medoid of each cluster is its index entry and is
  * scored against the query to decide whether the cluster is retrieved; Section 6.1: the activated
  * clusters are merged into the set of entries to transfer, which the mapping step routes entry by

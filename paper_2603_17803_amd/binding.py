@@ -20,7 +20,7 @@ SWARM_DEV_BAD_ENTRY, SWARM_DEV_BAD_CLUSTER, SWARM_DEV_BAD_SSD, SWARM_DEV_CAP, SW
 SWARM_DEV_BAD_OFFSETS, SWARM_DEV_OVERFLOW = 32, 64
 
 EXPORTS = ["swarm_create", "swarm_destroy", "swarm_last_error", "swarm_source_hash", "swarm_device_status", "swarm_score", "swarm_score_select", "swarm_score_select_static",
-           "swarm_coact_accumulate", "swarm_coact_build_density", "swarm_map_requests", "swarm_coact_density", "swarm_window_assign", "swarm_score_select_indexed", "swarm_expand_clusters",
+           "swarm_coact_accumulate", "swarm_coact_build_density", "swarm_map_requests", "swarm_map_requests_streams", "swarm_coact_density", "swarm_window_assign", "swarm_score_select_indexed", "swarm_expand_clusters",
            "swarm_submission_order", "swarm_step", "swarm_calibrate", "swarm_capture_begin", "swarm_capture_end",
            "swarm_graph_launch", "swarm_graph_destroy"]
 
@@ -60,6 +60,7 @@ def load() -> C.CDLL:
     L.swarm_score.argtypes = [vp, C.POINTER(swarm_keys), vp, i32, vp]
     L.swarm_coact_accumulate.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, u32]
     L.swarm_map_requests.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
+    L.swarm_map_requests_streams.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_step.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, i32]
     L.swarm_coact_build_density.argtypes = [vp, vp, i64, i32, i32, i32, vp, u32, C.c_double, u32, vp, vp, vp]
     L.swarm_coact_density.argtypes = [vp, vp, i32, i32, vp, C.c_double, C.c_uint32, vp, vp, vp]
@@ -201,6 +202,14 @@ def swarm_map_requests(ctx: int, sel: int, groups: int, S: int, H: int, N: int, 
     return load().swarm_map_requests(C.c_void_p(ctx), C.c_void_p(sel), groups, S, H, N, C.c_void_p(e2c), Nc,
                                      C.c_void_p(replicas), R, D, C.c_void_p(weight), C.c_void_p(resident),
                                      C.c_void_p(q_off), C.c_void_p(q_cluster), C.c_void_p(q_load), cap)
+
+
+def swarm_map_requests_streams(ctx: int, idx: int, steps: int, B: int, H: int, k: int, N: int, e2c: int, Nc: int, replicas: int,
+                               R: int, D: int, weight: Optional[int], resident: Optional[int], q_off: int, q_cluster: int,
+                               q_load: int, cap: int) -> int:
+    return load().swarm_map_requests_streams(C.c_void_p(ctx), C.c_void_p(idx), steps, B, H, k, N, C.c_void_p(e2c), Nc,
+                                             C.c_void_p(replicas), R, D, C.c_void_p(weight), C.c_void_p(resident),
+                                             C.c_void_p(q_off), C.c_void_p(q_cluster), C.c_void_p(q_load), cap)
 
 
 def swarm_capture_begin(ctx: int) -> int:
@@ -455,6 +464,37 @@ class Swarm:
                                 self._dev(q_load, torch.int32, "q_load"), cap)
         self._check("swarm_map_requests", rc)
         return q_off, q_cluster, q_load
+
+    def map_requests_streams(self, idx, N: int, e2c, Nc: int, replicas, D: int, weight=None, resident=None,
+                             cap: Optional[int] = None, out=None):
+        """idx int32 [steps][B][H][k] (or [B][H][k] for one step), as score_select writes it: the B streams of a step
+        are merged per head.  Returns (q_off [steps*H][D+1], q_cluster [steps*H][cap], q_load [steps*H][D])."""
+        torch = self.torch
+        if idx.dim() == 3:
+            idx = idx.unsqueeze(0)
+        steps, B, H, k = idx.shape
+        R = replicas.shape[1]
+        if tuple(e2c.shape) != (H, N) or tuple(replicas.shape) != (H * Nc, R):
+            raise ValueError("e2c must be [H][N] and replicas [H*Nc][R]")
+        if weight is not None and tuple(weight.shape) != (H * Nc,):
+            raise ValueError("weight must be [H*Nc]")
+        if resident is not None and resident.numel() < (H * Nc + 31) // 32:
+            raise ValueError("resident bitmap too short")
+        if cap is None:
+            cap = min(B * k, Nc)
+        if out is None:
+            out = (torch.empty((steps * H, D + 1), dtype=torch.int32, device=self.device),
+                   torch.empty((steps * H, cap), dtype=torch.int32, device=self.device),
+                   torch.empty((steps * H, D), dtype=torch.int32, device=self.device))
+        q_off, q_cluster, q_load = out
+        rc = swarm_map_requests_streams(self.ctx, self._dev(idx, torch.int32, "idx"), steps, B, H, k, N,
+                                        self._dev(e2c, torch.int32, "e2c"), Nc, self._dev(replicas, torch.int32, "replicas"), R, D,
+                                        None if weight is None else self._dev(weight, torch.int32, "weight"),
+                                        None if resident is None else self._dev(resident, (torch.int32, torch.uint32), "resident"),
+                                        self._dev(q_off, torch.int32, "q_off"), self._dev(q_cluster, torch.int32, "q_cluster"),
+                                        self._dev(q_load, torch.int32, "q_load"), cap)
+        self._check("swarm_map_requests_streams", rc)
+        return out
 
     def step(self, kind: str, keys, q, k: int, e2c, Nc: int, replicas, D: int, G: int = 1, weight=None, resident=None,
              cap: Optional[int] = None, out_idx=None, out_scores=None, want_scores: bool = False, out=None):

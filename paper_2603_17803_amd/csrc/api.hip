@@ -353,6 +353,21 @@ swarm_status swarm_map_requests(swarm_ctx* ctx, const int32_t* sel, int64_t grou
                       cap);
 }
 
+swarm_status swarm_map_requests_streams(swarm_ctx* ctx, const int32_t* idx, int64_t steps, int32_t B, int32_t H, int32_t k, int32_t N,
+                                        const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
+                                        const int32_t* weight, const uint32_t* resident,
+                                        int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int32_t cap) {
+    SWARM_ENTER(ctx);
+    if (!idx) SWARM_REJECT(ctx, "map_requests_streams: NULL idx");
+    if (steps < 1 || B < 1 || k < 1 || H < 1) SWARM_REJECT(ctx, "map_requests_streams: steps=%lld B=%d H=%d k=%d must all be >= 1", (long long)steps, B, H, k);
+    if ((int64_t)B * k > ((int64_t)1 << 24) || (int64_t)H * k > ((int64_t)1 << 30) || steps * H > ((int64_t)1 << 30))
+        SWARM_REJECT(ctx, "map_requests_streams: B*k above 2^24, H*k above 2^30 or steps*H above 2^30");
+    const swarm_status st = check_map_args(ctx, "map_requests_streams", steps * H, B * k, H, N, e2c, Nc, replicas, R, D, q_off, q_cluster,
+                                           q_load, cap);
+    if (st != SWARM_OK) return st;
+    return launch_map(ctx, idx, steps * H, B * k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, k);
+}
+
 swarm_status swarm_step(swarm_ctx* ctx, const swarm_keys* keys, const void* q, int32_t k, int32_t* out_idx,
                         float* out_scores, const int32_t* e2c, int32_t Nc, const int32_t* replicas, int32_t R, int32_t D,
                         const int32_t* weight, const uint32_t* resident, int32_t* q_off, int32_t* q_cluster,

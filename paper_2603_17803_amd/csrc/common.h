@@ -102,7 +102,7 @@ swarm_status launch_coact_popcount(swarm_ctx* ctx, int H, int N, int Npad, int n
 size_t map_lds_base_bytes(int Nc, int cap);   // on-chip staging of the mapping step before any table is staged
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
-                        const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap);
+                        const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap, int piece = 0);
 swarm_status launch_density(swarm_ctx* ctx, const int32_t* C, int H, int N, const int64_t* totals_in, double tau,
                             uint32_t flags, int32_t* rho, int32_t* queue, int64_t* totals);
 swarm_status launch_window(swarm_ctx* ctx, int nruns, int Npad, int N, int W, int H, const int32_t* new_ids, int n_new,

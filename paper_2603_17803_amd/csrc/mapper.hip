@@ -29,6 +29,8 @@ struct MapArgs {
     const int32_t* weight; const uint32_t* resident; int32_t* q_off; int32_t* q_cluster; int32_t* q_load; int cap;
     uint32_t* dev_flags;
     int split_off;      // word offset of the 2 * cap words the split into independent sub-problems needs; 0 = no room, never split
+    int piece;          // strided selections (the streams of a step, as the selection writes them): a group's S entries are
+    int piece_stride;   // pieces of `piece` consecutive ids, `piece_stride` words apart; unused by the contiguous kernels
 };
 
 // Chain over items [0, m) in visiting order.  keybase = (load << 6) | lane.  On return assign[i]
@@ -271,9 +273,15 @@ struct MapLds {
 // BIG: the kernel is meant for long lists (thousands of merged picks, hundreds of clusters): the per-item pass and
 // the SSD adjacency run on every thread and the merge marks bytes.  The short-list kernels leave that code out --
 // it is not only unused there, its mere presence between the phases cost them 0.25 us per launch.
-template <int NT, bool PRESTAGED, bool BIG>
+template <int NT, bool PRESTAGED, bool BIG, bool STRIDED = false>
 __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int32_t* __restrict__ sel, uint32_t* smem,
                                           int stage_e2c, int stage_tab) {
+    // position of the group's s-th entry behind `sel`
+    auto at = [&](int s0) __attribute__((always_inline)) {
+        if (!STRIDED) return s0;
+        const int pc = s0 / a.piece;
+        return pc * a.piece_stride + (s0 - pc * a.piece);
+    };
     const MapLds L(smem, a, stage_e2c, stage_tab);
     const int nwords = L.nwords;
     uint32_t *bitmap = L.bitmap, *list = L.list, *mask_lo = L.mask_lo, *mask_hi = L.mask_hi, *wgt = L.wgt, *order = L.order,
@@ -294,7 +302,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
 #pragma unroll
         for (int r = 0; r < SEL_REGS; ++r) {
             const int s0 = tid + r * NT;
-            my_sel[r] = (s0 < a.S) ? sel[s0] : -1;
+            my_sel[r] = (s0 < a.S) ? sel[at(s0)] : -1;
         }
         if (stage_tab) {
             stage_words<NT>(s_rep, a.replicas + cbase * a.R, a.Nc * a.R, tid);
@@ -370,7 +378,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         for (int s0 = tid + SEL_REGS * NT; s0 < a.S; s0 += MB * NT) {
             int32_t e[MB], c[MB];
 #pragma unroll
-            for (int u = 0; u < MB; ++u) e[u] = (s0 + u * NT < a.S) ? sel[s0 + u * NT] : -1;
+            for (int u = 0; u < MB; ++u) e[u] = (s0 + u * NT < a.S) ? sel[at(s0 + u * NT)] : -1;
 #pragma unroll
             for (int u = 0; u < MB; ++u) c[u] = cluster_of(e[u], staged_tag);
 #pragma unroll
@@ -671,11 +679,14 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
 
 // NT = 256 for a step's selection; 1024 for long merged selections, whose merge is plain per-entry work that
 // scales with the number of threads.
-template <int NT>
+// STRIDED: group g = (step g / H, head g % H) merges the B streams of that step out of selections laid out
+// [step][stream][head][k], the layout the selection step writes.
+template <int NT, bool STRIDED = false>
 __global__ __launch_bounds__(NT) void map_requests_kernel(MapArgs a, int stage_e2c, int stage_tab) {
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
     const int64_t g = blockIdx.x;
-    map_group<NT, false, (NT > 256)>(a, g, a.sel + g * a.S, smem, stage_e2c, stage_tab);
+    const int32_t* sel = STRIDED ? a.sel + (g / a.H) * (int64_t)a.S * a.H + (g % a.H) * a.piece : a.sel + g * a.S;
+    map_group<NT, false, (NT > 256), STRIDED>(a, g, sel, smem, stage_e2c, stage_tab);
 }
 
 // Selection and request mapping of one decode step of a single stream in one kernel: block h selects
@@ -750,10 +761,11 @@ __global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __
 
 size_t map_lds_base_bytes(int Nc, int cap) { return ((size_t)(Nc + 31) / 32 + (size_t)cap * 6 + MAP_AUX_WORDS) * 4; }
 
+// piece > 0: strided selections (see map_requests_kernel), S = streams x piece.
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
-                        const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap) {
-    MapArgs a{sel, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0};
+                        const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap, int piece) {
+    MapArgs a{sel, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0, piece, H * piece};
     size_t lds = map_lds_base_bytes(Nc, cap);
     const size_t budget = 64u * 1024u;
     int stage_tab = 0, stage_e2c = 0;
@@ -762,7 +774,12 @@ swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int 
     if (lds + tab_bytes <= budget) { stage_tab = 1; lds += tab_bytes; }
     if (lds + e2c_bytes <= budget) { stage_e2c = 1; lds += e2c_bytes; }
     if (lds + (size_t)cap * 8 <= budget) { a.split_off = (int)(lds / 4); lds += (size_t)cap * 8; }
-    if (S >= 2048)
+    if (piece > 0 && S >= 2048)
+        hipLaunchKernelGGL((map_requests_kernel<1024, true>), dim3((unsigned)groups), dim3(1024), lds, ctx->stream, a, stage_e2c, stage_tab);
+    else if (piece > 0)
+        hipLaunchKernelGGL((map_requests_kernel<MAP_THREADS, true>), dim3((unsigned)groups), dim3(MAP_THREADS), lds, ctx->stream, a,
+                           stage_e2c, stage_tab);
+    else if (S >= 2048)
         hipLaunchKernelGGL(map_requests_kernel<1024>, dim3((unsigned)groups), dim3(1024), lds, ctx->stream, a, stage_e2c, stage_tab);
     else
         hipLaunchKernelGGL(map_requests_kernel<MAP_THREADS>, dim3((unsigned)groups), dim3(MAP_THREADS), lds, ctx->stream, a, stage_e2c,
@@ -781,7 +798,7 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
     constexpr int NT = selcore::NT;
     const bool sliced = select_uses_slices(H, N, k);       // long rows: the slices' winners first, their selection fused with the mapping
     if (N > 64 * NT && !sliced) return SWARM_OK;
-    MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0};
+    MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0, 0, 0};
     size_t lds = map_lds_base_bytes(Nc, cap);
     const size_t budget = 64u * 1024u;
     lds = (lds + 15) / 16 * 16;

@@ -283,9 +283,9 @@ def test_drifting_batch_full_size_across_phase_changes(sw):
             out_idx = idx_win[t * B:(t + 1) * B]
             want = (t0 + t) in sampled
             _, sc = sw.score_select("page", Kd, dev(qs[t]), k, G=cfg.G, out_idx=out_idx, want_scores=want)
-            sel = out_idx.permute(1, 0, 2).reshape(H, B * k).contiguous()          # the 64 streams of a step merged per head
-            got = sw.map_requests(sel, H, N, e2c_d, cfg.Nc, rep_d, cfg.D, w_d)
+            got = sw.map_requests_streams(out_idx, N, e2c_d, cfg.Nc, rep_d, cfg.D, w_d)    # the 64 streams of a step merged per head
             if want:
+                sel = out_idx.permute(1, 0, 2).reshape(H, B * k).contiguous()
                 sc_h = sc.cpu().numpy()
                 _, ref64, ab = oracle.score("page", K, qs[t], G=cfg.G, nthreads=16)
                 tol = np.maximum(1e-3 * np.abs(ref64), 2 * cfg.d * cfg.G * 2.0 ** -24 * ab)

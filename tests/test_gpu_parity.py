@@ -313,6 +313,35 @@ def test_map_queues_bit_exact(sw, cfg, groups, S, rnd, use_w):
     assert sw.device_status() == 0
 
 
+STREAM_MAP_CASES = [
+    # cfg (H, N, Nc, D, R from it), steps, B, k
+    (W.CONFIGS["llama8b_32k"], 3, 1, 128),                        # one stream: the plain per-step mapping
+    (W.CONFIGS["drift_batch"].scaled(N=300, Nc=60, M=60), 2, 5, 17),   # short merged lists (the 256-thread kernel), ragged sizes
+    (W.CONFIGS["drift_batch"], 2, 64, 128),                       # the drifting batch's own shape: 8192 merged picks per group
+    (W.CONFIGS["drift_batch"].scaled(H=3, N=1000, Nc=200, M=200), 4, 19, 113),   # heads not a power of two, odd piece length
+]
+
+
+@pytest.mark.parametrize("cfg,steps,B,k", STREAM_MAP_CASES, ids=lambda v: v.name if isinstance(v, W.Config) else str(v))
+def test_map_of_merged_streams_bit_exact(sw, cfg, steps, B, k):
+    """swarm_map_requests_streams reads the selections as the selection step writes them ([step][stream][head][k]) and
+    merges a step's streams per head: the queues of the oracle, and of swarm_map_requests, on the transposed lists."""
+    H, N = cfg.H, cfg.N
+    e2c, weight, rep = W.cluster_tables(cfg)
+    idx = W.random_selections(steps * B, H, k, N, seed=B * 1000 + k).reshape(steps, B, H, k)
+    merged = np.ascontiguousarray(idx.transpose(0, 2, 1, 3)).reshape(steps * H, B * k)       # group (step, head): all streams' picks
+    rng = np.random.default_rng(7)
+    resident = rng.integers(0, 2 ** 32, size=(H * cfg.Nc + 31) // 32, dtype=np.uint64).astype(np.uint32)
+    resident &= rng.integers(0, 2 ** 32, size=resident.size, dtype=np.uint64).astype(np.uint32)
+    for res in (None, resident):
+        ref = oracle.map_requests(merged, H, N, e2c, cfg.Nc, rep, cfg.D, weight, res, nthreads=8)
+        got = sw.map_requests_streams(dev(idx), N, dev(e2c), cfg.Nc, dev(rep), cfg.D, dev(weight), None if res is None else dev(res))
+        two = sw.map_requests(dev(merged), H, N, dev(e2c), cfg.Nc, dev(rep), cfg.D, dev(weight), None if res is None else dev(res))
+        for g_, t_, r_ in zip(got, two, ref):
+            assert np.array_equal(g_.cpu().numpy(), r_) and np.array_equal(t_.cpu().numpy(), r_)
+    assert sw.device_status() == 0
+
+
 def test_map_variable_replication_and_heavy_weights(sw):
     rng = np.random.default_rng(5)
     H, N, Nc, D, R = 2, 400, 50, 6, 4
