@@ -697,14 +697,13 @@ __global__ __launch_bounds__(NT) void map_requests_kernel(MapArgs a, int stage_e
 // that and is 16-byte aligned).
 // CAND: second stage of the sliced selection of a long row -- the keys are the scores of the M listed winners of
 // the row's slices (ascending entry id), and the selected list positions are turned back into entry ids.
-template <int IPT, bool CAND>
-__global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __restrict__ scores, int N, int k,
-                                                                 int32_t* __restrict__ out_idx, MapArgs a, int stage_e2c,
-                                                                 int stage_tab, int sel_off, const int32_t* __restrict__ cand,
-                                                                 int cand_stride, int M) {
-    __shared__ selcore::Smem sm;
+template <int IPT, bool CAND, int NT = selcore::NT>
+__global__ __launch_bounds__(NT) void select_map_kernel(const float* __restrict__ scores, int N, int k,
+                                                        int32_t* __restrict__ out_idx, MapArgs a, int stage_e2c,
+                                                        int stage_tab, int sel_off, const int32_t* __restrict__ cand,
+                                                        int cand_stride, int M) {
+    __shared__ selcore::SmemT<NT> sm;
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
-    constexpr int NT = selcore::NT;
     const int tid = threadIdx.x;
     const int h = blockIdx.x;                                 // one stream: group = head
     const int64_t cbase = (int64_t)h * a.Nc;
@@ -736,7 +735,7 @@ __global__ __launch_bounds__(selcore::NT) void select_map_kernel(const float* __
     }
     for (int w = tid; w < L.nwords; w += NT) L.bitmap[w] = 0;
 
-    selcore::block_select<IPT>(key, CAND ? M : N, k, sel_lds, sm);
+    selcore::block_select<IPT, NT>(key, CAND ? M : N, k, sel_lds, sm);
     if (CAND) {
         __syncthreads();
         for (int i = tid; i < k; i += NT) sel_lds[i] = c[sel_lds[i]];
@@ -795,12 +794,13 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
                                const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap,
                                bool* launched) {
     *launched = false;
-    constexpr int NT = selcore::NT;
     const bool sliced = select_uses_slices(H, N, k);       // long rows: the slices' winners first, their selection fused with the mapping
+    // short rows select with smaller blocks, four scores per thread (see launch_select)
+    const int NT = sliced ? selcore::NT : N <= 4 * 256 ? 256 : N <= 4 * 512 ? 512 : selcore::NT;
     if (N > 64 * NT && !sliced) return SWARM_OK;
     MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0, 0, 0};
     size_t lds = map_lds_base_bytes(Nc, cap);
-    const size_t budget = 64u * 1024u;
+    const size_t budget = 64u * 1024u;                     // dynamic part; the selection's static 12.6 KiB come on top
     lds = (lds + 15) / 16 * 16;
     int stage_tab = 0, stage_e2c = 0;
     const size_t tab_bytes = ((size_t)Nc * R + 3) / 4 * 16 + ((size_t)Nc + 3) / 4 * 16, e2c_bytes = ((size_t)N + 3) / 4 * 16;
@@ -828,16 +828,18 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
         else if (M <= 32 * NT) SWARM_MERGEMAP(32);
         else SWARM_MERGEMAP(64);
 #undef SWARM_MERGEMAP
-        *launched = true;
-        return swarm_check_launch(ctx, "select_map_kernel");
+        *launched = hipGetLastError() == hipSuccess;      // a refused launch (e.g. its LDS request) leaves the two-kernel route to the caller
+        return SWARM_OK;
     }
 #define SWARM_SELMAP(IPT) hipLaunchKernelGGL((select_map_kernel<IPT, false>), grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off, nullptr, 0, 0)
-    if (N <= 4 * NT) SWARM_SELMAP(4);
+    if (NT == 256) hipLaunchKernelGGL((select_map_kernel<4, false, 256>), grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off, nullptr, 0, 0);
+    else if (NT == 512) hipLaunchKernelGGL((select_map_kernel<4, false, 512>), grid, block, lds, st, scores, N, k, out_idx, a, stage_e2c, stage_tab, sel_off, nullptr, 0, 0);
+    else if (N <= 4 * NT) SWARM_SELMAP(4);
     else if (N <= 8 * NT) SWARM_SELMAP(8);
     else if (N <= 16 * NT) SWARM_SELMAP(16);
     else if (N <= 32 * NT) SWARM_SELMAP(32);
     else SWARM_SELMAP(64);
 #undef SWARM_SELMAP
-    *launched = true;
-    return swarm_check_launch(ctx, "select_map_kernel");
+    *launched = hipGetLastError() == hipSuccess;          // a refused launch leaves the two-kernel route to the caller
+    return SWARM_OK;
 }

@@ -25,20 +25,22 @@ namespace selcore {
 
 using waveops::wave_incl_scan;
 
-constexpr int NT = 1024;        // threads per selecting block
-constexpr int NW = NT / 64;     // waves
+constexpr int NT = 1024;        // threads per selecting block (default form)
 constexpr int NB = 2048;        // value bins
 constexpr int CMAX = 1024;      // candidates ranked pairwise
 
-struct Smem {
+template <int NTH = NT>
+struct SmemT {
+    static constexpr int NW = NTH / 64;
     uint32_t hist[NB];
     uint32_t cand[CMAX];
-    uint32_t wave_a[NW], wave_b[NW];
-    __attribute__((aligned(16))) uint32_t wave_kmax[NW];
-    __attribute__((aligned(16))) uint32_t wave_kmin[NW];
+    uint32_t wave_a[16], wave_b[16];
+    __attribute__((aligned(16))) uint32_t wave_kmax[16];
+    __attribute__((aligned(16))) uint32_t wave_kmin[16];
     uint32_t cand_count, bstar, above, thr_key, thr_need;
     uint32_t digit, digit_above;
 };
+using Smem = SmemT<NT>;
 
 // Monotone map fp32 -> uint32: larger float <=> larger key.  -0 maps to the key of +0; every
 // NaN maps to key 0, below -inf.
@@ -64,19 +66,21 @@ __device__ __forceinline__ int bin_of(uint32_t key, float hi, float scale) {
 }
 
 
-// Exclusive block scan of two counters at once.  The 16 wave totals are scanned by every wave on its own (lane l reads
-// total l % 16, four DPP steps inside the row of 16 lanes) instead of being read and conditionally added one by one.
-__device__ __forceinline__ void block_excl_scan2(uint32_t a, uint32_t b, uint32_t& ea, uint32_t& eb, Smem& sm,
+// Exclusive block scan of two counters at once.  The wave totals (at most 16) are scanned by every wave on its own (lane l
+// reads total l % 16, four DPP steps inside the row of 16 lanes) instead of being read and conditionally added one by one.
+template <int NTH>
+__device__ __forceinline__ void block_excl_scan2(uint32_t a, uint32_t b, uint32_t& ea, uint32_t& eb, SmemT<NTH>& sm,
                                                  int lane, int wave) {
-    static_assert(NW == 16, "one wave total per lane of a DPP row");
+    constexpr int NW = NTH / 64;
+    static_assert(NW >= 1 && NW <= 16, "one wave total per lane of a DPP row");
     const uint32_t ia = wave_incl_scan(a), ib = wave_incl_scan(b);
     if (lane == 63) { sm.wave_a[wave] = ia; sm.wave_b[wave] = ib; }
     __syncthreads();
-    uint32_t ta = sm.wave_a[lane & 15], tb = sm.wave_b[lane & 15];
+    uint32_t ta = (lane & 15) < NW ? sm.wave_a[lane & 15] : 0u, tb = (lane & 15) < NW ? sm.wave_b[lane & 15] : 0u;
     ta += waveops::dpp_or_zero<0x111, 0xF>(ta);  tb += waveops::dpp_or_zero<0x111, 0xF>(tb);     // row_shr:1
     ta += waveops::dpp_or_zero<0x112, 0xF>(ta);  tb += waveops::dpp_or_zero<0x112, 0xF>(tb);     // row_shr:2
-    ta += waveops::dpp_or_zero<0x114, 0xF>(ta);  tb += waveops::dpp_or_zero<0x114, 0xF>(tb);     // row_shr:4
-    ta += waveops::dpp_or_zero<0x118, 0xF>(ta);  tb += waveops::dpp_or_zero<0x118, 0xF>(tb);     // row_shr:8: totals of waves 0..l
+    if (NW > 4) { ta += waveops::dpp_or_zero<0x114, 0xF>(ta);  tb += waveops::dpp_or_zero<0x114, 0xF>(tb); }    // row_shr:4
+    if (NW > 8) { ta += waveops::dpp_or_zero<0x118, 0xF>(ta);  tb += waveops::dpp_or_zero<0x118, 0xF>(tb); }    // row_shr:8: totals of waves 0..l
     const int prev = wave > 0 ? wave - 1 : 0;
     const uint32_t pa = (uint32_t)__builtin_amdgcn_readlane((int)ta, prev), pb = (uint32_t)__builtin_amdgcn_readlane((int)tb, prev);
     ea = ia - a + (wave > 0 ? pa : 0u);
@@ -84,11 +88,16 @@ __device__ __forceinline__ void block_excl_scan2(uint32_t a, uint32_t b, uint32_
 }
 
 // key[e] is the key of index tid*IPT + e; slots at or beyond N must hold key 0.
-// All NT threads of the block must call this.  out receives k ascending indices.
+// All NTH threads of the block must call this.  out receives k ascending indices.
 // index_offset is added to every emitted index (a block selecting inside a slice of a longer row).
-template <int IPT>
+// Short per-thread runs keep every score's bin in a register after the histogram pass (the candidate collection and
+// the compaction then compare small integers); long runs recompute it, their registers hold the keys.
+template <int IPT, int NTH = NT>
 __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, int k, int32_t* __restrict__ out,
-                                             Smem& sm, int index_offset = 0) {
+                                             SmemT<NTH>& sm, int index_offset = 0) {
+    constexpr int NW = NTH / 64;
+    constexpr bool KEEP = IPT <= 32;                    // bins kept in registers
+    constexpr int NBINS_KEPT = KEEP ? IPT : 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int base = tid * IPT;
 
@@ -104,18 +113,20 @@ __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, 
     kmax = ~waveops::wave_min_u32(~kmax);
     kmin = waveops::wave_min_u32(kmin);
     if (lane == 0) { sm.wave_kmax[wave] = kmax; sm.wave_kmin[wave] = kmin; }
-    sm.hist[tid] = 0;
-    sm.hist[tid + NT] = 0;
+#pragma unroll
+    for (int i = 0; i < NB / NTH; ++i) sm.hist[tid + i * NTH] = 0;
     if (tid == 0) { sm.cand_count = 0; sm.thr_key = 0; sm.thr_need = 0xffffffffu; }
     __syncthreads();
     {
         const uint4* pmax = reinterpret_cast<const uint4*>(sm.wave_kmax);
         const uint4* pmin = reinterpret_cast<const uint4*>(sm.wave_kmin);
 #pragma unroll
-        for (int w = 0; w < NW / 4; ++w) {
+        for (int w = 0; w < (NW + 3) / 4; ++w) {
             const uint4 a = pmax[w], b = pmin[w];
-            kmax = max(max(kmax, a.x), max(a.y, max(a.z, a.w)));
-            kmin = min(min(kmin, b.x), min(b.y, min(b.z, b.w)));
+            if (4 * w + 0 < NW) { kmax = max(kmax, a.x); kmin = min(kmin, b.x); }
+            if (4 * w + 1 < NW) { kmax = max(kmax, a.y); kmin = min(kmin, b.y); }
+            if (4 * w + 2 < NW) { kmax = max(kmax, a.z); kmin = min(kmin, b.z); }
+            if (4 * w + 3 < NW) { kmax = max(kmax, a.w); kmin = min(kmin, b.w); }
         }
     }
     // an empty row (N = 0) leaves kmax < kmin: hi < lo, and the scale below becomes 0
@@ -124,17 +135,31 @@ __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, 
     const float scale = range > 0.f ? fminf((float)NB / range, 1.0e30f) : 0.f;
 
     // value histogram
+    int bin[NBINS_KEPT];
+    auto bin_at = [&](int e) __attribute__((always_inline)) { return KEEP ? bin[e] : bin_of(key[e], hi, scale); };
 #pragma unroll
-    for (int e = 0; e < IPT; ++e) atomicAdd(&sm.hist[bin_of(key[e], hi, scale)], 1u);
+    for (int e = 0; e < IPT; ++e) {
+        const int b = bin_of(key[e], hi, scale);
+        if (KEEP) bin[e] = b;
+        atomicAdd(&sm.hist[b], 1u);
+    }
     __syncthreads();
 
     // bin b* holding the k-th largest: cumulative count from bin 0 (highest scores) first reaches k
     {
-        const uint32_t h0 = sm.hist[2 * tid], h1 = sm.hist[2 * tid + 1];
+        constexpr int PER = NB / NTH;                   // consecutive bins per thread
+        uint32_t hh[PER], sum = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { hh[i] = sm.hist[PER * tid + i]; sum += hh[i]; }
         uint32_t before, unused;
-        block_excl_scan2(h0 + h1, 0u, before, unused, sm, lane, wave);
-        if (before < (uint32_t)k && (uint32_t)k <= before + h0) { sm.bstar = 2 * tid; sm.above = before; }
-        else if (before + h0 < (uint32_t)k && (uint32_t)k <= before + h0 + h1) { sm.bstar = 2 * tid + 1; sm.above = before + h0; }
+        block_excl_scan2<NTH>(sum, 0u, before, unused, sm, lane, wave);
+        if (before < (uint32_t)k && (uint32_t)k <= before + sum) {
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                if (before < (uint32_t)k && (uint32_t)k <= before + hh[i]) { sm.bstar = PER * tid + i; sm.above = before; }
+                before += hh[i];
+            }
+        }
     }
     __syncthreads();
     const int bstar = (int)sm.bstar;
@@ -146,10 +171,10 @@ __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, 
             // rank the candidates of b* against each other
 #pragma unroll
             for (int e = 0; e < IPT; ++e)
-                if (bin_of(key[e], hi, scale) == bstar) sm.cand[atomicAdd(&sm.cand_count, 1u)] = key[e];
+                if (bin_at(e) == bstar) sm.cand[atomicAdd(&sm.cand_count, 1u)] = key[e];
             __syncthreads();
-            if ((uint32_t)tid < c) {
-                const uint32_t mine = sm.cand[tid];
+            for (uint32_t t = tid; t < c; t += NTH) {
+                const uint32_t mine = sm.cand[t];
                 uint32_t gt = 0, eq = 0;
                 for (uint32_t j = 0; j < c; ++j) {
                     const uint32_t other = sm.cand[j];
@@ -168,7 +193,7 @@ __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, 
                 __syncthreads();
 #pragma unroll
                 for (int e = 0; e < IPT; ++e)
-                    if (bin_of(key[e], hi, scale) == bstar && (key[e] & mask) == prefix)
+                    if (bin_at(e) == bstar && (key[e] & mask) == prefix)
                         atomicAdd(&sm.hist[(key[e] >> shift) & 255u], 1u);
                 __syncthreads();
                 if (wave == 0) {
@@ -201,27 +226,45 @@ __device__ __forceinline__ void block_select(const uint32_t (&key)[IPT], int N, 
     }
     const uint32_t T = sm.thr_key, need_eq = sm.thr_need;   // need == c: T = 0, every candidate is taken
 
-    // ordered compaction
+    // ordered compaction.  A score is taken outright when it lies in a bin above b*, or in b* above the threshold key;
+    // scores equal to the threshold key are taken in index order until need_eq of them are in.
     uint32_t gt = 0, eq = 0;
+    uint32_t take_mask = 0, eq_mask = 0;                // bit e (KEEP only; IPT <= 32)
 #pragma unroll
     for (int e = 0; e < IPT; ++e) {
-        const int b = bin_of(key[e], hi, scale);
-        gt += (b < bstar) || (b == bstar && key[e] > T);
-        eq += (b == bstar && key[e] == T);
+        const int b = bin_at(e);
+        const bool g = (b < bstar) || (b == bstar && key[e] > T);
+        const bool q = (b == bstar && key[e] == T);
+        gt += g;
+        eq += q;
+        if (KEEP) { take_mask |= (uint32_t)g << e; eq_mask |= (uint32_t)q << e; }
     }
     uint32_t gt_before, eq_before;
-    block_excl_scan2(gt, eq, gt_before, eq_before, sm, lane, wave);
+    block_excl_scan2<NTH>(gt, eq, gt_before, eq_before, sm, lane, wave);
     uint32_t pos = gt_before + min(eq_before, need_eq);
-    uint32_t eq_seen = eq_before;
-#pragma unroll
-    for (int e = 0; e < IPT; ++e) {
-        const int b = bin_of(key[e], hi, scale);
-        const bool is_eq = (b == bstar && key[e] == T);
-        const bool take = (b < bstar) || (b == bstar && key[e] > T) || (is_eq && eq_seen < need_eq);
-        eq_seen += is_eq;
-        if (take) {
+    if (KEEP) {
+        // the equal scores this thread still takes: its first (need_eq - eq_before) of them
+        const uint32_t room = need_eq > eq_before ? need_eq - eq_before : 0u;
+        uint32_t m = eq_mask;
+        for (uint32_t i = 0; i < room && m; ++i) { take_mask |= m & (0u - m); m &= m - 1u; }
+        while (take_mask) {
+            const int e = __ffs(take_mask) - 1;
+            take_mask &= take_mask - 1u;
             if (pos < (uint32_t)k) out[pos] = index_offset + base + e;     // pos < k always holds; the guard keeps a slip in bounds
             ++pos;
+        }
+    } else {
+        uint32_t eq_seen = eq_before;
+#pragma unroll
+        for (int e = 0; e < IPT; ++e) {
+            const int b = bin_of(key[e], hi, scale);
+            const bool is_eq = (b == bstar && key[e] == T);
+            const bool take = (b < bstar) || (b == bstar && key[e] > T) || (is_eq && eq_seen < need_eq);
+            eq_seen += is_eq;
+            if (take) {
+                if (pos < (uint32_t)k) out[pos] = index_offset + base + e;
+                ++pos;
+            }
         }
     }
 }
