@@ -101,7 +101,13 @@ swarm_status swarm_device_status(swarm_ctx* ctx, uint32_t* flags);
  *   token keys:      s[b][h][n] = sum_g sum_c q[b][h*G+g][c] * K[h][n][c]
  *   page summaries:  s[b][h][n] = sum_g sum_c max(q_c * min[h][n][c], q_c * max[h][n][c])
  *                    (channel-wise upper bound of the inner product over the page's box)
- *   products of two bf16 values are exact in fp32; accumulation is fp32.
+ *   Products of two bf16 values are exact in fp32 and are accumulated in fp32.  A page term is computed as
+ *   min(q_c,0) * min_c + max(q_c,0) * max_c, which equals max(q_c * min_c, q_c * max_c) when the summary is finite
+ *   and min_c <= max_c -- the precondition of page scoring: an infinite or NaN summary channel, or min_c > max_c,
+ *   gives a score that differs from the formula above (a zero weight times an infinity is NaN).  With up to seven
+ *   streams the G query heads of a group are first added into fp32 weights (one rounding per head), then multiplied;
+ *   with eight or more streams every query head is its own exact bf16 operand of the bf16 matrix cores and the heads
+ *   add in their fp32 accumulators.  Either way a score differs from the exact sum by fp32 accumulation error only.
  *   select: the k largest of s[b][h][0..N); equal scores are won by the lower index; -0 equals
  *   +0; NaN ranks below every number.  The k indices come out in ascending order.
  *
