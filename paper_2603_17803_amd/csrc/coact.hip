@@ -46,7 +46,8 @@ __global__ __launch_bounds__(1024) void trace_build_kernel(const int32_t* __rest
     const int e0 = blockIdx.z * TRACE_SPAN;
     const int span = min(TRACE_SPAN, Npad - e0);
     uint32_t* fresh = words + span * 4;
-    for (int i = threadIdx.x; i < span * 4 + (COUNT ? 128 : 0); i += blockDim.x) words[i] = 0u;
+    for (int i = threadIdx.x; i < span; i += blockDim.x) reinterpret_cast<uint4*>(words)[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (COUNT && threadIdx.x < 128) fresh[threadIdx.x] = 0u;
     __syncthreads();
     const int64_t row0 = (int64_t)run * 128;
     const int nrows = (int)min((int64_t)128, rows - row0);                       // <= 0 for a run of pure padding
