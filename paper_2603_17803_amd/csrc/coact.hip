@@ -4,10 +4,10 @@
 // The trace is binary, so it is kept in memory as bits: for every head and every run of 128 trace
 // rows one 16-byte word per entry, bits[h][run][entry], one bit per trace row of the run (rows 32w ..
 // 32w+31 in dword w, in the order of trace_bit below).  Both operands of the product are entry panels of this one array.  On the way
-// to the matrix cores a workgroup expands the bits of its two entry panels to rows of 4-bit 0/1
-// operands in LDS (contraction index contiguous), and the product runs on the 4-bit form of
-// v_mfma_f32_32x32x64_f8f6f4, exact for these operands (see below).  Feeding expanded operands from
-// memory instead would multiply the traffic through the L2 by four to eight; the bit form keeps a
+// to the matrix cores the bits are expanded to 4-bit 0/1 operands -- the 256 tile rows by the workgroup, into LDS
+// (contraction index contiguous), the 64 tile columns of a wave by the wave itself, in registers -- and the product
+// runs on the 4-bit form of v_mfma_f32_32x32x64_f8f6f4, exact for these operands (see below).  Feeding expanded
+// operands from memory instead would multiply the traffic through the L2 by four to eight; the bit form keeps a
 // smaller tile affordable.
 // C is symmetric, so only tiles on or above the diagonal are computed and each off-diagonal tile is
 // stored twice (once transposed).
@@ -131,12 +131,10 @@ __device__ __forceinline__ int32_t updated_count(int32_t old, int32_t v, uint32_
 constexpr int TM = 256;                        // C tile rows per workgroup
 constexpr int TN = 128;                        // C tile columns per workgroup
 constexpr int KC = 64;                         // contraction BYTES per chunk and operand row: 128 trace rows as 4-bit values, two MFMA k-steps of 64
-constexpr int A_BYTES = TM * KC;               // operand panels of one chunk in LDS
-constexpr int B_BYTES = TN * KC;
-constexpr int BUF_BYTES = A_BYTES + B_BYTES;   // 24 KiB; two of them form the ring
+constexpr int A_BYTES = TM * KC;               // A operand panel of one chunk in LDS: 16 KiB; two of them form the ring
 constexpr int TROW = 512 + 16;                 // epilogue staging row, padded: the 16-byte slots of 8 consecutive lanes differ
 constexpr int SYRK_LDS_BYTES = 4 * 32 * TROW;  // 66 KiB: the epilogue's staging (one 32-column block per wave) is the larger user
-static_assert(SYRK_LDS_BYTES >= 2 * BUF_BYTES, "operand ring must fit");
+static_assert(SYRK_LDS_BYTES >= 2 * A_BYTES, "operand ring must fit");
 
 // Operand rows in LDS are 64 bytes; 16-byte piece c of row r lives at slot c ^ swz(r).  Measured on
 // gfx950: a 16-byte LDS read is served 16 consecutive lanes at a time across 64 four-byte banks, a
@@ -161,10 +159,10 @@ __device__ __forceinline__ int lds_off(int row, int piece) { return row * KC + (
 // C tile of 256 x 128 per workgroup of 4 waves (2 x 2, each 128 x 64 = 4 x 2 MFMA tiles, 128
 // accumulator registers), two workgroups per compute unit: while one waits at its hand-over barrier,
 // writes its tile or starts up, the other keeps the matrix cores busy.  The contraction runs in
-// chunks of 128 trace rows (one 16-byte bit word per entry) through a two-deep LDS ring: thread t owns row t
-// of the A panel and half of row t/2 of the B panel; the bit words of the next chunks are in flight from
-// memory (three chunks ahead), those of chunk c+1 are being expanded and written into the idle LDS buffer, chunk c feeds the matrix
-// cores; operand fragments of k-step s+1 are read from LDS while the MFMAs of k-step s run.
+// chunks of 128 trace rows (one 16-byte bit word per entry) through a two-deep LDS ring for the row panel: thread t
+// owns row t of it; the bit words of the next chunks are in flight from memory (three chunks ahead), those of chunk
+// c+1 are being expanded and written into the idle LDS buffer, chunk c feeds the matrix cores; the operands of
+// k-step s+1 are read from LDS (rows) or expanded from the lane's own bit words (columns) while the MFMAs of k-step s run.
 // Because the operands travel as bits, the smaller tile costs next to nothing in memory traffic.
 // Workgroups are numbered so that the eight L2 slices (one per XCD, workgroups are dealt to them
 // round-robin) each walk a contiguous run of the tile schedule.
@@ -196,40 +194,41 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wy = wave >> 1, wx = wave & 1;
 
-    // memory -> registers, one 16-byte word (a run of 128 trace rows = one chunk) per panel row at a
-    // time: thread t takes row t of the A panel and row t/2 of the B panel, of which it expands the
-    // half t%2.  Four register sets, indexed by run number mod 4.
+    // A operand (the 256 tile rows): memory -> registers -> LDS.  Thread t takes row t of the A panel, one 16-byte
+    // word (a run of 128 trace rows = one chunk) at a time, expands it to 4-bit operands and stores the 64 bytes.
+    // B operand (the wave's 64 tile columns): straight from the trace bits in registers.  Lane l supplies row l%32 of
+    // each of the wave's two 32-column blocks with contraction indices [32 (l/32), +32) of a k-step -- which is ONE
+    // 32-bit word of that entry's run (word 2 ks + l/32), expanded by seven vector operations.  Going through LDS
+    // with both panels asked for 1.2 sixteen-byte LDS instructions per MFMA and kept the LDS data path backed up for a
+    // quarter of the run; expanding both panels in every wave asks for more vector instructions than fit beside the MFMAs.
+    // Four register sets, indexed by run number mod 4.
+    const int frow = lane & 31, fhalf = lane >> 5;
     const v4i* panel = bits + (size_t)h * nruns * Npad;
     const v4i* a_src = panel + (size_t)ti * TM + tid;
-    const v4i* b_src = panel + (size_t)tj * TN + (tid >> 1);
-    const bool odd = tid & 1;
-    v4i ba[4], bb[4];
+    const uint32_t* b_src = reinterpret_cast<const uint32_t*>(panel + (size_t)tj * TN + wx * 64 + frow) + fhalf;
+    v4i ba[4];
+    uint32_t bq[4][2][2];                          // [set][column block][k-step]
     const int last_run = nruns - 1;
     auto load_bits = [&](int set, int run) __attribute__((always_inline)) {           // clamped: a redundant reload past the end is harmless
         const size_t off = (size_t)min(run, last_run) * Npad;                           // a minimum, not a select: no branch inside the loop
         ba[set] = a_src[off];
-        bb[set] = b_src[off];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) bq[set][j][ks] = b_src[off * 4 + j * (32 * 4) + ks * 2];
     };
-    // registers -> LDS, in pieces of 16 contraction bytes (32 trace rows = one 32-bit word of the run):
-    // pieces 0..3 are the A row's, 4..5 the two of the B half row.  A piece is expanded one dword (8 trace
-    // rows) at a time and stored when complete.
-    int st_off[6];
+    // registers -> LDS, in pieces of 16 contraction bytes (32 trace rows = one 32-bit word of the run).  A piece is
+    // expanded one dword (8 trace rows) at a time and stored when complete.
+    int st_off[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) st_off[p] = lds_off(tid, p);
-#pragma unroll
-    for (int q = 0; q < 2; ++q) st_off[4 + q] = A_BYTES + lds_off(tid >> 1, 2 * (tid & 1) + q);
     v4i ex;
-    uint32_t bw[2];                                // the thread's half of the B row's words for the chunk being expanded
-    auto pick_b = [&](int set) __attribute__((always_inline)) {
-        bw[0] = (uint32_t)(odd ? bb[set][2] : bb[set][0]);
-        bw[1] = (uint32_t)(odd ? bb[set][3] : bb[set][1]);
-    };
     auto expand_quarter = [&](int set, int piece, int q) __attribute__((always_inline)) {
-        const uint32_t w = piece < 4 ? (uint32_t)ba[set][piece] : bw[piece - 4];
+        const uint32_t w = (uint32_t)ba[set][piece];
         ex[q] = (int)((q ? w >> (q - 1) : w << 1) & 0x22222222u);
     };
     auto store_piece = [&](int buf, int piece) __attribute__((always_inline)) {
-        *reinterpret_cast<v4i*>(lds + buf * BUF_BYTES + st_off[piece]) = ex;
+        *reinterpret_cast<v4i*>(lds + buf * A_BYTES + st_off[piece]) = ex;
     };
 
     v16f facc[4][2];
@@ -241,25 +240,21 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
             for (int r = 0; r < 16; ++r) facc[i][j][r] = 0.f;
     const int unit_scale = 0x7f7f7f7f;             // E8M0 127 = 2^0 in every byte the instruction may pick
 
-    // fragment addressing: lane l reads row l%32 of an MFMA tile, bytes [16*(l/32), +16) of the 32-byte
+    // A fragment addressing: lane l reads row l%32 of an MFMA tile, bytes [16*(l/32), +16) of the 32-byte
     // k-step (64 contraction indices as nibbles).  The swizzle term is the same for rows 32 apart; the tile index is a constant byte offset.
-    const int frow = lane & 31, fhalf = lane >> 5;
-    int fa_base[2], fb_base[2];
+    int fa_base[2];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        fa_base[ks] = lds_off(wy * 128 + frow, 2 * ks + fhalf);
-        fb_base[ks] = A_BYTES + lds_off(wx * 64 + frow, 2 * ks + fhalf);
-    }
+    for (int ks = 0; ks < 2; ++ks) fa_base[ks] = lds_off(wy * 128 + frow, 2 * ks + fhalf);
     v4i fa[2][4], fb[2][2];
-    // fragment number f of a k-step, in the order the MFMAs need them (MFMA m uses A tile m/2, B tile m%2)
-    auto read_frag = [&](int buf, int ks, int set, int f) __attribute__((always_inline)) {
-        const int8_t* base = lds + buf * BUF_BYTES;
-        if (f == 0) fa[set][0] = *reinterpret_cast<const v4i*>(base + fa_base[ks]);
-        else if (f < 3) fb[set][f - 1] = *reinterpret_cast<const v4i*>(base + fb_base[ks] + (f - 1) * 32 * KC);
-        else fa[set][f - 2] = *reinterpret_cast<const v4i*>(base + fa_base[ks] + (f - 2) * 32 * KC);
+    auto read_a = [&](int buf, int ks, int fs, int i) __attribute__((always_inline)) {
+        fa[fs][i] = *reinterpret_cast<const v4i*>(lds + buf * A_BYTES + fa_base[ks] + i * 32 * KC);
     };
-    auto mfma = [&](int set, int m) __attribute__((always_inline)) {
-        const v4i a4 = fa[set][m >> 1], b4 = fb[set][m & 1];
+    auto expand_b = [&](int fs, int set, int ks, int j) __attribute__((always_inline)) {
+        const uint32_t w = bq[set][j][ks];
+        fb[fs][j] = v4i{(int)((w << 1) & 0x22222222u), (int)(w & 0x22222222u), (int)((w >> 1) & 0x22222222u), (int)((w >> 2) & 0x22222222u)};
+    };
+    auto mfma = [&](int fs, int m) __attribute__((always_inline)) {
+        const v4i a4 = fa[fs][m >> 1], b4 = fb[fs][m & 1];
         const v8i a8 = {a4.x, a4.y, a4.z, a4.w, 0, 0, 0, 0}, b8 = {b4.x, b4.y, b4.z, b4.w, 0, 0, 0, 0};   // the 4-bit form reads 4 registers
         facc[m >> 1][m & 1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, facc[m >> 1][m & 1], 4, 4, 0, unit_scale, 0,
                                                                              unit_scale);
@@ -268,49 +263,50 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     load_bits(0, 0);
     load_bits(1, 1);
     load_bits(2, 2);
-    pick_b(0);
 #pragma unroll
-    for (int piece = 0; piece < 6; ++piece) {
+    for (int piece = 0; piece < 4; ++piece) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) expand_quarter(0, piece, q);
         store_piece(0, piece);
     }
     __syncthreads();
 #pragma unroll
-    for (int f = 0; f < 6; ++f) read_frag(0, 0, 0, f);
+    for (int i = 0; i < 4; ++i) read_a(0, 0, 0, i);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) expand_b(0, 0, 0, j);
 
-    // Chunk d (run d of 128 trace rows, bits in register set d%4) computes out of LDS buffer d%2; its own
-    // bits are spent.  The next chunk is expanded into the other LDS buffer, which no wave reads after the
-    // hand-over barrier of the previous chunk; set (d+3)%4 is refilled at the start of the chunk, three
-    // chunks ahead of its use.  The work is laid out as 16 slots, one per MFMA: slot m issues the MFMA, then a
-    // fragment read for the second k-step (first six slots), then its share of the expansion (24 dwords
-    // of 2 operations and 6 LDS stores per chunk, spread over the first 8 slots).  The hand-over
-    // barrier sits after the first k-step (it cannot sit earlier: the reads that follow it refill the
-    // first k-step's fragment registers); the second k-step's MFMAs and the other workgroup on the
-    // compute unit cover the LDS latency of the next chunk's first fragments.
+    // Chunk d (run d of 128 trace rows, bits in register set d%4) computes out of LDS buffer d%2; its own A
+    // bits are spent.  The next chunk's A rows are expanded into the other LDS buffer, which no wave reads after
+    // the hand-over barrier of the previous chunk; set (d+3)%4 is refilled at the start of the chunk, three
+    // chunks ahead of its use.  The work is laid out as 16 slots, one per MFMA: slot m issues the MFMA, then an
+    // operand of the second k-step (an A fragment read in the first four slots, a B fragment expanded in the next
+    // two), then its share of the A expansion (16 dwords of 2 operations and 4 LDS stores per chunk, spread over
+    // the first 8 slots).  The hand-over barrier sits after the first k-step (it cannot sit earlier: the reads that
+    // follow it refill the first k-step's fragment registers); the second k-step's MFMAs and the other workgroup
+    // on the compute unit cover the LDS latency of the next chunk's first fragments.
     auto chunk_body = [&](int d, int set) __attribute__((always_inline)) {   // set = d % 4, passed as a literal
         const int buf = set & 1, nbuf = buf ^ 1;
         const int nset = (set + 1) & 3, lset = (set + 3) & 3;
-        pick_b(nset);
-        constexpr int BAR = 8;                               // MFMA slots before the hand-over barrier: the whole first k-step,
-        static_assert(BAR >= 8 && 24 % BAR == 0, "");          // whose fragment set the reads after the barrier overwrite
 #pragma unroll
-        for (int s = 0; s < BAR; ++s) {
-            mfma(s >> 3, s & 7);
-            if (s < 6) read_frag(buf, 1, 1, s);
+        for (int s = 0; s < 8; ++s) {
+            mfma(0, s);
+            if (s < 4) read_a(buf, 1, 1, s);
+            else if (s < 6) expand_b(1, set, 1, s - 4);
             if (s == 0) load_bits(lset, d + 3);
 #pragma unroll
-            for (int u = (24 / BAR) * s; u < (24 / BAR) * (s + 1); ++u) {
+            for (int u = 2 * s; u < 2 * (s + 1); ++u) {
                 expand_quarter(nset, u >> 2, u & 3);
                 if ((u & 3) == 3) store_piece(nbuf, u >> 2);
             }
         }
         __syncthreads();
 #pragma unroll
-        for (int f = 0; f < 6; ++f) read_frag(nbuf, 0, 0, f);          // after the last chunk this reads stale but valid LDS and is never used
+        for (int i = 0; i < 4; ++i) read_a(nbuf, 0, 0, i);            // after the last chunk this reads stale but valid LDS and is never used
+#pragma unroll
+        for (int j = 0; j < 2; ++j) expand_b(0, nset, 0, j);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int s = BAR; s < 16; ++s) mfma(s >> 3, s & 7);
+        for (int s = 0; s < 8; ++s) mfma(1, s);
     };
     __builtin_amdgcn_s_setprio(2);                          // the contraction outranks the other workgroup's epilogue stores
     for (int d = 0; d < nruns; d += 4) {                    // nruns is a multiple of 4
