@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void calib_mfma_fp4_kernel(int iters, int seed
     const int t = threadIdx.x;
     const v8i_c x = {(seed + t) & 0x22222222, (seed * 3) & 0x22222222, (seed * 5 + t) & 0x22222222, (seed * 7) & 0x22222222, 0, 0, 0, 0};
     const v8i_c y = {(seed * 11) & 0x22222222, (seed + 1) & 0x22222222, (t * seed) & 0x22222222, (seed * 13) & 0x22222222, 0, 0, 0, 0};
-    const int unit = 0x7f7f7f7f;
+    constexpr int unit = 0;                            // no block scales: the unscaled form, as the co-activation kernel issues it
     for (int i = 0; i < iters; ++i) {
 #pragma unroll
         for (int a = 0; a < 16; ++a) acc[a] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(x, y, acc[a], 4, 4, 0, unit, 0, unit);
