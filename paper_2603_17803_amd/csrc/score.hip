@@ -221,8 +221,12 @@ __global__ __launch_bounds__(256) void score_lean_kernel(const u32x4* __restrict
     float v = b1 ? k1 : k0;
     const float sv = b1 ? k0 : k1;
     v += dpp(sv, std::integral_constant<int, 0x4E>{});        // quad_perm [2,3,0,1]
-    v += dpp(v, std::integral_constant<int, 0x124>{});        // row_ror:4  (rotation inside a row of 16 lanes)
-    if (LPR >= 16) v += dpp(v, std::integral_constant<int, 0x128>{});   // row_ror:8
+    if (LPR == 8) {
+        v += __shfl_xor(v, 4, 64);                            // a rotation inside 16 lanes would reach into the neighbouring group of 8
+    } else {
+        v += dpp(v, std::integral_constant<int, 0x124>{});    // row_ror:4  (rotation inside a row of 16 lanes)
+        v += dpp(v, std::integral_constant<int, 0x128>{});    // row_ror:8
+    }
     if (LPR >= 32) v += __shfl_xor(v, 16, 64);
     // lane (b0, b1) of a group now holds row 2 b0 + b1 of its group's four rows
     const int n = row0 + (2 * (int)b0 + (int)(b1 ? 1 : 0)) * RPW;

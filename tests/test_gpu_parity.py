@@ -104,6 +104,13 @@ CASES = [
     W.CONFIGS["tiny"].scaled(d=512, N=64, k=3, T=1),
     W.CONFIGS["llama8b_32k"].scaled(N=1500, k=20, T=1, H=16),                # more heads than XCDs (head-major workgroup order)
     W.CONFIGS["llama8b_32k"].scaled(N=900, k=11, T=1, H=6, B=3),             # heads not a power of two, several streams
+    W.CONFIGS["tiny"].scaled(d=64, N=1000, k=9, T=1, H=2),                   # lean sweep, 8 lanes per row (token rows of 128 bytes)
+    W.CONFIGS["llama8b_32k"].scaled(d=32, N=777, k=13, T=1, H=4),            # lean sweep, 8 lanes per row (page rows of 128 bytes), ragged tail
+    W.CONFIGS["llama8b_32k"].scaled(d=64, N=130, k=7, T=1, H=1),             # lean sweep, 16 lanes per row, one head
+    W.CONFIGS["llama8b_32k"].scaled(N=333, k=20, T=2, H=4, B=3),             # lean sweep, several streams, last workgroup past the rows
+    W.CONFIGS["drift_batch"].scaled(N=100, B=33, G=6, H=2, T=1, k=5),        # matrix-core scorer: two passes over the query heads, a second stream tile of one stream
+    W.CONFIGS["drift_batch"].scaled(N=260, B=8, G=1, H=1, T=1, k=5, d=64),   # matrix-core scorer: page rows of 256 bytes, fewest streams
+    W.CONFIGS["drift_batch"].scaled(N=129, B=12, G=3, H=2, T=1, k=5, unit="token", page_size=1, d=256),   # matrix-core scorer: token rows of 512 bytes
 ]
 
 
