@@ -190,7 +190,8 @@ def test_counts_up_to_the_row_limit_stay_exact(sw):
 def test_select_long_rows_sliced_and_streaming(sw):
     """Few long rows are selected in two stages (slices, then their winners); many rows of more than 65536
     entries take the streaming kernel.  Both against the oracle on the device's own scores."""
-    for B, N, k in ((1, 65536, 1024), (2, 40000, 700), (1, 200000, 300), (40, 66000, 50)):
+    for B, N, k in ((1, 65536, 1024), (2, 40000, 700), (1, 200000, 300), (40, 66000, 50),
+                    (1, 65536, 2000), (1, 65536, 4000), (3, 131072, 3000), (2, 30000, 9000)):   # every width of the winners' merge
         cfg = W.CONFIGS["tiny"].scaled(N=N, k=k, T=1, d=8, B=B)
         K = W.keys(cfg)
         q = W.queries(cfg, 0, 1)[0]

@@ -110,7 +110,10 @@ CASES = [
     W.CONFIGS["llama8b_32k"].scaled(N=333, k=20, T=2, H=4, B=3),             # lean sweep, several streams, last workgroup past the rows
     W.CONFIGS["drift_batch"].scaled(N=100, B=33, G=6, H=2, T=1, k=5),        # matrix-core scorer: two passes over the query heads, a second stream tile of one stream
     W.CONFIGS["drift_batch"].scaled(N=260, B=8, G=1, H=1, T=1, k=5, d=64),   # matrix-core scorer: page rows of 256 bytes, fewest streams
-    W.CONFIGS["drift_batch"].scaled(N=129, B=12, G=3, H=2, T=1, k=5, unit="token", page_size=1, d=256),   # matrix-core scorer: token rows of 512 bytes
+    W.CONFIGS["drift_batch"].scaled(N=129, B=12, G=3, H=2, T=1, k=5, unit="token", page_size=1, d=256),   # matrix-core scorer: token rows of 512 bytes    W.CONFIGS["tiny"].scaled(d=256, N=300, k=9, T=1, H=2),                   # lean sweep, 32 lanes per row, token rows
+    W.CONFIGS["tiny"].scaled(d=16, N=300, k=9, T=1),                         # general sweep, two lanes per row
+    W.CONFIGS["tiny"].scaled(d=64, N=300, k=9, T=1, H=3),                    # general sweep, eight lanes per row
+    W.CONFIGS["llama8b_32k"].scaled(d=32, N=300, k=9, T=1, H=2, G=2),        # general sweep, eight lanes per row, two query heads folded
 ]
 
 
@@ -730,6 +733,13 @@ STEP_CASES = [
     (W.CONFIGS["token_stress"].scaled(N=65536, k=15000, T=1, Nc=2048), False, True),
     (W.CONFIGS["token_stress"].scaled(T=2), True, True),          # long row, sliced selection: its second stage is fused with the mapping
     (W.CONFIGS["token_stress"].scaled(N=40000, k=700, T=1, H=2), False, False),
+    # every block size and per-thread width of the fused kernel
+    (W.CONFIGS["tiny"].scaled(N=1000, k=20, T=2, Nc=52, M=52, R=2, D=8), True, True),
+    (W.CONFIGS["token_stress"].scaled(N=30000, k=9000, T=1, Nc=512, M=512), False, True),
+    (W.CONFIGS["token_stress"].scaled(N=50000, k=10000, T=1, Nc=256, M=256), True, False),
+    (W.CONFIGS["token_stress"].scaled(N=65536, k=2000, T=1), False, True),
+    (W.CONFIGS["token_stress"].scaled(N=65536, k=4000, T=1), True, True),
+    (W.CONFIGS["token_stress"].scaled(N=131072, k=3000, T=1, H=2), False, True),
 ]
 
 
