@@ -19,6 +19,7 @@
 
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -132,9 +133,13 @@ constexpr int TM = 256;                        // C tile rows per workgroup
 constexpr int TN = 128;                        // C tile columns per workgroup
 constexpr int KC = 64;                         // contraction BYTES per chunk and operand row: 128 trace rows as 4-bit values, two MFMA k-steps of 64
 constexpr int A_BYTES = TM * KC;               // A operand panel of one chunk in LDS: 16 KiB; two of them form the ring
-constexpr int TROW = 512 + 16;                 // epilogue staging row, padded: the 16-byte slots of 8 consecutive lanes differ
-constexpr int SYRK_LDS_BYTES = 4 * 32 * TROW;  // 66 KiB: the epilogue's staging (one 32-column block per wave) is the larger user
-static_assert(SYRK_LDS_BYTES >= 2 * A_BYTES, "operand ring must fit");
+constexpr int RAW_DEPTH = 4;                   // chunks of raw trace bits on their way from memory or waiting in LDS
+constexpr int RAW_CHUNK = (TM + TN) * 16;      // one chunk of raw bits: the 16-byte run words of the tile's 256 rows, then of its 128 columns
+constexpr int RAW_BASE = 2 * A_BYTES;          // the raw ring sits behind the operand ring
+constexpr int SYRK_WAVES = 8;                  // 4 x 2 waves of 64 x 64
+constexpr int TROW = 256 + 16;                 // epilogue staging row (64 counts), padded: the 16-byte slots of 8 consecutive lanes differ
+constexpr int SYRK_LDS_BYTES = SYRK_WAVES * 32 * TROW;   // 68 KiB: the epilogue's staging (one 32-column block per wave) is the larger user
+static_assert(SYRK_LDS_BYTES >= RAW_BASE + RAW_DEPTH * RAW_CHUNK, "operand ring and raw ring must fit");
 
 // Operand rows in LDS are 64 bytes; 16-byte piece c of row r lives at slot c ^ swz(r).  Measured on
 // gfx950: a 16-byte LDS read is served 16 consecutive lanes at a time across 64 four-byte banks, a
@@ -157,14 +162,24 @@ __device__ __forceinline__ int lds_off(int row, int piece) { return row * KC + (
 // consecutive rows of an output dword are the same bit of the word's eight nibbles (trace_bit above),
 // and a mask (with a shift where the bit has to move inside its nibble) is the whole expansion of eight rows.
 
-// C tile of 256 x 128 per workgroup of 4 waves (2 x 2, each 128 x 64 = 4 x 2 MFMA tiles, 128
-// accumulator registers), two workgroups per compute unit: while one waits at its hand-over barrier,
-// writes its tile or starts up, the other keeps the matrix cores busy.  The contraction runs in
-// chunks of 128 trace rows (one 16-byte bit word per entry) through a two-deep LDS ring for the row panel: thread t
-// owns row t of it; the bit words of the next chunks are in flight from memory (three chunks ahead), those of chunk
-// c+1 are being expanded and written into the idle LDS buffer, chunk c feeds the matrix cores; the operands of
-// k-step s+1 are read from LDS (rows) or expanded from the lane's own bit words (columns) while the MFMAs of k-step s run.
-// Because the operands travel as bits, the smaller tile costs next to nothing in memory traffic.
+// C tile of 256 x 128 per workgroup of 8 waves (4 x 2, each 64 x 64 = 2 x 2 MFMA tiles, 64 accumulator registers),
+// two workgroups per compute unit, i.e. four waves per SIMD: while the waves of one workgroup write their tile, wait at
+// a hand-over barrier or start up, each SIMD still has two or three waves feeding its matrix cores.  (Measured on one
+// device with a model of this loop: two waves per SIMD that both compute run the loop at 69 % of the matrix cores'
+// rate, one wave alone at 50 % -- with 128 x 64 per wave, two waves per SIMD, a tile's write phase left the SIMD to a
+// single computing wave.)
+// The contraction runs in chunks of 128 trace rows (one 16-byte run word per entry).  Three stages, all in LDS:
+//   raw ring   (RAW_DEPTH chunks)  the run words of the tile's 256 rows and 128 columns, loaded memory -> LDS directly
+//              (buffer_load ... lds, 16 bytes per lane: six loads per chunk and workgroup, issued by waves 0..5, no
+//              register ever holds data in flight -- with four waves per SIMD there are none to spare for that)
+//   row ring   (2 chunks)          the 256 rows expanded to 4-bit operands, thread t expands half of row t/2
+//   fragments                      rows from the row ring (16-byte LDS reads), columns expanded in registers from the
+//                                  lane's own 8 raw bytes per 32-column block
+// One barrier per chunk hands over all three: before it a wave has waited for its own load of chunk d + 2, has written
+// its share of chunk d + 1's rows and has read everything it needs of chunk d + 1's raw bits; after it the slot of
+// chunk d + 1's raw bits is free for the load of chunk d + 1 + RAW_DEPTH, chunk d + 1's rows may be read, and the row
+// buffer of chunk d may be overwritten (during chunk d + 1).
+// Because the operands travel as bits, the small tile costs next to nothing in memory traffic.
 // Workgroups are numbered so that the eight L2 slices (one per XCD, workgroups are dealt to them
 // round-robin) each walk a contiguous run of the tile schedule.
 // RHO (MODE 0, VEC): the epilogue also counts, for every row of C, the elements that reach the head's
@@ -174,13 +189,13 @@ __device__ __forceinline__ int lds_off(int row, int piece) { return row * KC + (
 // give those of the direct tile's rows; a diagonal block's two tiles are computed in full, and by
 // symmetry their column counts are the block's row counts.  Counts meet in LDS and leave as one
 // atomic add per row and tile.
+typedef __attribute__((address_space(3))) void lds_void;
+
 template <int MODE, bool VEC, bool RHO = false>
-__global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns,
-                                                            int32_t* __restrict__ C, uint32_t decay_q16,
-                                                            int tiles_per_head, int total_tiles, int per_xcd,
-                                                            const int32_t* __restrict__ tile_order,
-                                                            uint32_t* __restrict__ dev_flags,
-                                                            const int64_t* __restrict__ cstar, int32_t* __restrict__ rho) {
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns, int32_t* __restrict__ C, uint32_t decay_q16,
+                       int tiles_per_head, int total_tiles, int per_xcd, const int32_t* __restrict__ tile_order,
+                       uint32_t* __restrict__ dev_flags, const int64_t* __restrict__ cstar, int32_t* __restrict__ rho) {
     static_assert(!RHO || (MODE == 0 && VEC), "the fused density count belongs to the overwriting, vectorised form");
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int xcd = blockIdx.x & 7, slot_id = blockIdx.x >> 3;
@@ -194,133 +209,148 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wy = wave >> 1, wx = wave & 1;
-
-    // A operand (the 256 tile rows): memory -> registers -> LDS.  Thread t takes row t of the A panel, one 16-byte
-    // word (a run of 128 trace rows = one chunk) at a time, expands it to 4-bit operands and stores the 64 bytes.
-    // B operand (the wave's 64 tile columns): straight from the trace bits in registers.  Lane l supplies row l%32 of
-    // each of the wave's two 32-column blocks with contraction indices [32 (l/32), +32) of a k-step -- which is ONE
-    // 32-bit word of that entry's run (word 2 ks + l/32), expanded by seven vector operations.  Going through LDS
-    // with both panels asked for 1.2 sixteen-byte LDS instructions per MFMA and kept the LDS data path backed up for a
-    // quarter of the run; expanding both panels in every wave asks for more vector instructions than fit beside the MFMAs.
-    // Four register sets, indexed by run number mod 4.
     const int frow = lane & 31, fhalf = lane >> 5;
-    const v4i* panel = bits + (size_t)h * nruns * Npad;
-    const v4i* a_src = panel + (size_t)ti * TM + tid;
-    const uint32_t* b_src = reinterpret_cast<const uint32_t*>(panel + (size_t)tj * TN + wx * 64 + frow) + fhalf;
-    v4i ba[4];
-    uint32_t bq[4][2][2];                          // [set][column block][k-step]
+
+    // memory -> raw ring.  A chunk's raw bits are 6 KiB, contiguous in memory in two pieces (rows, columns), and land in
+    // LDS in the same order: wave w < 4 brings rows [64 w, +64) of the tile, waves 4 and 5 columns [64 (w - 4), +64); lane l
+    // of a load carries 16 bytes to byte 16 l of the wave's KiB.  One buffer descriptor per run (its range is the run:
+    // 16 Npad bytes), so an offset past the run would read zeros, not memory.
+    const char* panel = reinterpret_cast<const char*>(bits) + (size_t)h * nruns * Npad * 16;
+    const uint32_t src_lane = (uint32_t)(((wave < 4 ? ti * TM + wave * 64 : tj * TN + (wave - 4) * 64) + lane) * 16);
     const int last_run = nruns - 1;
-    auto load_bits = [&](int set, int run) __attribute__((always_inline)) {           // clamped: a redundant reload past the end is harmless
-        const size_t off = (size_t)min(run, last_run) * Npad;                           // a minimum, not a select: no branch inside the loop
-        ba[set] = a_src[off];
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) bq[set][j][ks] = b_src[off * 4 + j * (32 * 4) + ks * 2];
+    auto issue_load = [&](int run) __attribute__((always_inline)) {                   // clamped: a redundant reload past the end is harmless
+        if (wave < 6) {
+            const char* runp = panel + (size_t)min(run, last_run) * Npad * 16;
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(runp), 0, Npad * 16, 0x00020000);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(lds + RAW_BASE + (run % RAW_DEPTH) * RAW_CHUNK + wave * 1024), 16,
+                                                     src_lane, 0, 0, 0);
+        }
     };
-    // registers -> LDS, in pieces of 16 contraction bytes (32 trace rows = one 32-bit word of the run).  A piece is
-    // expanded one dword (8 trace rows) at a time and stored when complete.
-    int st_off[4];
+    // raw ring -> registers.  Thread t owns half ahalf = t % 2 of row t / 2 of the row panel: 8 bytes, two pieces of 32 trace
+    // rows.  Lane l of a fragment supplies row l % 32 with the contraction indices of lane half l / 32, and which 32 trace
+    // rows of a chunk those are is free as long as both operands agree: k-step ks of lane half f is word 2 f + ks of the
+    // run, so the two k-steps of a lane are 8 contiguous raw bytes.
+    const int arow = tid >> 1, ahalf = tid & 1;
+    const int rawa_off = RAW_BASE + arow * 16 + ahalf * 8;
+    const int rawb_off = RAW_BASE + TM * 16 + (wx * 64 + frow) * 16 + fhalf * 8;
+    v2i ba;                                        // raw bits of this thread's half row, next chunk
+    v2i bw[2][2];                                  // raw column bits [chunk parity][column block] = {k-step 0, k-step 1}
+    auto read_raw_a = [&](int run) __attribute__((always_inline)) {
+        ba = *reinterpret_cast<const v2i*>(lds + (run % RAW_DEPTH) * RAW_CHUNK + rawa_off);
+    };
+    auto read_raw_b = [&](int set, int run) __attribute__((always_inline)) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) st_off[p] = lds_off(tid, p);
+        for (int j = 0; j < 2; ++j) bw[set][j] = *reinterpret_cast<const v2i*>(lds + (run % RAW_DEPTH) * RAW_CHUNK + rawb_off + j * 512);
+    };
+    // registers -> row ring, in pieces of 16 contraction bytes (32 trace rows = one 32-bit word of the run).  A piece is
+    // expanded one dword (8 trace rows) at a time and stored when complete.
+    int st_off[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) st_off[p] = lds_off(arow, 2 * ahalf + p);
     v4i ex;
     // Row operand: the bit of trace row 8q + n of a 32-row word is bit q of nibble n, and for q = 0, 1, 2 it is left where
     // it is -- the nibbles 0b0001, 0b0010, 0b0100 are 0.5, 1 and 2 in E2M1 -- while the column operand (below) carries the
     // inverse factor at the same contraction index, so every product of two set bits is still exactly 1.  Only q = 3 (the
     // sign bit of its nibble) has to move.  Five vector operations per 32 trace rows instead of seven.
-    auto expand_quarter = [&](int set, int piece, int q) __attribute__((always_inline)) {
-        const uint32_t w = (uint32_t)ba[set][piece];
+    auto expand_quarter = [&](int piece, int q) __attribute__((always_inline)) {
+        const uint32_t w = (uint32_t)ba[piece];
         ex[q] = (int)(q == 3 ? (w >> 2) & 0x22222222u : w & (0x11111111u << q));
     };
     auto store_piece = [&](int buf, int piece) __attribute__((always_inline)) {
         *reinterpret_cast<v4i*>(lds + buf * A_BYTES + st_off[piece]) = ex;
     };
 
-    v16f facc[4][2];
+    v16f facc[2][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) facc[i][j][r] = 0.f;
-    constexpr int unit_scale = 0;                  // no block scales: the compiler then emits the unscaled form of the instruction (scale 2^0)
 
-    // A fragment addressing: lane l reads row l%32 of an MFMA tile, bytes [16*(l/32), +16) of the 32-byte
-    // k-step (64 contraction indices as nibbles).  The swizzle term is the same for rows 32 apart; the tile index is a constant byte offset.
+    // A fragment addressing: lane l reads row l%32 of an MFMA tile, the 16-byte piece 2 (l/32) + ks of its row.
+    // The swizzle term is the same for rows 32 apart; the tile index is a constant byte offset.
     int fa_base[2];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) fa_base[ks] = lds_off(wy * 128 + frow, 2 * ks + fhalf);
-    v4i fa[2][4], fb[2][2];
+    for (int ks = 0; ks < 2; ++ks) fa_base[ks] = lds_off(wy * 64 + frow, 2 * fhalf + ks);
+    v4i fa[2][2], fb[2];
     auto read_a = [&](int buf, int ks, int fs, int i) __attribute__((always_inline)) {
         fa[fs][i] = *reinterpret_cast<const v4i*>(lds + buf * A_BYTES + fa_base[ks] + i * 32 * KC);
     };
     // Column operand: 2, 1, 0.5 and 1 at q = 0, 1, 2, 3, the inverses of the row operand's factors (two shifts, four masks).
-    auto expand_b = [&](int fs, int set, int ks, int j) __attribute__((always_inline)) {
-        const uint32_t w = bq[set][j][ks], w2 = w >> 2;
-        fb[fs][j] = v4i{(int)((w << 2) & 0x44444444u), (int)(w & 0x22222222u), (int)(w2 & 0x11111111u), (int)(w2 & 0x22222222u)};
+    // One set of fragment registers: a k-step's columns are expanded after the previous k-step's MFMAs have been issued.
+    auto expand_b = [&](int set, int ks, int j) __attribute__((always_inline)) {
+        const uint32_t w = (uint32_t)bw[set][j][ks], w2 = w >> 2;
+        fb[j] = v4i{(int)((w << 2) & 0x44444444u), (int)(w & 0x22222222u), (int)(w2 & 0x11111111u), (int)(w2 & 0x22222222u)};
     };
+    // no block scales: with both scales 0 the compiler emits the unscaled form of the instruction (scale 2^0)
     auto mfma = [&](int fs, int m) __attribute__((always_inline)) {
-        const v4i a4 = fa[fs][m >> 1], b4 = fb[fs][m & 1];
+        const v4i a4 = fa[fs][m >> 1], b4 = fb[m & 1];
         const v8i a8 = {a4.x, a4.y, a4.z, a4.w, 0, 0, 0, 0}, b8 = {b4.x, b4.y, b4.z, b4.w, 0, 0, 0, 0};   // the 4-bit form reads 4 registers
-        facc[m >> 1][m & 1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, facc[m >> 1][m & 1], 4, 4, 0, unit_scale, 0,
-                                                                             unit_scale);
+        facc[m >> 1][m & 1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, facc[m >> 1][m & 1], 4, 4, 0, 0, 0, 0);
     };
 
-    load_bits(0, 0);
-    load_bits(1, 1);
-    load_bits(2, 2);
+    // start-up: chunks 0 .. RAW_DEPTH-1 on their way; chunk 0 expanded; chunk RAW_DEPTH into the slot of chunk 0
 #pragma unroll
-    for (int piece = 0; piece < 4; ++piece) {
+    for (int c = 0; c < RAW_DEPTH; ++c) issue_load(c);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    read_raw_a(0);
+    read_raw_b(0, 0);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) expand_quarter(0, piece, q);
+    for (int piece = 0; piece < 2; ++piece) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) expand_quarter(piece, q);
         store_piece(0, piece);
     }
     __syncthreads();
+    issue_load(RAW_DEPTH);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) read_a(0, 0, 0, i);
+    for (int i = 0; i < 2; ++i) read_a(0, 0, 0, i);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) expand_b(0, 0, 0, j);
+    for (int j = 0; j < 2; ++j) expand_b(0, 0, j);
 
-    // Chunk d (run d of 128 trace rows, bits in register set d%4) computes out of LDS buffer d%2; its own A
-    // bits are spent.  The next chunk's A rows are expanded into the other LDS buffer, which no wave reads after
-    // the hand-over barrier of the previous chunk; set (d+3)%4 is refilled at the start of the chunk, three
-    // chunks ahead of its use.  The work is laid out as 16 slots, one per MFMA: slot m issues the MFMA, then an
-    // operand of the second k-step (an A fragment read in the first four slots, a B fragment expanded in the next
-    // two), then its share of the A expansion (16 dwords of 2 operations and 4 LDS stores per chunk, spread over
-    // the first 8 slots).  The hand-over barrier sits after the first k-step (it cannot sit earlier: the reads that
-    // follow it refill the first k-step's fragment registers); the second k-step's MFMAs and the other workgroup
-    // on the compute unit cover the LDS latency of the next chunk's first fragments.
-    auto chunk_body = [&](int d, int set) __attribute__((always_inline)) {   // set = d % 4, passed as a literal
-        const int buf = set & 1, nbuf = buf ^ 1;
-        const int nset = (set + 1) & 3, lset = (set + 3) & 3;
+    // Chunk d (parity `set`, passed as a literal) computes out of row buffer `set`.  First k-step: its four MFMAs, between
+    // them the row fragments of the second k-step and this thread's share of chunk d + 1's rows (raw bits read at the top of
+    // the chunk: they were published by the previous barrier); then the columns of the second k-step; the barrier; the load
+    // of chunk d + 1 + RAW_DEPTH; the first row fragments of chunk d + 1, whose LDS latency the second k-step's MFMAs and
+    // the SIMD's other waves cover; the columns of chunk d + 1's first k-step.
+    auto chunk_body = [&](int d, int set) __attribute__((always_inline)) {
+        const int nset = set ^ 1;
+        read_raw_a(d + 1);
+        read_raw_b(nset, d + 1);
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
+        for (int s = 0; s < 4; ++s) {
             mfma(0, s);
-            if (s < 4) read_a(buf, 1, 1, s);
-            else if (s < 6) expand_b(1, set, 1, s - 4);
-            if (s == 0) load_bits(lset, d + 3);
+            if (s < 2) read_a(set, 1, 1, s);
 #pragma unroll
             for (int u = 2 * s; u < 2 * (s + 1); ++u) {
-                expand_quarter(nset, u >> 2, u & 3);
-                if ((u & 3) == 3) store_piece(nbuf, u >> 2);
+                expand_quarter(u >> 2, u & 3);
+                if ((u & 3) == 3) store_piece(nset, u >> 2);
             }
         }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) expand_b(set, 1, j);
+        // this wave's load of chunk d + 2 has landed; the RAW_DEPTH - 2 younger ones may still be in flight
+        asm volatile("s_waitcnt vmcnt(%0)" :: "n"(RAW_DEPTH - 2) : "memory");
         __syncthreads();
+        issue_load(d + 1 + RAW_DEPTH);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) read_a(nbuf, 0, 0, i);            // after the last chunk this reads stale but valid LDS and is never used
-#pragma unroll
-        for (int j = 0; j < 2; ++j) expand_b(0, nset, 0, j);
+        for (int i = 0; i < 2; ++i) read_a(nset, 0, 0, i);            // after the last chunk this reads stale but valid LDS and is never used
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int s = 0; s < 8; ++s) mfma(1, s);
+        for (int s = 0; s < 4; ++s) mfma(1, s);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) expand_b(nset, 0, j);
     };
-    __builtin_amdgcn_s_setprio(2);                          // the contraction outranks the other workgroup's epilogue stores
-    for (int d = 0; d < nruns; d += 4) {                    // nruns is a multiple of 4
+    __builtin_amdgcn_s_setprio(2);                          // the contraction outranks the other waves' epilogue stores
+    for (int d = 0; d < nruns; d += 2) {                    // nruns is a multiple of 4
         chunk_body(d, 0);
         chunk_body(d + 1, 1);
-        chunk_body(d + 2, 2);
-        chunk_body(d + 3, 3);
     }
+    // every load has landed before the staging below reuses the rings, and every wave has left the loop
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
 
     __builtin_amdgcn_s_setprio(0);
     // 32x32 result layout: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4.  One
@@ -330,9 +360,9 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     // bytes but the lines are spread over lanes, so that tile is re-laid out through the (now idle)
     // LDS and leaves in 16-byte stores that cover whole lines.  Streaming stores when C is not read.
     // the counts as integers (exact: every partial sum is an integer below 2^24)
-    v16i acc[4][2];
+    v16i acc[2][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -340,13 +370,14 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     int32_t* Ch = C + (size_t)h * N * N;
     const int col_in = lane & 31, half = lane >> 5, row_in = half * 4;
     int8_t* tbuf = lds + wave * (32 * TROW);
-    const int gi_base = ti * TM + wy * 128;
+    const int gi_base = ti * TM + wy * 64;
+    const int mrow = lane >> 4, c16 = lane & 15;             // mirrored tile: a store covers 4 rows of 64 columns, 16 bytes per lane
     // Addresses are a wave-uniform row pointer (scalar arithmetic) plus one per-lane element offset
     // that is the same for every store of a tile.
     // The lane part is a 32-bit BYTE offset, so that an access is "scalar base + 32-bit lane offset", the
     // addressing form that needs no per-store 64-bit vector arithmetic and no register pair per address.
     const uint32_t lane_direct = ((uint32_t)row_in * (uint32_t)N + col_in) * 4u;
-    const uint32_t lane_mirror = ((uint32_t)half * (uint32_t)N + col_in * 4) * 4u;
+    const uint32_t lane_mirror = ((uint32_t)mrow * (uint32_t)N + c16 * 4) * 4u;
     auto at = [](int32_t* base, uint32_t byte_off) __attribute__((always_inline)) {
         return reinterpret_cast<int32_t*>(reinterpret_cast<char*>(base) + byte_off);
     };
@@ -357,8 +388,8 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     if (RHO) {
         const int64_t c = cstar[h];
         if (c < 0x7fffffffll) c32 = (int32_t)c;
-        cnt_row[threadIdx.x] = 0u;
-        if (threadIdx.x < TN) cnt_col[threadIdx.x] = 0u;
+        if (threadIdx.x < TM) cnt_row[threadIdx.x] = 0u;
+        else if (threadIdx.x < TM + TN) cnt_col[threadIdx.x - TM] = 0u;
         __syncthreads();                                   // the waves' counts meet in these counters
     }
     // 1 where v >= c32, 0 elsewhere, without a compare: counts lie in [0, 2^24] and c32 in [0, 2^31), so
@@ -382,7 +413,7 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
             const bool c0_ok = !GUARD || tj * TN + wx * 64 + col_in < N, c1_ok = !GUARD || tj * TN + wx * 64 + 32 + col_in < N;
             uint32_t colc0 = 0u, colc1 = 0u;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int urow = i * 32 + (r >> 2) * 8 + (r & 3);
@@ -402,11 +433,11 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int gj_base = tj * TN + wx * 64 + j * 32;
-            // park the 128 x 32 block as [column][row] for the mirrored tile; the LDS executes one wave's
+            // park the 64 x 32 block as [column][row] for the mirrored tile; the LDS executes one wave's
             // accesses in order, so the block of the previous j has been read by then
             if (VEC && !diag) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int rq = 0; rq < 4; ++rq) {
                         const v4i v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
@@ -414,14 +445,14 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
                     }
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             }
-            // direct tile: rows gi_base + 0..127, columns gj_base + 0..31
+            // direct tile: rows gi_base + 0..63, columns gj_base + 0..31
             size_t cj_off = (size_t)gi_base * N + gj_base;                            // wave-uniform
             if (RHO) asm volatile("" : "+s"(cj_off));   // own row pointers per column block: shared ones (128 scalar registers) do not fit beside the counting
             int32_t* Cj = Ch + cj_off;
             const bool col_ok = !GUARD || gj_base + col_in < N;
             uint32_t colc = 0u;
 #pragma unroll
-            for (int ip = 0; ip < (PAIRED ? 0 : 4); ip += 2) {                        // 32 rows x 2 in flight when C is read back
+            for (int ip = 0; ip < (PAIRED ? 0 : 2); ip += 2) {                        // 32 rows x 2 in flight when C is read back
                 int32_t old[2][16];
                 if (MODE != 0) {
 #pragma unroll
@@ -452,25 +483,26 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
                 if (MODE != 0) asm volatile("" ::: "memory");
             }
             if (RHO && !PAIRED) atomicAdd(&cnt_col[wx * 64 + j * 32 + col_in], colc);
-            // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..127
+            // mirrored tile: rows gj_base + 0..31, columns gi_base + 0..63
             if (VEC && !diag) {
                 size_t cm_off = (size_t)gj_base * N + gi_base;                        // wave-uniform
                 if (RHO) asm volatile("" : "+s"(cm_off));
                 int32_t* Cm = Ch + cm_off;
-                const bool mcol_ok = !GUARD || gi_base + col_in * 4 < N;              // N is a multiple of 4 here
+                const bool mcol_ok = !GUARD || gi_base + c16 * 4 < N;                 // N is a multiple of 4 here
+                constexpr int MB = MODE == 0 ? 8 : 4;                                 // rows in flight: the old counts need registers too
 #pragma unroll
-                for (int sp = 0; sp < 16; sp += 8) {
-                    v4i v[8], o[8];
+                for (int sp = 0; sp < 8; sp += MB) {
+                    v4i v[MB], o[MB];
 #pragma unroll
-                    for (int sidx = sp; sidx < sp + 8; ++sidx) {
-                        v[sidx - sp] = *reinterpret_cast<const v4i*>(tbuf + (2 * sidx + half) * TROW + col_in * 16);
-                        if (MODE != 0 && mcol_ok && (!GUARD || gj_base + 2 * sidx + half < N))
-                            o[sidx - sp] = *reinterpret_cast<const v4i*>(at(Cm + (size_t)(2 * sidx) * N, lane_mirror));
+                    for (int sidx = sp; sidx < sp + MB; ++sidx) {
+                        v[sidx - sp] = *reinterpret_cast<const v4i*>(tbuf + (4 * sidx + mrow) * TROW + c16 * 16);
+                        if (MODE != 0 && mcol_ok && (!GUARD || gj_base + 4 * sidx + mrow < N))
+                            o[sidx - sp] = *reinterpret_cast<const v4i*>(at(Cm + (size_t)(4 * sidx) * N, lane_mirror));
                     }
 #pragma unroll
-                    for (int sidx = sp; sidx < sp + 8; ++sidx) {
-                        if (mcol_ok && (!GUARD || gj_base + 2 * sidx + half < N)) {
-                            v4i* p = reinterpret_cast<v4i*>(at(Cm + (size_t)(2 * sidx) * N, lane_mirror));
+                    for (int sidx = sp; sidx < sp + MB; ++sidx) {
+                        if (mcol_ok && (!GUARD || gj_base + 4 * sidx + mrow < N)) {
+                            v4i* p = reinterpret_cast<v4i*>(at(Cm + (size_t)(4 * sidx) * N, lane_mirror));
                             if (RHO) {
                                 const v4i w = v[sidx - sp];
                                 rowc[0] += reaches(w.x); rowc[1] += reaches(w.y); rowc[2] += reaches(w.z); rowc[3] += reaches(w.w);
@@ -496,13 +528,13 @@ __global__ __launch_bounds__(256, 2) void coact_syrk_kernel(const v4i* __restric
     if (RHO) {
         if (!diag) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) atomicAdd(&cnt_row[wy * 128 + col_in * 4 + c], rowc[c]);
+            for (int c = 0; c < 4; ++c) atomicAdd(&cnt_row[wy * 64 + c16 * 4 + c], rowc[c]);
         }
         __syncthreads();
         int32_t* rh = rho + (size_t)h * N;
         const int u = threadIdx.x;
-        if (!diag && ti * TM + u < N && cnt_row[u]) atomicAdd(rh + ti * TM + u, (int32_t)cnt_row[u]);
-        if (u < TN && tj * TN + u < N && cnt_col[u]) atomicAdd(rh + tj * TN + u, (int32_t)cnt_col[u]);
+        if (!diag && u < TM && ti * TM + u < N && cnt_row[u]) atomicAdd(rh + ti * TM + u, (int32_t)cnt_row[u]);
+        if (u >= TM && u < TM + TN && tj * TN + u - TM < N && cnt_col[u - TM]) atomicAdd(rh + tj * TN + u - TM, (int32_t)cnt_col[u - TM]);
     }
 }
 
@@ -712,7 +744,7 @@ swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns
         }
         ctx->syrk_lds_opt_in = true;
     }
-    dim3 grid((unsigned)(per_xcd * 8)), block(256);
+    dim3 grid((unsigned)(per_xcd * 8)), block(64 * SYRK_WAVES);
     const int tph = (int)tiles_per_head, tot = (int)total;
     hipLaunchKernelGGL(fused ? fused_kernel : kernels[mode][vec ? 1 : 0], grid, block, fused ? RHO_LDS_BYTES : SYRK_LDS_BYTES,
                        ctx->stream, reinterpret_cast<const v4i*>(ctx->trace), N, Npad, nruns, C, decay_q16, tph, tot, per_xcd,
