@@ -156,8 +156,8 @@ def coact_rooflines(H, N, rows, coact_ms, peaks, decayed):
     """Both roofs of the co-activation build and the one that binds it.  C is written once (read and written when an
     old matrix is updated), so below peak_ops / peak_bytes operations per byte it is the memory system."""
     Tpad = (rows + 511) // 512 * 512
-    tiles = (N + 255) // 256
-    issued_ops = 2.0 * H * tiles * (tiles + 1) * 256 * 128 * Tpad               # MFMA ops actually issued (tiles on or above the diagonal)
+    tiles = (N + 255) // 256 * 2                                               # tiles of 128 x 128 along one side (the trace is padded to 256 entries)
+    issued_ops = 2.0 * H * (tiles * (tiles + 1) // 2) * 128 * 128 * Tpad        # MFMA ops actually issued (tiles on or above the diagonal)
     nbytes = H * N * N * 4 * (2 if decayed else 1) + H * N * (Tpad // 8)
     tops = issued_ops / (coact_ms * 1e-3) / 1e12
     gbs = nbytes / (coact_ms * 1e-3) / 1e9
@@ -512,8 +512,8 @@ def only_coact(args, cfg, binding, W, torch, stream):
     e1.record(stream)
     stream.synchronize()
     ms = e0.elapsed_time(e1) / args.steps
-    tiles = (N + 255) // 256
-    issued = 2.0 * H * tiles * (tiles + 1) * 256 * 128 * ((T + 511) // 512 * 512)
+    tiles = (N + 255) // 256 * 2
+    issued = 2.0 * H * (tiles * (tiles + 1) // 2) * 128 * 128 * ((T + 511) // 512 * 512)
     print(json.dumps({"only": "coact", "workload": cfg.name, "ms_per_build_incl_trace": round(ms, 3), "issued_ops": issued,
                       "TOPs": round(issued / (ms * 1e-3) / 1e12, 1), "frac_of_int8_peak_5000": round(issued / (ms * 1e-3) / 5e15, 4),
                       "frac_of_fp4_peak_10100": round(issued / (ms * 1e-3) / 10.1e15, 4),

@@ -129,16 +129,16 @@ __device__ __forceinline__ int32_t updated_count(int32_t old, int32_t v, uint32_
     return s;
 }
 
-constexpr int TM = 256;                        // C tile rows per workgroup
+constexpr int TM = 128;                        // C tile rows per workgroup
 constexpr int TN = 128;                        // C tile columns per workgroup
 constexpr int KC = 64;                         // contraction BYTES per chunk and operand row: 128 trace rows as 4-bit values, two MFMA k-steps of 64
-constexpr int A_BYTES = TM * KC;               // A operand panel of one chunk in LDS: 16 KiB; two of them form the ring
+constexpr int A_BYTES = TM * KC;               // A operand panel of one chunk in LDS: 8 KiB; two of them form the ring
 constexpr int RAW_DEPTH = 4;                   // chunks of raw trace bits on their way from memory or waiting in LDS
-constexpr int RAW_CHUNK = (TM + TN) * 16;      // one chunk of raw bits: the 16-byte run words of the tile's 256 rows, then of its 128 columns
+constexpr int RAW_CHUNK = (TM + TN) * 16;      // one chunk of raw bits: the 16-byte run words of the tile's 128 rows, then of its 128 columns
 constexpr int RAW_BASE = 2 * A_BYTES;          // the raw ring sits behind the operand ring
-constexpr int SYRK_WAVES = 8;                  // 4 x 2 waves of 64 x 64
+constexpr int SYRK_WAVES = 4;                  // 2 x 2 waves of 64 x 64
 constexpr int TROW = 256 + 16;                 // epilogue staging row (64 counts), padded: the 16-byte slots of 8 consecutive lanes differ
-constexpr int SYRK_LDS_BYTES = SYRK_WAVES * 32 * TROW;   // 68 KiB: the epilogue's staging (one 32-column block per wave) is the larger user
+constexpr int SYRK_LDS_BYTES = SYRK_WAVES * 32 * TROW;   // 34 KiB: the epilogue's staging (one 32-column block per wave) is the larger user
 static_assert(SYRK_LDS_BYTES >= RAW_BASE + RAW_DEPTH * RAW_CHUNK, "operand ring and raw ring must fit");
 
 // Operand rows in LDS are 64 bytes; 16-byte piece c of row r lives at slot c ^ swz(r).  Measured on
@@ -162,17 +162,17 @@ __device__ __forceinline__ int lds_off(int row, int piece) { return row * KC + (
 // consecutive rows of an output dword are the same bit of the word's eight nibbles (trace_bit above),
 // and a mask (with a shift where the bit has to move inside its nibble) is the whole expansion of eight rows.
 
-// C tile of 256 x 128 per workgroup of 8 waves (4 x 2, each 64 x 64 = 2 x 2 MFMA tiles, 64 accumulator registers),
-// two workgroups per compute unit, i.e. four waves per SIMD: while the waves of one workgroup write their tile, wait at
-// a hand-over barrier or start up, each SIMD still has two or three waves feeding its matrix cores.  (Measured on one
-// device with a model of this loop: two waves per SIMD that both compute run the loop at 69 % of the matrix cores'
-// rate, one wave alone at 50 % -- with 128 x 64 per wave, two waves per SIMD, a tile's write phase left the SIMD to a
-// single computing wave.)
+// C tile of 128 x 128 per workgroup of 4 waves (2 x 2, each 64 x 64 = 2 x 2 MFMA tiles, 64 accumulator registers),
+// four workgroups per compute unit, i.e. four waves per SIMD, each from a workgroup of its own.  A workgroup alternates
+// between contracting (matrix cores) and writing its tile (memory); with equal demand on both, two workgroups per
+// compute unit keep the busier of the two resources occupied two thirds of the time, four of them four fifths, and
+// while one writes, every SIMD still has three waves feeding its matrix cores.  (Measured on one device with a model
+// of this loop: two computing waves per SIMD run it at 69 % of the matrix cores' rate, one wave alone at 50 %.)
 // The contraction runs in chunks of 128 trace rows (one 16-byte run word per entry).  Three stages, all in LDS:
-//   raw ring   (RAW_DEPTH chunks)  the run words of the tile's 256 rows and 128 columns, loaded memory -> LDS directly
-//              (buffer_load ... lds, 16 bytes per lane: six loads per chunk and workgroup, issued by waves 0..5, no
-//              register ever holds data in flight -- with four waves per SIMD there are none to spare for that)
-//   row ring   (2 chunks)          the 256 rows expanded to 4-bit operands, thread t expands half of row t/2
+//   raw ring   (RAW_DEPTH chunks)  the run words of the tile's 128 rows and 128 columns, loaded memory -> LDS directly
+//              (buffer_load ... lds, 16 bytes per lane: one load per chunk and wave, no register ever holds data in
+//              flight -- with four waves per SIMD there are none to spare for that)
+//   row ring   (2 chunks)          the 128 rows expanded to 4-bit operands, thread t expands half of row t/2
 //   fragments                      rows from the row ring (16-byte LDS reads), columns expanded in registers from the
 //                                  lane's own 8 raw bytes per 32-column block
 // One barrier per chunk hands over all three: before it a wave has waited for its own load of chunk d + 2, has written
@@ -186,13 +186,13 @@ __device__ __forceinline__ int lds_off(int row, int piece) { return row * KC + (
 // threshold cstar[h] (Algorithm 1, Step 3: the density of an entry is the number of entries within the
 // radius, and "within the radius" is "count >= threshold", see the density pass).  A lane's register
 // column of the direct tile gives the counts of the mirrored tile's rows, the mirrored tile's vectors
-// give those of the direct tile's rows; a diagonal block's two tiles are computed in full, and by
-// symmetry their column counts are the block's row counts.  Counts meet in LDS and leave as one
+// give those of the direct tile's rows; a diagonal tile is computed in full, and by
+// symmetry its column counts are its row counts.  Counts meet in LDS and leave as one
 // atomic add per row and tile.
 typedef __attribute__((address_space(3))) void lds_void;
 
 template <int MODE, bool VEC, bool RHO = false>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns, int32_t* __restrict__ C, uint32_t decay_q16,
                        int tiles_per_head, int total_tiles, int per_xcd, const int32_t* __restrict__ tile_order,
                        uint32_t* __restrict__ dev_flags, const int64_t* __restrict__ cstar, int32_t* __restrict__ rho) {
@@ -203,23 +203,23 @@ void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns,
     if (slot_id >= per_xcd || t >= total_tiles) return;
     const int h = t / tiles_per_head;
     const int32_t packed = tile_order[t - h * tiles_per_head];
-    const int ti = packed >> 16, tj = packed & 0xffff;       // 256-row tile, 128-column tile
-    const bool diag = (tj >> 1) == ti;                       // inside a diagonal 256 x 256 block: its two tiles cover it, no mirror
+    const int ti = packed >> 16, tj = packed & 0xffff;       // tile row, tile column (tj >= ti)
+    const bool diag = tj == ti;                              // a diagonal tile is computed in full: no mirror
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wy = wave >> 1, wx = wave & 1;
     const int frow = lane & 31, fhalf = lane >> 5;
 
-    // memory -> raw ring.  A chunk's raw bits are 6 KiB, contiguous in memory in two pieces (rows, columns), and land in
-    // LDS in the same order: wave w < 4 brings rows [64 w, +64) of the tile, waves 4 and 5 columns [64 (w - 4), +64); lane l
+    // memory -> raw ring.  A chunk's raw bits are 4 KiB, contiguous in memory in two pieces (rows, columns), and land in
+    // LDS in the same order: waves 0 and 1 bring rows [64 w, +64) of the tile, waves 2 and 3 columns [64 (w - 2), +64); lane l
     // of a load carries 16 bytes to byte 16 l of the wave's KiB.  One buffer descriptor per run (its range is the run:
     // 16 Npad bytes), so an offset past the run would read zeros, not memory.
     const char* panel = reinterpret_cast<const char*>(bits) + (size_t)h * nruns * Npad * 16;
-    const uint32_t src_lane = (uint32_t)(((wave < 4 ? ti * TM + wave * 64 : tj * TN + (wave - 4) * 64) + lane) * 16);
+    const uint32_t src_lane = (uint32_t)(((wave < 2 ? ti * TM + wave * 64 : tj * TN + (wave - 2) * 64) + lane) * 16);
     const int last_run = nruns - 1;
     auto issue_load = [&](int run) __attribute__((always_inline)) {                   // clamped: a redundant reload past the end is harmless
-        if (wave < 6) {
+        {
             const char* runp = panel + (size_t)min(run, last_run) * Npad * 16;
             const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(runp), 0, Npad * 16, 0x00020000);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(lds + RAW_BASE + (run % RAW_DEPTH) * RAW_CHUNK + wave * 1024), 16,
@@ -381,7 +381,7 @@ void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns,
     auto at = [](int32_t* base, uint32_t byte_off) __attribute__((always_inline)) {
         return reinterpret_cast<int32_t*>(reinterpret_cast<char*>(base) + byte_off);
     };
-    // density counters behind everything else in LDS: 256 direct-tile rows, then 128 direct-tile columns
+    // density counters behind everything else in LDS: 128 direct-tile rows, then 128 direct-tile columns
     uint32_t* cnt_row = reinterpret_cast<uint32_t*>(lds + SYRK_LDS_BYTES);
     uint32_t* cnt_col = cnt_row + TM;
     int32_t c32 = 0x7fffffff;                              // counts never reach it (rows <= 2^24): "nothing is within the radius"
@@ -402,7 +402,7 @@ void coact_syrk_kernel(const v4i* __restrict__ bits, int N, int Npad, int nruns,
     auto combine = [&](int32_t old, int32_t v) __attribute__((always_inline)) {
         return updated_count<MODE == 0 ? 1 : MODE>(old, v, decay_q16, ovf);
     };
-    // GUARD: the tile reaches past N (only tiles of the last tile row / column when N is not a multiple of 256)
+    // GUARD: the tile reaches past N (only tiles of the last tile row / column when N is not a multiple of 128)
     auto emit = [&](auto guard_tag) __attribute__((always_inline)) {
         constexpr bool GUARD = decltype(guard_tag)::value;
         // Overwriting form: the direct tile first, the two 32-column blocks of a row back to back, so that the two
@@ -643,10 +643,9 @@ swarm_status launch_trace_build(swarm_ctx* ctx, const int32_t* idx, int64_t rows
     return swarm_check_launch(ctx, "trace_build_kernel");
 }
 
-// Order in which the tiles on or above the diagonal are handed out: super-blocks of 4 x 16 tiles
+// Order in which the tiles on or above the diagonal are handed out: super-blocks of 8 x 16 tiles
 // (1024 x 2048 entries), so that the workgroups resident on one XCD share few panels in its L2.
-// Tile (ti, tj) covers rows [256 ti, +256) and columns [128 tj, +128); the tiles of a row start at
-// tj = 2 ti, the left half of the diagonal block.
+// Tile (ti, tj) covers rows [128 ti, +128) and columns [128 tj, +128), tj >= ti.
 static swarm_status tile_order_for(swarm_ctx* ctx, int ntm, const int32_t** out) {
     for (const auto& t : ctx->tile_orders)
         if (t.first == ntm) { *out = t.second; return SWARM_OK; }
@@ -654,18 +653,17 @@ static swarm_status tile_order_for(swarm_ctx* ctx, int ntm, const int32_t** out)
         snprintf(ctx->err, sizeof(ctx->err), "coact: first call with this N while recording; run the sequence once first");
         return SWARM_EINVAL;
     }
-    const int ntn = 2 * ntm;
-    const size_t count = (size_t)ntm * (ntm + 1);
+    const size_t count = (size_t)ntm * (ntm + 1) / 2;
     int32_t* host = static_cast<int32_t*>(malloc(count * sizeof(int32_t)));
     if (!host) {
         snprintf(ctx->err, sizeof(ctx->err), "out of host memory");
         return SWARM_ENOMEM;
     }
     size_t n = 0;
-    for (int bi = 0; bi < ntm; bi += 4)
-        for (int bj = 2 * bi / 16 * 16; bj < ntn; bj += 16)
-            for (int ti = bi; ti < bi + 4 && ti < ntm; ++ti)
-                for (int tj = (bj > 2 * ti ? bj : 2 * ti); tj < bj + 16 && tj < ntn; ++tj)
+    for (int bi = 0; bi < ntm; bi += 8)
+        for (int bj = bi / 16 * 16; bj < ntm; bj += 16)
+            for (int ti = bi; ti < bi + 8 && ti < ntm; ++ti)
+                for (int tj = (bj > ti ? bj : ti); tj < bj + 16 && tj < ntm; ++tj)
                     if (n < count) host[n++] = (ti << 16) | tj; else ++n;
     swarm_status st = SWARM_OK;
     int32_t* dev = nullptr;
@@ -707,9 +705,9 @@ swarm_status launch_fill_i32(swarm_ctx* ctx, int32_t* p, size_t n, int32_t v) {
 swarm_status launch_coact_syrk(swarm_ctx* ctx, int H, int N, int Npad, int nruns, int32_t* C, uint32_t decay_q16,
                                const int64_t* cstar, int32_t* rho) {
     const int ntm = Npad / TM;
-    const int64_t tiles_per_head = (int64_t)ntm * (ntm + 1);
+    const int64_t tiles_per_head = (int64_t)ntm * (ntm + 1) / 2;
     const int64_t total = tiles_per_head * H;
-    if (total > (int64_t)1 << 30 || 2 * ntm > 65535) {
+    if (total > (int64_t)1 << 30 || ntm > 65535) {
         snprintf(ctx->err, sizeof(ctx->err), "coact: N=%d, H=%d give too many tiles for one launch", N, H);
         return SWARM_EINVAL;
     }
