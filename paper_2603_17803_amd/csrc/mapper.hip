@@ -179,6 +179,112 @@ __device__ __forceinline__ void greedy_chain_wide(uint32_t m, int lane, const ui
     }
 }
 
+// Chain of a sub-problem with exactly two SSDs, sa < sb (e.g. a replica pair of the round-robin placement with two
+// replicas), or with the single SSD sa (sb < 0: no replication).  There is one comparison per link, so both loads live in scalar registers and a link is scalar work:
+// compare, two selects, two adds (plus the bit that records the winner), where the general chain reduces over SSD lanes.
+// Items come 64 at a time, one per lane.  An item with a single candidate needs no comparison: a run of such items is
+// added up in parallel (they come first in the visiting order, which is by replication factor); a run of items with
+// both candidates is walked link by link.  Same results as the general chain: ties go to the lower SSD.
+__device__ __forceinline__ void greedy_chain_pair(uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
+                                                  const uint32_t* wgt, uint32_t* assign, uint32_t& keybase, uint32_t& cnt,
+                                                  int sa, int sb) {
+    const int sbr = sb >= 0 ? sb : sa;             // sb < 0: a sub-problem of the single SSD sa (no item has a second candidate)
+    uint32_t la = (uint32_t)__builtin_amdgcn_readlane((int)keybase, sa) >> 6, lb = (uint32_t)__builtin_amdgcn_readlane((int)keybase, sbr) >> 6;
+    uint32_t ca = (uint32_t)__builtin_amdgcn_readlane((int)cnt, sa), cb = (uint32_t)__builtin_amdgcn_readlane((int)cnt, sbr);
+    for (uint32_t base = 0; base < m; base += 64) {
+        const uint32_t n = min(64u, m - base);
+        uint32_t it = 0, ml = 0, w = 0;
+        if ((uint32_t)lane < n) {
+            it = order[base + lane];
+            ml = mask_lo[it];
+            w = wgt[it];
+        }
+        const bool ha = (ml >> sa) & 1u, hb = sb >= 0 && ((ml >> sbr) & 1u);
+        const uint64_t only_a = __ballot(ha && !hb), only_b = __ballot(!ha && hb), both = __ballot(ha && hb);
+        const uint64_t single = only_a | only_b;
+        const uint32_t w_both = (ha && hb) ? w : 0u;
+        uint64_t to_b = only_b;
+        uint32_t pos = 0;
+        while (pos < n) {
+            const uint64_t from = ~0ull << pos;                  // pos < 64
+            // a run of items without a comparison (single candidate, or none): up to the next item with both
+            const uint64_t nb = both & from;
+            const uint32_t s_end = nb ? (uint32_t)__ffsll((unsigned long long)nb) - 1u : n;
+            if (s_end > pos) {
+                const uint64_t run = from & (s_end < 64u ? ~(~0ull << s_end) : ~0ull);
+                if (single & run) {
+                    const bool mine = (run >> lane) & 1ull;
+                    uint32_t ta, tb;
+                    (void)wave_excl_scan((mine && ha && !hb) ? w : 0u, &ta);
+                    (void)wave_excl_scan((mine && hb && !ha) ? w : 0u, &tb);
+                    la += ta;
+                    lb += tb;
+                }
+            }
+            // a run of items with both candidates: up to the next item without
+            const uint64_t ns = ~both & (s_end < 64u ? ~0ull << s_end : 0ull);
+            const uint32_t b_end = min(n, ns ? (uint32_t)__ffsll((unsigned long long)ns) - 1u : 64u);
+            // A link in scalar arithmetic (loads stay below 2^26, so a sign is a comparison).
+            if (s_end == 0u && b_end == n) {
+                // The whole batch is one run (the common case: the items with a single candidate come first in the visiting
+                // order).  The chain runs on the difference d = la - lb: SSD sb takes the item when d > 0 (equal loads: the
+                // lower SSD), which lowers d by the weight; otherwise sa takes it and d rises.  Lane j of `dlog` keeps the
+                // difference item j met (literal lane numbers: the batch is unrolled in groups of 8 behind uniform
+                // branches; slots past n carry weight 0 and change nothing); the winners are read off it afterwards, and
+                // the two loads follow from their sum and their difference.
+                int32_t d = (int32_t)(la - lb);
+                uint32_t dlog = 0u;
+#pragma unroll
+                for (uint32_t q = 0; q < 64; q += 8) {
+                    if (q < n) {
+                        int32_t s_w[8];                                      // the group's weights first: a link then never waits for its own
+#pragma unroll
+                        for (uint32_t u = 0; u < 8; ++u) s_w[u] = __builtin_amdgcn_readlane((int)w_both, (int)(q + u));
+                        asm volatile("" : "+s"(s_w[0]), "+s"(s_w[1]), "+s"(s_w[2]), "+s"(s_w[3]), "+s"(s_w[4]), "+s"(s_w[5]), "+s"(s_w[6]), "+s"(s_w[7]));
+#pragma unroll
+                        for (uint32_t u = 0; u < 8; ++u) {
+                            asm("v_writelane_b32 %0, %1, %2" : "+v"(dlog) : "s"(d), "n"(q + u));
+                            int32_t lower = d - s_w[u], higher = d + s_w[u];   // both outcomes beside the comparison: two steps on the dependent path, not three
+                            asm volatile("" : "+s"(lower), "+s"(higher));
+                            d = d > 0 ? lower : higher;
+                        }
+                    }
+                }
+                to_b |= both & __ballot((int32_t)dlog > 0);
+                uint32_t wrun;
+                (void)wave_excl_scan(w_both, &wrun);
+                const uint32_t sum = la + lb + wrun;            // below 2^27
+                la = (uint32_t)((int32_t)sum + d) >> 1;
+                lb = (uint32_t)((int32_t)sum - d) >> 1;
+            } else {
+                for (uint32_t j = s_end; j < b_end; ++j) {
+                    const uint32_t s_w = (uint32_t)__builtin_amdgcn_readlane((int)w_both, (int)j);
+                    const uint32_t pick_b = (uint32_t)((int32_t)(lb - la) >> 31);        // all ones: SSD sb
+                    la += s_w & ~pick_b;
+                    lb += s_w & pick_b;
+                    to_b |= (uint64_t)(pick_b & 1u) << j;
+                }
+            }
+            pos = b_end;
+        }
+        // bucket positions, in item order
+        const uint64_t routed = single | both;
+        const uint64_t to_a = routed & ~to_b;
+        const uint64_t below = (1ull << lane) - 1ull;
+        if ((uint32_t)lane < n) {
+            uint32_t as = INF32;
+            if ((routed >> lane) & 1ull)
+                as = ((to_b >> lane) & 1ull) ? (((uint32_t)sb << 24) | (cb + (uint32_t)__popcll(to_b & below)))
+                                             : (((uint32_t)sa << 24) | (ca + (uint32_t)__popcll(to_a & below)));
+            assign[it] = as;
+        }
+        ca += (uint32_t)__popcll(to_a);
+        cb += (uint32_t)__popcll(to_b);
+    }
+    if (lane == sa) { keybase = (la << 6) | (uint32_t)lane; cnt = ca; }
+    if (lane == sb) { keybase = (lb << 6) | (uint32_t)lane; cnt = cb; }
+}
+
 __device__ __forceinline__ void run_chain_packed(int D, uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
                                                  const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign, uint32_t& keybase,
                                                  uint32_t& cnt) {
@@ -634,7 +740,13 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
                     run += (uint32_t)__popcll(b);
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-                run_chain_packed(D, run, lane, order2 + base, mask_lo, mask_hi, wgt, assign, keybase, mycnt);
+                const uint64_t ssds = __ballot(lane < D && L.comp_of[lane] == c);         // the component's SSDs
+                if (D <= 32 && __popcll(ssds) <= 2 && ssds != 0ull) {
+                    const int sa = __ffsll((unsigned long long)ssds) - 1, sb = 63 - __clzll((unsigned long long)ssds);
+                    greedy_chain_pair(run, lane, order2 + base, mask_lo, wgt, assign, keybase, mycnt, sa, sb != sa ? sb : -1);
+                } else {
+                    run_chain_packed(D, run, lane, order2 + base, mask_lo, mask_hi, wgt, assign, keybase, mycnt);
+                }
             }
             if (lane < D) {
                 const uint32_t c = L.comp_of[lane];

@@ -367,7 +367,10 @@ def test_map_variable_replication_and_heavy_weights(sw):
         run_map(sw, sel, H, N, e2c, Nc, rep, D, weight)
 
 
-@pytest.mark.parametrize("D,F,Nc,S", [(8, 2, 500, 3000), (12, 3, 700, 4000), (40, 5, 900, 6000), (64, 8, 1200, 8000), (8, 8, 300, 2000)])
+@pytest.mark.parametrize("D,F,Nc,S", [(8, 2, 500, 3000), (12, 3, 700, 4000), (40, 5, 900, 6000), (64, 8, 1200, 8000), (8, 8, 300, 2000),
+                                      # families of two SSDs (the scalar chain of a replica pair), with single-copy clusters among them:
+                                      # long and short lists, more pairs than waves, equal weights (ties go to the lower SSD)
+                                      (8, 4, 500, 3000), (8, 4, 400, 1500), (32, 16, 900, 6000), (6, 3, 200, 1000)])
 def test_map_independent_ssd_families_run_side_by_side(sw, D, F, Nc, S):
     """Many merged clusters whose replica sets fall into F families of SSDs that share nothing: the device runs one
     chain per family side by side (more families than waves included), and the queues are still the sequential
