@@ -401,7 +401,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     uint32_t flags = 0;
 
     const int32_t* e2c = a.e2c + (size_t)h * a.N;
-    constexpr int SEL_REGS = 4;
+    constexpr int SEL_REGS = BIG ? 8 : 4;           // long lists: 8192 merged picks on 1024 threads are one burst of loads, not two round trips
     int32_t my_sel[SEL_REGS];
     if (!PRESTAGED) {
         // burst of independent loads: the selection into registers, the tables into LDS
