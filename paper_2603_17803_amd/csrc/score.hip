@@ -356,9 +356,9 @@ __global__ __launch_bounds__(256) void score_batched_kernel(const u32x4* __restr
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) a[s] = arow[s];      // cached loads: a 128-byte line serves eight consecutive k-steps of a lane
 
-    f32x16 acc;
+    f32x16 acc, acc1;                                      // two chains of dependent MFMAs: the wave is alone on its SIMD
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int r = 0; r < 16; ++r) { acc[r] = 0.f; acc1[r] = 0.f; }
 
     for (int g0 = 0; g0 < G; g0 += SB_GT) {
         const int gn = min(SB_GT, G - g0);
@@ -368,13 +368,30 @@ __global__ __launch_bounds__(256) void score_batched_kernel(const u32x4* __restr
         }
         park(gn, qv);
         __syncthreads();
-        for (int g = 0; g < gn; ++g) {
+        // The weight fragments of query head g + 1 are read from LDS while head g's MFMAs run (two register sets): read
+        // one k-step ahead, every pair of MFMAs waited for an LDS round trip of its own, 64 of them per wave.  What is left
+        // of this phase is LDS bandwidth: every wave reads all of the tile's weights (1 KiB per MFMA and SIMD).
+        u32x4 wb[2][KSTEPS];
+        auto read_frags = [&](int set, int g) __attribute__((always_inline)) {
             const u32x4* wf = wt + ((size_t)(g * NVER + (PAGE ? hf : 0)) * 32 + r32) * WROW + (PAGE ? 0 : hf * KSTEPS);
 #pragma unroll
-            for (int s = 0; s < KSTEPS; ++s)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[s]), __builtin_bit_cast(bf16x8, wf[s]), acc, 0, 0, 0);
+            for (int s = 0; s < KSTEPS; ++s) wb[set][s] = wf[s];
+        };
+        read_frags(0, 0);
+#pragma unroll
+        for (int g = 0; g < SB_GT; ++g) {
+            if (g < gn) {
+                if (g + 1 < SB_GT && g + 1 < gn) read_frags((g + 1) & 1, g + 1);
+#pragma unroll
+                for (int s = 0; s < KSTEPS; s += 2) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[s]), __builtin_bit_cast(bf16x8, wb[g & 1][s]), acc, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[s + 1]), __builtin_bit_cast(bf16x8, wb[g & 1][s + 1]), acc1, 0, 0, 0);
+                }
+            }
         }
     }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] += acc1[r];
     // result tile: lane l, register r -> stream b0 + l%32, entry n0 + 8*(r/4) + 4*(l/32) + r%4
     const int b = b0 + r32;
     if (b < B) {
