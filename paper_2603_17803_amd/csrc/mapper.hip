@@ -338,11 +338,11 @@ __device__ __forceinline__ void stage_words(int32_t* __restrict__ dst, const int
 }
 
 // LDS layout shared by the stand-alone and the fused kernel.
-constexpr int MAP_AUX_WORDS = 8 * 64;        // off, adj_lo, adj_hi, comp_of, seg_off, seg_cnt, pub_load, pub_cnt: 64 words each
+constexpr int MAP_AUX_WORDS = 8 * 64;        // off, adj_lo, adj_hi, comp_of, seg_first, seg_cnt, pub_load, pub_cnt: 64 words each
 
 struct MapLds {
     uint32_t *bitmap, *list, *mask_lo, *mask_hi, *wgt, *order, *assign, *order2, *comp_item, *off;
-    uint32_t *adj_lo, *adj_hi, *comp_of, *seg_off, *seg_cnt, *pub_load, *pub_cnt;
+    uint32_t *adj_lo, *adj_hi, *comp_of, *seg_first, *seg_cnt, *pub_load, *pub_cnt;
     int32_t *s_e2c, *s_rep, *s_wgt;
     int nwords;
     __device__ __forceinline__ MapLds(uint32_t* smem, const MapArgs& a, int stage_e2c, int stage_tab) {
@@ -360,8 +360,8 @@ struct MapLds {
         adj_lo = off + 64;
         adj_hi = adj_lo + 64;
         comp_of = adj_hi + 64;
-        seg_off = comp_of + 64;
-        seg_cnt = seg_off + 64;
+        seg_first = comp_of + 64;          // routed items by their lowest candidate SSD
+        seg_cnt = seg_first + 64;
         pub_load = seg_cnt + 64;
         pub_cnt = pub_load + 64;
         s_e2c = reinterpret_cast<int32_t*>(smem + ((off + MAP_AUX_WORDS - smem + 3) & ~3));   // N words when staged (16-byte aligned)
@@ -549,6 +549,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         L.adj_lo[lane] = 0u;
         L.adj_hi[lane] = 0u;
         L.seg_cnt[lane] = 0u;
+        L.seg_first[lane] = 0u;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
     }   // wave 0
@@ -606,6 +607,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         for (uint32_t i = tid; i < mm; i += NT) {
             uint64_t bits = stage_tab ? item(i, std::true_type{}) : item(i, std::false_type{});
             const uint32_t lo = (uint32_t)bits, hi = (uint32_t)(bits >> 32);
+            if (bits) atomicAdd(&L.seg_first[__ffsll((unsigned long long)bits) - 1], 1u);
             while (bits) {
                 const int d = __ffsll((unsigned long long)bits) - 1;
                 bits &= bits - 1;
@@ -634,7 +636,9 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 
     // visiting order: stable by replication factor (identity when all factors agree)
-    if (__builtin_expect(m > 0 && rf_min == rf_max, 1)) {
+    const bool identity = m > 0 && rf_min == rf_max;
+    if (lane == 0) off[5] = identity ? 1u : 0u;
+    if (__builtin_expect(identity, 1)) {
         for (uint32_t i = lane; i < m; i += 64) order[i] = i;
     } else if (m > 0) {
         uint32_t* rfv = assign;                      // assign is rewritten below, before the chain runs
@@ -666,10 +670,12 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
             L.adj_lo[lane] = 0u;
             L.adj_hi[lane] = 0u;
             L.seg_cnt[lane] = 0u;
+            L.seg_first[lane] = 0u;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
             for (uint32_t i = lane; i < m; i += 64) {
                 const uint32_t lo = mask_lo[i], hi = mask_hi[i];
                 uint64_t bits = ((uint64_t)hi << 32) | lo;
+                if (bits) atomicAdd(&L.seg_first[__ffsll((unsigned long long)bits) - 1], 1u);
                 while (bits) {
                     const int d = __ffsll((unsigned long long)bits) - 1;
                     bits &= bits - 1;
@@ -689,7 +695,10 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         const int rep = active ? __ffsll((unsigned long long)reach) - 1 : 64;
         const uint64_t reps = __ballot(active && rep == lane);
         ncomp = (uint32_t)__popcll(reps);
-        L.comp_of[lane] = active ? (uint32_t)__popcll(reps & ((1ull << rep) - 1ull)) : 0xffu;
+        const uint32_t my_comp = active ? (uint32_t)__popcll(reps & ((1ull << rep) - 1ull)) : 0xffu;
+        L.comp_of[lane] = my_comp;
+        // an item belongs to the sub-problem of its lowest candidate SSD: the sub-problems' sizes from the per-SSD counts
+        if (active && L.seg_first[lane]) atomicAdd(&L.seg_cnt[my_comp], L.seg_first[lane]);
     }
     if (lane == 0) off[0] = ncomp;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
@@ -712,15 +721,8 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         __syncthreads();
         ncomp = off[0];
         if (ncomp > 1) {
-            // all threads: the component of every item, and the components' sizes
             const uint32_t mm = off[1];
-            for (uint32_t i = tid; i < mm; i += NT) {
-                const uint64_t mk = ((uint64_t)mask_hi[i] << 32) | mask_lo[i];
-                const uint32_t c = mk ? L.comp_of[__ffsll((unsigned long long)mk) - 1] : 0xffu;
-                L.comp_item[i] = c;
-                if (mk) atomicAdd(&L.seg_cnt[c], 1u);
-            }
-            __syncthreads();
+            const bool identity = off[5] != 0u;            // the visiting order is the list order: no look-up
             // component c on wave c mod (number of waves): the wave gathers the component's items in visiting
             // order (stable), then runs their chain; a wave that gets several components runs them one after the
             // other on the same registers (their SSDs are disjoint)
@@ -730,17 +732,19 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
             uint32_t keybase = (uint32_t)lane, mycnt = 0;
             for (uint32_t c = (uint32_t)wave; c < ncomp; c += NW) {
                 const uint32_t base = (uint32_t)__builtin_amdgcn_readlane((int)seg, (int)c);
+                const uint64_t ssds = __ballot(lane < D && L.comp_of[lane] == c);         // the component's SSDs
+                const uint32_t ssds_lo = (uint32_t)ssds, ssds_hi = (uint32_t)(ssds >> 32);
                 uint32_t run = 0;
                 for (uint32_t i0 = 0; i0 < mm; i0 += 64) {
                     const uint32_t i = i0 + lane;
-                    const uint32_t it = i < mm ? order[i] : 0u;
-                    const bool hit = i < mm && L.comp_item[it] == c;
+                    const uint32_t it = i < mm ? (identity ? i : order[i]) : 0u;
+                    // an item's candidates all lie in one sub-problem: any of them tells which
+                    const bool hit = i < mm && ((mask_lo[it] & ssds_lo) | (mask_hi[it] & ssds_hi)) != 0u;
                     const uint64_t b = __ballot(hit);
                     if (hit) order2[base + run + (uint32_t)__popcll(b & ((1ull << lane) - 1ull))] = it;
                     run += (uint32_t)__popcll(b);
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-                const uint64_t ssds = __ballot(lane < D && L.comp_of[lane] == c);         // the component's SSDs
                 if (D <= 32 && __popcll(ssds) <= 2 && ssds != 0ull) {
                     const int sa = __ffsll((unsigned long long)ssds) - 1, sb = 63 - __clzll((unsigned long long)ssds);
                     greedy_chain_pair(run, lane, order2 + base, mask_lo, wgt, assign, keybase, mycnt, sa, sb != sa ? sb : -1);
