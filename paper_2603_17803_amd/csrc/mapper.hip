@@ -31,6 +31,7 @@ struct MapArgs {
     int split_off;      // word offset of the 2 * cap words the split into independent sub-problems needs; 0 = no room, never split
     int piece;          // strided selections (the streams of a step, as the selection writes them): a group's S entries are
     int piece_stride;   // pieces of `piece` consecutive ids, `piece_stride` words apart; unused by the contiguous kernels
+    int piece_shift;    // log2(piece) when it is a power of two (a shift instead of a division per entry), -1 otherwise
 };
 
 // Chain over items [0, m) in visiting order.  keybase = (load << 6) | lane.  On return assign[i]
@@ -385,7 +386,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     // position of the group's s-th entry behind `sel`
     auto at = [&](int s0) __attribute__((always_inline)) {
         if (!STRIDED) return s0;
-        const int pc = s0 / a.piece;
+        const int pc = a.piece_shift >= 0 ? s0 >> a.piece_shift : s0 / a.piece;
         return pc * a.piece_stride + (s0 - pc * a.piece);
     };
     const MapLds L(smem, a, stage_e2c, stage_tab);
@@ -410,12 +411,32 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
             const int s0 = tid + r * NT;
             my_sel[r] = (s0 < a.S) ? sel[at(s0)] : -1;
         }
+        // Replica and weight tables of at most two resp. one 16-byte vector per thread travel through registers beside the
+        // entry->cluster table: staged one after the other, each table waited for a memory round trip of its own.
+        const int nrep = a.Nc * a.R;
+        const int32_t* rep_src = a.replicas + cbase * a.R;
+        const int32_t* wgt_src = a.weight ? a.weight + cbase : nullptr;
+        const bool rep_fast = stage_tab && (nrep & 3) == 0 && (nrep >> 2) <= 2 * NT && (reinterpret_cast<uintptr_t>(rep_src) & 15) == 0;
+        const bool wgt_fast = stage_tab && wgt_src && (a.Nc & 3) == 0 && (a.Nc >> 2) <= NT && (reinterpret_cast<uintptr_t>(wgt_src) & 15) == 0;
+        int4 v_rep[2] = {make_int4(0, 0, 0, 0), make_int4(0, 0, 0, 0)}, v_wgt = make_int4(0, 0, 0, 0);
+        if (rep_fast) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                if (tid + u * NT < (nrep >> 2)) v_rep[u] = reinterpret_cast<const int4*>(rep_src)[tid + u * NT];
+        }
+        if (wgt_fast && tid < (a.Nc >> 2)) v_wgt = reinterpret_cast<const int4*>(wgt_src)[tid];
         if (stage_tab) {
-            stage_words<NT>(s_rep, a.replicas + cbase * a.R, a.Nc * a.R, tid);
-            if (a.weight) stage_words<NT>(s_wgt, a.weight + cbase, a.Nc, tid);
-            else for (int i = tid; i < a.Nc; i += NT) s_wgt[i] = 1;
+            if (!rep_fast) stage_words<NT>(s_rep, rep_src, nrep, tid);
+            if (!wgt_src) { for (int i = tid; i < a.Nc; i += NT) s_wgt[i] = 1; }
+            else if (!wgt_fast) stage_words<NT>(s_wgt, wgt_src, a.Nc, tid);
         }
         if (stage_e2c) stage_words<NT>(s_e2c, e2c, a.N, tid);
+        if (rep_fast) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                if (tid + u * NT < (nrep >> 2)) reinterpret_cast<int4*>(s_rep)[tid + u * NT] = v_rep[u];
+        }
+        if (wgt_fast && tid < (a.Nc >> 2)) reinterpret_cast<int4*>(s_wgt)[tid] = v_wgt;
         for (int w = tid; w < nwords; w += NT) bitmap[w] = 0;
         __syncthreads();
     }
@@ -762,33 +783,47 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         }
         __syncthreads();
     }
-    if (wave != 0) {                                 // emission is single-wave work
+    // Bucket offsets are single-wave work; the scatter of the queues is per-item work, which the long-list kernels
+    // leave to all their waves when those are still here (they are after a split into sub-problems).
+    const bool all_emit = BIG && try_split;
+    if (wave != 0 && !all_emit) {
         if (flags) atomicOr(a.dev_flags, flags);
         return;
     }
-    if (ncomp > 1) {
-        const bool active = lane < D && L.comp_of[lane] != 0xffu;
-        load = active ? L.pub_load[lane] : 0u;
-        cnt = active ? L.pub_cnt[lane] : 0u;
+    uint32_t total = 0;
+    if (wave == 0) {
+        if (ncomp > 1) {
+            const bool active = lane < D && L.comp_of[lane] != 0xffu;
+            load = active ? L.pub_load[lane] : 0u;
+            cnt = active ? L.pub_cnt[lane] : 0u;
+        }
+        // buckets SSD-major, insertion order inside a bucket
+        const uint32_t my_off = wave_excl_scan(lane < D ? cnt : 0u, &total);
+        off[lane] = my_off;
+        int32_t* q_off = a.q_off + g * (D + 1);
+        if (lane < D) {
+            q_off[lane] = (int32_t)my_off;
+            a.q_load[g * D + lane] = (int32_t)load;
+        }
+        if (lane == 0) {
+            q_off[D] = (int32_t)total;
+            if (all_emit) { L.seg_cnt[0] = total; L.seg_cnt[1] = m; }      // the sub-problems' sizes have been read
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
     }
-
-    // emit buckets SSD-major, insertion order inside a bucket
-    uint32_t total;
-    const uint32_t my_off = wave_excl_scan(lane < D ? cnt : 0u, &total);
-    off[lane] = my_off;
-    int32_t* q_off = a.q_off + g * (D + 1);
-    if (lane < D) {
-        q_off[lane] = (int32_t)my_off;
-        a.q_load[g * D + lane] = (int32_t)load;
+    uint32_t m_emit = m;
+    if (all_emit) {
+        __syncthreads();
+        total = L.seg_cnt[0];
+        m_emit = L.seg_cnt[1];
     }
-    if (lane == 0) q_off[D] = (int32_t)total;
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    const uint32_t first = all_emit ? (uint32_t)tid : (uint32_t)lane, step = all_emit ? (uint32_t)NT : 64u;
     int32_t* qc = a.q_cluster + g * a.cap;
-    for (uint32_t i = lane; i < m; i += 64) {
+    for (uint32_t i = first; i < m_emit; i += step) {
         const uint32_t as = assign[i];
         if (as != INF32) qc[off[as >> 24] + (as & 0xffffffu)] = (int32_t)list[i];
     }
-    for (uint32_t p = total + lane; p < (uint32_t)a.cap; p += 64) qc[p] = -1;
+    for (uint32_t p = total + first; p < (uint32_t)a.cap; p += step) qc[p] = -1;
 
     if (flags) atomicOr(a.dev_flags, flags);
 }
@@ -880,7 +915,8 @@ size_t map_lds_base_bytes(int Nc, int cap) { return ((size_t)(Nc + 31) / 32 + (s
 swarm_status launch_map(swarm_ctx* ctx, const int32_t* sel, int64_t groups, int S, int H, int N, const int32_t* e2c,
                         int Nc, const int32_t* replicas, int R, int D, const int32_t* weight,
                         const uint32_t* resident, int32_t* q_off, int32_t* q_cluster, int32_t* q_load, int cap, int piece) {
-    MapArgs a{sel, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0, piece, H * piece};
+    MapArgs a{sel, S, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0, piece, H * piece,
+              (piece > 0 && (piece & (piece - 1)) == 0) ? __builtin_ctz((unsigned)piece) : -1};
     size_t lds = map_lds_base_bytes(Nc, cap);
     const size_t budget = 64u * 1024u;
     int stage_tab = 0, stage_e2c = 0;
@@ -914,7 +950,7 @@ swarm_status launch_select_map(swarm_ctx* ctx, const float* scores, int H, int N
     // short rows select with smaller blocks, four scores per thread (see launch_select)
     const int NT = sliced ? selcore::NT : N <= 4 * 256 ? 256 : N <= 4 * 512 ? 512 : selcore::NT;
     if (N > 64 * NT && !sliced) return SWARM_OK;
-    MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0, 0, 0};
+    MapArgs a{nullptr, k, H, N, e2c, Nc, replicas, R, D, weight, resident, q_off, q_cluster, q_load, cap, ctx->dev_flags, 0, 0, 0, -1};
     size_t lds = map_lds_base_bytes(Nc, cap);
     const size_t budget = 64u * 1024u;                     // dynamic part; the selection's static 12.6 KiB come on top
     lds = (lds + 15) / 16 * 16;
