@@ -545,12 +545,29 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     }
     uint32_t m = 0, load = 0, cnt = 0, wsum = 0;
     const int D = a.D;
+    // Long lists: every thread places the cluster of its own bitmap bit (the words' popcounts are scanned by every wave
+    // for itself: lane j = word j), instead of wave 0 walking the bitmap alone.
+    const bool par_compact = BIG && try_split && nwords <= 64;
+    uint32_t m_par = 0;
+    if (par_compact) {
+        const uint32_t wexcl = wave_excl_scan(lane < nwords ? (uint32_t)__popc(bitmap[lane]) : 0u, &m_par);
+        for (int b0 = 0; b0 < nwords * 32; b0 += NT) {
+            const int bit = b0 + tid, w = bit >> 5;
+            const uint32_t word = w < nwords ? bitmap[w] : 0u;
+            const uint32_t before = (uint32_t)__shfl((int)wexcl, w & 63, 64);
+            if ((word >> (bit & 31)) & 1u) {
+                const uint32_t pos = before + (uint32_t)__popc(word & ((1u << (bit & 31)) - 1u));
+                if (pos < (uint32_t)a.cap) list[pos] = (uint32_t)bit;
+            }
+        }
+    }
     if (wave == 0) {
     // compaction in ascending cluster id; a lane takes a slice of 8, 16 or 32 bits, the narrowest that still puts
     // the whole bitmap on the 64 lanes at once, so that a densely set, short bitmap is not walked by a few lanes
     const int pw_shift = nwords <= 16 ? 2 : nwords <= 32 ? 1 : 0;     // log2 of the slices per word
     const int sbits = 32 >> pw_shift, nslices = nwords << pw_shift;   // slice width: 8, 16 or 32 bits
-    for (int s0 = 0; s0 < nslices; s0 += 64) {
+    m = m_par;
+    for (int s0 = 0; s0 < (par_compact ? 0 : nslices); s0 += 64) {
         const int sl = s0 + lane;
         const int w = sl >> pw_shift, sh = (sl & ((1 << pw_shift) - 1)) * sbits;
         uint32_t bits = (sl < nslices) ? ((bitmap[w] >> sh) & (sbits == 32 ? 0xffffffffu : (1u << sbits) - 1u)) : 0u;
@@ -660,7 +677,8 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     const bool identity = m > 0 && rf_min == rf_max;
     if (lane == 0) off[5] = identity ? 1u : 0u;
     if (__builtin_expect(identity, 1)) {
-        for (uint32_t i = lane; i < m; i += 64) order[i] = i;
+        // a split into sub-problems reads the list order without a look-up: the table is written only if there is none
+        if (!try_split) { for (uint32_t i = lane; i < m; i += 64) order[i] = i; }
     } else if (m > 0) {
         uint32_t* rfv = assign;                      // assign is rewritten below, before the chain runs
         for (uint32_t i = lane; i < m; i += 64) rfv[i] = order[i];
@@ -722,6 +740,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         if (active && L.seg_first[lane]) atomicAdd(&L.seg_cnt[my_comp], L.seg_first[lane]);
     }
     if (lane == 0) off[0] = ncomp;
+    if (identity && try_split && ncomp <= 1) { for (uint32_t i = lane; i < m; i += 64) order[i] = i; }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
     if (ncomp <= 1) {
         // greedy least-loaded assignment, one chain
@@ -756,14 +775,27 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
                 const uint64_t ssds = __ballot(lane < D && L.comp_of[lane] == c);         // the component's SSDs
                 const uint32_t ssds_lo = (uint32_t)ssds, ssds_hi = (uint32_t)(ssds >> 32);
                 uint32_t run = 0;
-                for (uint32_t i0 = 0; i0 < mm; i0 += 64) {
-                    const uint32_t i = i0 + lane;
-                    const uint32_t it = i < mm ? (identity ? i : order[i]) : 0u;
-                    // an item's candidates all lie in one sub-problem: any of them tells which
-                    const bool hit = i < mm && ((mask_lo[it] & ssds_lo) | (mask_hi[it] & ssds_hi)) != 0u;
-                    const uint64_t b = __ballot(hit);
-                    if (hit) order2[base + run + (uint32_t)__popcll(b & ((1ull << lane) - 1ull))] = it;
-                    run += (uint32_t)__popcll(b);
+                for (uint32_t i0 = 0; i0 < mm; i0 += 256) {          // four batches of look-ups in flight together
+                    uint32_t it[4], ml[4], mh[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const uint32_t i = i0 + u * 64 + lane;
+                        it[u] = i < mm ? (identity ? i : order[i]) : 0u;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const bool in = i0 + u * 64 + lane < mm;
+                        ml[u] = in ? mask_lo[it[u]] : 0u;
+                        mh[u] = (in && D > 32) ? mask_hi[it[u]] : 0u;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        // an item's candidates all lie in one sub-problem: any of them tells which
+                        const bool hit = ((ml[u] & ssds_lo) | (mh[u] & ssds_hi)) != 0u;
+                        const uint64_t b = __ballot(hit);
+                        if (hit) order2[base + run + (uint32_t)__popcll(b & ((1ull << lane) - 1ull))] = it[u];
+                        run += (uint32_t)__popcll(b);
+                    }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
                 if (D <= 32 && __popcll(ssds) <= 2 && ssds != 0ull) {
