@@ -50,13 +50,13 @@ struct MapArgs {
 template <int STEPS>
 __device__ __forceinline__ void greedy_chain_packed(uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
                                                     const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign,
-                                                    uint32_t& keybase, uint32_t& cnt, int D) {
+                                                    uint32_t& keybase, uint32_t& cnt, int D, bool identity = false) {
     const uint32_t lane5 = (uint32_t)lane & 31u;
     for (uint32_t base = 0; base < m; base += 32) {
         const uint32_t n = min(32u, m - base);
         uint32_t it = 0, mlo = 0, mhi = 0, w6 = 0;
         if ((uint32_t)lane < n) {
-            it = order[base + lane];
+            it = identity ? base + (uint32_t)lane : order[base + lane];     // identity: the visiting order is the list order, no look-up
             mlo = mask_lo[it];
             mhi = mask_hi[it];
             w6 = (wgt[it] << 6) & (0u - (uint32_t)((mlo | mhi) != 0u));   // an unroutable item adds no load (read with the masks, not after them)
@@ -162,9 +162,9 @@ __device__ __forceinline__ void greedy_chain_packed(uint32_t m, int lane, const 
 template <int STEPS>
 __device__ __forceinline__ void greedy_chain_wide(uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
                                                   const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign,
-                                                  uint32_t& load, uint32_t& cnt) {
+                                                  uint32_t& load, uint32_t& cnt, bool identity = false) {
     for (uint32_t it = 0; it < m; ++it) {
-        const uint32_t i = order[it];
+        const uint32_t i = identity ? it : order[it];
         const uint64_t mask = ((uint64_t)mask_hi[i] << 32) | mask_lo[i];
         if (mask == 0) { if (lane == 0) assign[i] = INF32; continue; }
         const bool cand = (mask >> lane) & 1ull;
@@ -288,11 +288,11 @@ __device__ __forceinline__ void greedy_chain_pair(uint32_t m, int lane, const ui
 
 __device__ __forceinline__ void run_chain_packed(int D, uint32_t m, int lane, const uint32_t* order, const uint32_t* mask_lo,
                                                  const uint32_t* mask_hi, const uint32_t* wgt, uint32_t* assign, uint32_t& keybase,
-                                                 uint32_t& cnt) {
-    if (D <= 4) greedy_chain_packed<2>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
-    else if (D <= 8) greedy_chain_packed<3>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
-    else if (D <= 16) greedy_chain_packed<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
-    else greedy_chain_packed<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D);
+                                                 uint32_t& cnt, bool identity = false) {
+    if (D <= 4) greedy_chain_packed<2>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D, identity);
+    else if (D <= 8) greedy_chain_packed<3>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D, identity);
+    else if (D <= 16) greedy_chain_packed<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D, identity);
+    else greedy_chain_packed<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, D, identity);
 }
 
 constexpr int MAP_THREADS = 256;
@@ -677,8 +677,7 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
     const bool identity = m > 0 && rf_min == rf_max;
     if (lane == 0) off[5] = identity ? 1u : 0u;
     if (__builtin_expect(identity, 1)) {
-        // a split into sub-problems reads the list order without a look-up: the table is written only if there is none
-        if (!try_split) { for (uint32_t i = lane; i < m; i += 64) order[i] = i; }
+        // the list order is the visiting order: the chains and the split read it without a look-up, the table stays unwritten
     } else if (m > 0) {
         uint32_t* rfv = assign;                      // assign is rewritten below, before the chain runs
         for (uint32_t i = lane; i < m; i += 64) rfv[i] = order[i];
@@ -740,17 +739,16 @@ __device__ __forceinline__ void map_group(const MapArgs& a, int64_t g, const int
         if (active && L.seg_first[lane]) atomicAdd(&L.seg_cnt[my_comp], L.seg_first[lane]);
     }
     if (lane == 0) off[0] = ncomp;
-    if (identity && try_split && ncomp <= 1) { for (uint32_t i = lane; i < m; i += 64) order[i] = i; }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
     if (ncomp <= 1) {
         // greedy least-loaded assignment, one chain
         if (__builtin_expect(wsum < (1u << 26), 1)) {
             uint32_t keybase = (uint32_t)lane;
-            run_chain_packed(D, m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt);
+            run_chain_packed(D, m, lane, order, mask_lo, mask_hi, wgt, assign, keybase, cnt, identity);
             load = keybase >> 6;
         } else {
-            if (D <= 16) greedy_chain_wide<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
-            else greedy_chain_wide<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt);
+            if (D <= 16) greedy_chain_wide<4>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt, identity);
+            else greedy_chain_wide<6>(m, lane, order, mask_lo, mask_hi, wgt, assign, load, cnt, identity);
         }
     }
     if (lane == 0) off[1] = m;
